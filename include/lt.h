@@ -1,0 +1,181 @@
+/*
+ * lt.h -- C ABI of the LightTransfer hot path for one AMD MI355X (gfx950).
+ *
+ * What the library computes (LightTransfer, arXiv 2410.13846):
+ *   - lt_lazy_ratio   the lazy ratio r_i of a layer (Section "LightTransfer-Test", Eq. 1)
+ *   - lt_select_lazy  which layers become lazy: the ones a max-priority queue of capacity P
+ *                     would pop, i.e. the L - P largest ratios (same section; Figure 3)
+ *   - lt_append_kv    KV cache of a hybrid stack: full layers keep every token, lazy layers keep
+ *                     only the initial and the most recent tokens (same section, last paragraph)
+ *   - lt_decode_attn  one decoding step of attention per layer (Section "Preliminary", decoding
+ *                     stage): softmax(q K^T + M) V with M the causal mask in a full layer and the
+ *                     sink mask (first w_sink, last w_recent positions) in a lazy layer
+ *                     (Appendix "Theoretical Analysis")
+ *
+ * Conventions for every call
+ *   Pointers marked "device" are HIP device addresses on the current device; "host" are ordinary
+ *   host addresses.  The caller owns ALL device memory (KV slab, workspaces, inputs, outputs) and
+ *   the stream; the library never allocates or frees device memory.  Device work is enqueued on
+ *   `stream` (a hipStream_t passed as void*; NULL is the default stream) and the call returns
+ *   without waiting for it.  Token counts live on the host, so no call synchronises.
+ *   bf16 tensors are raw 16-bit patterns, dense and row-major in the stated shape unless strides
+ *   are given; fp32 outputs are dense.  head_dim must be 128.  All sequences of a batch have the
+ *   same length in a layer.
+ *   Errors: every call validates its arguments before enqueuing anything and returns a status;
+ *   on any status other than LT_OK no device work was enqueued and no state changed.  There are
+ *   no exceptions, no aborts and no global state; different lt_ctx objects are independent.  One
+ *   lt_ctx must not be used from two threads at once.
+ */
+#ifndef LT_H
+#define LT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct lt_ctx lt_ctx; /* opaque, host memory owned by the library */
+
+typedef enum {
+    LT_OK = 0,
+    LT_ERR_INVALID_ARG = 1, /* NULL pointer, negative size, unknown enum value, NaN ratio */
+    LT_ERR_SHAPE = 2,       /* sizes that do not fit together (heads, head_dim, w_last > n, ...) */
+    LT_ERR_CAPACITY = 3,    /* a full layer would exceed max_tokens, or a buffer is too small */
+    LT_ERR_STATE = 4,       /* call out of order (decode on an empty layer, ...) */
+    LT_ERR_HIP = 5,         /* the HIP runtime refused a launch or an event call */
+    LT_ERR_NOMEM = 6        /* host allocation failed */
+} lt_status;
+
+/* Which keys count as X_recent in the lazy ratio.  Eq. 1 together with the per-row kept sets of
+ * the appendix gives each query its own window ending at that query (PER_QUERY, the default and
+ * exactly the mass streaming attention keeps); Table 1 slices the last w_recent prompt keys once
+ * for all queries (FIXED).  Both apply the causal mask. */
+typedef enum { LT_RECENT_PER_QUERY = 0, LT_RECENT_FIXED = 1 } lt_ratio_mode;
+
+typedef struct lt_config {
+    int32_t n_layers;     /* L */
+    int32_t batch;        /* B, sequences decoded together */
+    int32_t n_q_heads;    /* Hq */
+    int32_t n_kv_heads;   /* Hkv, divides Hq; query head h reads KV head h / (Hq/Hkv); Hq/Hkv <= 8 */
+    int32_t head_dim;     /* 128 */
+    int32_t w_sink;       /* initial tokens a lazy layer keeps (Appendix A: 4) */
+    int32_t w_recent;     /* most recent tokens a lazy layer keeps, current token included (1020) */
+    int64_t max_tokens;   /* capacity of a full layer's cache, in tokens per sequence */
+    float softmax_scale;  /* multiplies q.k before the softmax; 0 selects 1/sqrt(head_dim) */
+} lt_config;
+
+/* ---- KV-cache manager -------------------------------------------------------------------- */
+
+/* Bytes of device memory the KV slab needs for this configuration and lazy mask: per layer one K
+ * and one V block of bf16 [B][Hkv][cap][128], cap = max_tokens (full layer) or w_sink + w_recent
+ * (lazy layer), each block aligned to 256 bytes.  Returns 0 on invalid arguments.
+ * is_lazy: host, L entries, non-zero = lazy. */
+size_t lt_kv_bytes(const lt_config *cfg, const uint8_t *is_lazy);
+
+/* Bytes of device workspace lt_decode_attn needs (partial results of the split over the key
+ * axis; fp32).  Returns 0 on invalid arguments. */
+size_t lt_workspace_bytes(const lt_config *cfg);
+
+/* Create the host-side state of a hybrid stack over caller-owned device memory.
+ * kv_slab (device, >= lt_kv_bytes, 256-byte aligned) and workspace (device, >= lt_workspace_bytes,
+ * 256-byte aligned) stay owned by the caller and must outlive the context.  Nothing is enqueued:
+ * cache contents are undefined until appended.  *out receives the context. */
+lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab, size_t kv_bytes,
+                    void *workspace, size_t ws_bytes, lt_ctx **out);
+
+/* Free the host-side state.  Device memory is untouched.  NULL is allowed. */
+void lt_destroy(lt_ctx *ctx);
+
+/* Forget every token of every layer (host counters only). */
+lt_status lt_reset(lt_ctx *ctx);
+
+/* Tokens appended to a layer so far (total) and entries its cache holds (stored:
+ * total for a full layer, min(total, w_sink + w_recent) for a lazy one).  Either output may be NULL. */
+lt_status lt_layer_len(const lt_ctx *ctx, int32_t layer, int64_t *total_tokens, int64_t *stored_tokens);
+
+/* Where a layer's cache lives inside the slab: device addresses of its K and V blocks, strides in
+ * bf16 elements between sequences and between KV heads (token stride is 128), capacity in tokens,
+ * and whether it is lazy.  Any output may be NULL.  In a lazy layer the token at absolute position
+ * p sits in slot p when p < w_sink and in slot w_sink + (p - w_sink) mod w_recent otherwise. */
+lt_status lt_layer_view(const lt_ctx *ctx, int32_t layer, void **k_dev, void **v_dev,
+                        int64_t *stride_b, int64_t *stride_h, int64_t *capacity, int32_t *is_lazy);
+
+/* ---- lazy-layer identification ------------------------------------------------------------ */
+
+/* Bytes of device workspace lt_lazy_ratio needs for a prompt of n tokens scored over its last
+ * w_last queries.  Returns 0 on invalid arguments. */
+size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last);
+
+/* Lazy ratio of one layer (Eq. 1): for each of the last w_last prompt positions p = n-w_last..n-1
+ * and each query head, the share rho of the causal softmax row of that query (keys 0..p, logits
+ * softmax_scale * q.k) that falls on the first w_sink keys and on the recent keys
+ * (PER_QUERY: p-w_recent+1..p; FIXED: n-w_recent..n-1, up to p); the union is a set.
+ *   q_last        device, bf16 [B][Hq][w_last][128], queries of positions n-w_last..n-1
+ *   k             device, bf16, key of (sequence b, KV head g, position j) at element offset
+ *                 b*k_stride_b + g*k_stride_h + j*k_stride_t; the 128 dims are contiguous and
+ *                 every stride is a multiple of 8 elements (may point into the KV slab)
+ *   n, w_last     prompt length and number of scored queries, 1 <= w_last <= min(n, 64)
+ *   workspace     device, >= lt_lazy_ratio_workspace_bytes(cfg, n, w_last), 256-byte aligned
+ *   rho_dev       device, fp32 [B][Hq][w_last], may be NULL
+ *   ratio_seq_dev device, fp32 [B]: mean of rho over heads and queries of each sequence, may be NULL
+ *   ratio_mean_dev device, fp32 [1]: mean of ratio_seq over the batch (the layer's r_i)
+ * Uses cfg->batch, head counts, head_dim, w_sink, w_recent and softmax_scale. */
+lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b,
+                        int64_t k_stride_h, int64_t k_stride_t, int64_t n, int32_t w_last,
+                        lt_ratio_mode mode, void *workspace, size_t ws_bytes, float *rho_dev,
+                        float *ratio_seq_dev, float *ratio_mean_dev, void *stream);
+
+/* Choose the lazy layers (pure host code): the n_lazy layers with the largest ratios, ties going
+ * to the lower layer index; this is the set a max-priority queue of capacity L - n_lazy pops when
+ * layers are pushed in order.
+ *   ratios_host  host, fp32 [L]; a NaN is rejected with LT_ERR_INVALID_ARG
+ *   is_lazy_out  host, uint8 [L], 1 = lazy
+ *   order_out    host, int32 [L], layers from laziest to least lazy; may be NULL */
+lt_status lt_select_lazy(const float *ratios_host, int32_t n_layers, int32_t n_lazy, uint8_t *is_lazy_out,
+                         int32_t *order_out);
+
+/* ---- decoding ----------------------------------------------------------------------------- */
+
+/* Append n_new tokens (the same count for every sequence) to a layer.
+ *   k_new, v_new  device, bf16 [B][Hkv][n_new][128]
+ * Full layer: tokens go to positions total..total+n_new-1; LT_ERR_CAPACITY if that exceeds
+ * max_tokens.  Lazy layer: a token whose absolute position is neither among the first w_sink nor
+ * among the last w_recent after this call is dropped, every other token goes to its ring slot
+ * (see lt_layer_view), so a bulk append of a whole prompt leaves exactly the reduced cache. */
+lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new,
+                       void *stream);
+
+/* Attention of the newest token of every sequence over the layer's cache, to be called after the
+ * token's own K/V were appended (the causal mask keeps the diagonal).
+ *   q        device, bf16 [B][Hq][128]
+ *   out      device, fp32 [B][Hq][128]: sum_j softmax_j(softmax_scale * q.k_j) v_j over the stored entries
+ *   lse_out  device, fp32 [B][Hq]: natural-log of the softmax denominator; may be NULL
+ * LT_ERR_STATE if the layer is empty. */
+lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream);
+
+/* ---- tuning and measurement ---------------------------------------------------------------- */
+
+/* Keys one workgroup of the split decode kernel handles in full / lazy layers (multiples of 64);
+ * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
+lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
+
+enum { LT_KERNEL_DECODE_FULL = 0, LT_KERNEL_DECODE_LAZY = 1, LT_KERNEL_MERGE = 2, LT_KERNEL_APPEND = 3,
+       LT_KERNEL_COUNT = 4 };
+
+/* Bracket every later kernel launch of this context with a pair of HIP events on the launch
+ * stream (on != 0), or stop doing so (on == 0).  Enabling discards earlier measurements. */
+lt_status lt_profile_enable(lt_ctx *ctx, int32_t on);
+
+/* Wait for the recorded events and return, for one kernel kind, how many launches were measured
+ * and their summed duration in milliseconds.  Launches beyond the internal event pool (65536
+ * pairs) are not measured. */
+lt_status lt_profile_read(lt_ctx *ctx, int32_t kernel, int64_t *launches, double *total_ms);
+
+const char *lt_status_str(lt_status status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LT_H */

@@ -1,0 +1,448 @@
+// C-ABI layer of the LightTransfer hot path: argument validation, the KV-cache manager (slab
+// layout, per-layer token counts, ring geometry), lazy-layer selection on the host, and the
+// launch plumbing (split heuristics, optional event timing).  All arithmetic of the method runs
+// in the kernels behind lt_kernels.h; this file only decides shapes and addresses.
+#include "../../include/lt.h"
+#include "lt_kernels.h"
+
+#include <algorithm>
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+namespace {
+
+constexpr size_t kAlign = 256;
+constexpr int64_t kMaxTokens = (int64_t)1 << 30;        // per-sequence positions are 32-bit inside the decode kernel
+constexpr int kMinKeysFull = 256;                       // smallest split the decode workspace is sized for (full layers)
+constexpr int kMinKeysLazy = 64;                        // same, lazy layers
+constexpr int kMaxEventPairs = 65536;
+constexpr float kLog2e = 1.4426950408889634f;
+
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+bool config_ok(const lt_config *c)
+{
+    if (c == nullptr) return false;
+    if (c->n_layers <= 0 || c->batch <= 0 || c->n_q_heads <= 0 || c->n_kv_heads <= 0) return false;
+    if (c->w_sink < 0 || c->w_recent < 0) return false;
+    if (c->max_tokens <= 0 || c->max_tokens > kMaxTokens) return false;
+    if (!(c->softmax_scale >= 0.f) || std::isinf(c->softmax_scale)) return false;
+    return true;
+}
+
+lt_status config_shape(const lt_config *c)
+{
+    if (c->head_dim != ltk::kHeadDim) return LT_ERR_SHAPE;
+    if (c->n_q_heads % c->n_kv_heads != 0) return LT_ERR_SHAPE;
+    if (c->n_q_heads / c->n_kv_heads > ltk::kMaxGroup) return LT_ERR_SHAPE;
+    if (c->batch > 65535 || c->n_kv_heads > 65535 || c->n_q_heads > 65535) return LT_ERR_SHAPE;   // grid y/z limits
+    return LT_OK;
+}
+
+float effective_scale(const lt_config *c)
+{
+    return c->softmax_scale > 0.f ? c->softmax_scale : 1.0f / std::sqrt((float)c->head_dim);
+}
+
+int64_t window_of(const lt_config *c) { return (int64_t)c->w_sink + c->w_recent; }
+
+int64_t layer_capacity(const lt_config *c, bool lazy) { return lazy ? window_of(c) : c->max_tokens; }
+
+size_t block_bytes(const lt_config *c, bool lazy)
+{
+    return align_up((size_t)c->batch * c->n_kv_heads * (size_t)layer_capacity(c, lazy) * ltk::kHeadDim * sizeof(uint16_t));
+}
+
+int64_t max_splits(const lt_config *c)
+{
+    const int64_t full = ceil_div(c->max_tokens, kMinKeysFull);
+    const int64_t lazy = ceil_div(std::max<int64_t>(window_of(c), 1), kMinKeysLazy);
+    return std::max<int64_t>(std::max(full, lazy), 1);
+}
+
+struct Layer {
+    uint16_t *k = nullptr, *v = nullptr;
+    int64_t capacity = 0;
+    int64_t total = 0;
+    bool lazy = false;
+};
+
+struct EventPair {
+    hipEvent_t start, stop;
+    int32_t kernel;
+};
+
+}  // namespace
+
+struct lt_ctx {
+    lt_config cfg;
+    std::vector<Layer> layers;
+    float *part_acc = nullptr, *part_ml = nullptr;
+    int64_t splits_cap = 0;
+    int32_t keys_full = 0, keys_lazy = 0;      // 0 = heuristic
+    bool profiling = false;
+    std::vector<EventPair> events;             // pool, created on first enable
+    size_t events_used = 0;
+};
+
+namespace {
+
+// Keys per workgroup: enough workgroups to cover the chip several times, but not so small that
+// the partial results rival the KV bytes.  `streams` = B * Hkv independent key streams.
+int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t splits_cap)
+{
+    const int64_t target_blocks = 256 * 8;                         // 256 compute units, several workgroups each
+    int64_t keys = ceil_div(stored * streams, target_blocks);
+    keys = ceil_div(keys, ltk::kKeyGranule) * ltk::kKeyGranule;
+    const int64_t lo = lazy ? 128 : 256, hi = 2048;
+    keys = std::min(std::max(keys, lo), hi);
+    while (ceil_div(stored, keys) > splits_cap) keys += ltk::kKeyGranule;
+    return (int)keys;
+}
+
+struct ScopedEvents {
+    lt_ctx *ctx;
+    hipStream_t stream;
+    EventPair *pair = nullptr;
+    ScopedEvents(lt_ctx *c, hipStream_t s, int32_t kernel) : ctx(c), stream(s)
+    {
+        if (ctx->profiling && ctx->events_used < ctx->events.size()) {
+            pair = &ctx->events[ctx->events_used++];
+            pair->kernel = kernel;
+            (void)hipEventRecord(pair->start, stream);
+        }
+    }
+    ~ScopedEvents()
+    {
+        if (pair != nullptr) (void)hipEventRecord(pair->stop, stream);
+    }
+};
+
+}  // namespace
+
+extern "C" {
+
+const char *lt_status_str(lt_status s)
+{
+    switch (s) {
+    case LT_OK: return "ok";
+    case LT_ERR_INVALID_ARG: return "invalid argument";
+    case LT_ERR_SHAPE: return "shapes do not fit together";
+    case LT_ERR_CAPACITY: return "capacity exceeded";
+    case LT_ERR_STATE: return "call out of order";
+    case LT_ERR_HIP: return "HIP runtime error";
+    case LT_ERR_NOMEM: return "host allocation failed";
+    }
+    return "unknown status";
+}
+
+size_t lt_kv_bytes(const lt_config *cfg, const uint8_t *is_lazy)
+{
+    if (!config_ok(cfg) || config_shape(cfg) != LT_OK || is_lazy == nullptr) return 0;
+    size_t total = 0;
+    for (int i = 0; i < cfg->n_layers; ++i) total += 2 * block_bytes(cfg, is_lazy[i] != 0);
+    return total;
+}
+
+size_t lt_workspace_bytes(const lt_config *cfg)
+{
+    if (!config_ok(cfg) || config_shape(cfg) != LT_OK) return 0;
+    const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)max_splits(cfg);
+    return align_up(rows * ltk::kHeadDim * sizeof(float)) + align_up(rows * 2 * sizeof(float));
+}
+
+lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab, size_t kv_bytes, void *workspace,
+                    size_t ws_bytes, lt_ctx **out)
+{
+    if (out == nullptr) return LT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!config_ok(cfg) || is_lazy == nullptr || kv_slab == nullptr || workspace == nullptr) return LT_ERR_INVALID_ARG;
+    const lt_status shape = config_shape(cfg);
+    if (shape != LT_OK) return shape;
+    if (((uintptr_t)kv_slab % kAlign) != 0 || ((uintptr_t)workspace % kAlign) != 0) return LT_ERR_INVALID_ARG;
+    if (kv_bytes < lt_kv_bytes(cfg, is_lazy) || ws_bytes < lt_workspace_bytes(cfg)) return LT_ERR_CAPACITY;
+
+    lt_ctx *ctx = new (std::nothrow) lt_ctx();
+    if (ctx == nullptr) return LT_ERR_NOMEM;
+    ctx->cfg = *cfg;
+    ctx->cfg.softmax_scale = effective_scale(cfg);
+    try {
+        ctx->layers.resize(cfg->n_layers);
+    } catch (const std::bad_alloc &) {
+        delete ctx;
+        return LT_ERR_NOMEM;
+    }
+    uint8_t *cursor = static_cast<uint8_t *>(kv_slab);
+    for (int i = 0; i < cfg->n_layers; ++i) {
+        Layer &l = ctx->layers[i];
+        l.lazy = is_lazy[i] != 0;
+        l.capacity = layer_capacity(cfg, l.lazy);
+        const size_t bytes = block_bytes(cfg, l.lazy);
+        l.k = reinterpret_cast<uint16_t *>(cursor);
+        l.v = reinterpret_cast<uint16_t *>(cursor + bytes);
+        cursor += 2 * bytes;
+    }
+    ctx->splits_cap = max_splits(cfg);
+    const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)ctx->splits_cap;
+    ctx->part_acc = static_cast<float *>(workspace);
+    ctx->part_ml = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(rows * ltk::kHeadDim * sizeof(float)));
+    *out = ctx;
+    return LT_OK;
+}
+
+void lt_destroy(lt_ctx *ctx)
+{
+    if (ctx == nullptr) return;
+    for (EventPair &p : ctx->events) {
+        (void)hipEventDestroy(p.start);
+        (void)hipEventDestroy(p.stop);
+    }
+    delete ctx;
+}
+
+lt_status lt_reset(lt_ctx *ctx)
+{
+    if (ctx == nullptr) return LT_ERR_INVALID_ARG;
+    for (Layer &l : ctx->layers) l.total = 0;
+    return LT_OK;
+}
+
+lt_status lt_layer_len(const lt_ctx *ctx, int32_t layer, int64_t *total_tokens, int64_t *stored_tokens)
+{
+    if (ctx == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
+    const Layer &l = ctx->layers[layer];
+    if (total_tokens != nullptr) *total_tokens = l.total;
+    if (stored_tokens != nullptr) *stored_tokens = std::min(l.total, l.capacity);
+    return LT_OK;
+}
+
+lt_status lt_layer_view(const lt_ctx *ctx, int32_t layer, void **k_dev, void **v_dev, int64_t *stride_b, int64_t *stride_h,
+                        int64_t *capacity, int32_t *is_lazy)
+{
+    if (ctx == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
+    const Layer &l = ctx->layers[layer];
+    if (k_dev != nullptr) *k_dev = l.k;
+    if (v_dev != nullptr) *v_dev = l.v;
+    if (stride_h != nullptr) *stride_h = l.capacity * ltk::kHeadDim;
+    if (stride_b != nullptr) *stride_b = l.capacity * ltk::kHeadDim * ctx->cfg.n_kv_heads;
+    if (capacity != nullptr) *capacity = l.capacity;
+    if (is_lazy != nullptr) *is_lazy = l.lazy ? 1 : 0;
+    return LT_OK;
+}
+
+// ---- lazy-layer identification ---------------------------------------------------------------
+
+static int score_keys_per_block(const lt_config *cfg, int64_t n)
+{
+    // Enough workgroups to fill 256 compute units a few times; ranges are multiples of the LDS tile.
+    const int64_t streams = (int64_t)cfg->batch * cfg->n_kv_heads;
+    int64_t keys = ceil_div(n * streams, 256 * 4);
+    keys = ceil_div(keys, ltk::kScoreTileKeys) * ltk::kScoreTileKeys;
+    return (int)std::min<int64_t>(std::max<int64_t>(keys, 256), 4096);
+}
+
+size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last)
+{
+    if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n <= 0 || w_last <= 0 || w_last > 64) return 0;
+    const int64_t chunks = ceil_div(n, score_keys_per_block(cfg, n));
+    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * chunks) * 3 * sizeof(float);
+    return align_up(part) + align_up((size_t)cfg->batch * sizeof(float));
+}
+
+lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
+                        int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, void *workspace, size_t ws_bytes,
+                        float *rho_dev, float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
+{
+    if (!config_ok(cfg) || q_last == nullptr || k == nullptr || workspace == nullptr || ratio_mean_dev == nullptr)
+        return LT_ERR_INVALID_ARG;
+    if (mode != LT_RECENT_PER_QUERY && mode != LT_RECENT_FIXED) return LT_ERR_INVALID_ARG;
+    if (n <= 0 || w_last <= 0 || k_stride_b < 0 || k_stride_h < 0 || k_stride_t <= 0) return LT_ERR_INVALID_ARG;
+    const lt_status shape = config_shape(cfg);
+    if (shape != LT_OK) return shape;
+    if (w_last > n || w_last > 64 || n > kMaxTokens) return LT_ERR_SHAPE;
+    if (k_stride_t < ltk::kHeadDim || (k_stride_b % 8) != 0 || (k_stride_h % 8) != 0 || (k_stride_t % 8) != 0) return LT_ERR_SHAPE;
+    if (((uintptr_t)q_last % 16) != 0 || ((uintptr_t)k % 16) != 0 || ((uintptr_t)workspace % kAlign) != 0) return LT_ERR_INVALID_ARG;
+    if (ws_bytes < lt_lazy_ratio_workspace_bytes(cfg, n, w_last)) return LT_ERR_CAPACITY;
+
+    ltk::ScoreArgs a{};
+    a.q_last = static_cast<const uint16_t *>(q_last);
+    a.k = static_cast<const uint16_t *>(k);
+    a.k_stride_b = k_stride_b;
+    a.k_stride_h = k_stride_h;
+    a.k_stride_t = k_stride_t;
+    a.n = n;
+    a.w_last = w_last;
+    a.batch = cfg->batch;
+    a.n_q_heads = cfg->n_q_heads;
+    a.n_kv_heads = cfg->n_kv_heads;
+    a.w_sink = cfg->w_sink;
+    a.w_recent = cfg->w_recent;
+    a.fixed_mode = mode == LT_RECENT_FIXED ? 1 : 0;
+    a.keys_per_block = score_keys_per_block(cfg, n);
+    a.n_chunks = (int32_t)ceil_div(n, a.keys_per_block);
+    a.scale_log2e = effective_scale(cfg) * kLog2e;
+    a.part = static_cast<float *>(workspace);
+    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * a.n_chunks) * 3 * sizeof(float);
+    a.seq_scratch = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(part));
+    a.rho = rho_dev;
+    a.ratio_seq = ratio_seq_dev;
+    a.ratio_mean = ratio_mean_dev;
+    return ltk::lazy_ratio(a, static_cast<hipStream_t>(stream)) == hipSuccess ? LT_OK : LT_ERR_HIP;
+}
+
+lt_status lt_select_lazy(const float *ratios_host, int32_t n_layers, int32_t n_lazy, uint8_t *is_lazy_out, int32_t *order_out)
+{
+    if (ratios_host == nullptr || is_lazy_out == nullptr || n_layers <= 0 || n_lazy < 0 || n_lazy > n_layers)
+        return LT_ERR_INVALID_ARG;
+    for (int i = 0; i < n_layers; ++i)
+        if (std::isnan(ratios_host[i])) return LT_ERR_INVALID_ARG;
+    std::vector<int32_t> order;
+    try {
+        order.resize(n_layers);
+    } catch (const std::bad_alloc &) {
+        return LT_ERR_NOMEM;
+    }
+    for (int i = 0; i < n_layers; ++i) order[i] = i;
+    // laziest first; equal ratios keep layer order, so ties go to the lower index
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return ratios_host[x] > ratios_host[y]; });
+    std::memset(is_lazy_out, 0, (size_t)n_layers);
+    for (int i = 0; i < n_lazy; ++i) is_lazy_out[order[i]] = 1;
+    if (order_out != nullptr) std::memcpy(order_out, order.data(), (size_t)n_layers * sizeof(int32_t));
+    return LT_OK;
+}
+
+// ---- decoding ------------------------------------------------------------------------------------
+
+lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new, void *stream)
+{
+    if (ctx == nullptr || k_new == nullptr || v_new == nullptr || layer < 0 || layer >= ctx->cfg.n_layers || n_new <= 0)
+        return LT_ERR_INVALID_ARG;
+    if (((uintptr_t)k_new % 16) != 0 || ((uintptr_t)v_new % 16) != 0) return LT_ERR_INVALID_ARG;
+    Layer &l = ctx->layers[layer];
+    if (n_new > kMaxTokens || l.total + n_new > kMaxTokens) return LT_ERR_CAPACITY;
+    if (!l.lazy && l.total + n_new > l.capacity) return LT_ERR_CAPACITY;
+    if (l.capacity > 0) {                       // a lazy layer with an empty window stores nothing
+        ltk::AppendArgs a{};
+        a.k_new = static_cast<const uint16_t *>(k_new);
+        a.v_new = static_cast<const uint16_t *>(v_new);
+        a.k_cache = l.k;
+        a.v_cache = l.v;
+        a.stride_h = l.capacity * ltk::kHeadDim;
+        a.stride_b = a.stride_h * ctx->cfg.n_kv_heads;
+        a.n_new = n_new;
+        a.total_before = l.total;
+        a.batch = ctx->cfg.batch;
+        a.n_kv_heads = ctx->cfg.n_kv_heads;
+        a.is_lazy = l.lazy ? 1 : 0;
+        a.w_sink = ctx->cfg.w_sink;
+        a.w_recent = ctx->cfg.w_recent;
+        ScopedEvents ev(ctx, static_cast<hipStream_t>(stream), LT_KERNEL_APPEND);
+        if (ltk::append(a, static_cast<hipStream_t>(stream)) != hipSuccess) return LT_ERR_HIP;
+    }
+    l.total += n_new;
+    return LT_OK;
+}
+
+lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream)
+{
+    if (ctx == nullptr || q == nullptr || out == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
+    if (((uintptr_t)q % 16) != 0) return LT_ERR_INVALID_ARG;
+    const Layer &l = ctx->layers[layer];
+    const int64_t stored = std::min(l.total, l.capacity);
+    if (stored <= 0) return LT_ERR_STATE;
+    const lt_config &c = ctx->cfg;
+
+    ltk::DecodeArgs a{};
+    a.k_cache = l.k;
+    a.v_cache = l.v;
+    a.q = static_cast<const uint16_t *>(q);
+    a.part_acc = ctx->part_acc;
+    a.part_ml = ctx->part_ml;
+    a.out = out;
+    a.lse = lse_out;
+    a.stride_h = l.capacity * ltk::kHeadDim;
+    a.stride_b = a.stride_h * c.n_kv_heads;
+    a.batch = c.batch;
+    a.n_q_heads = c.n_q_heads;
+    a.n_kv_heads = c.n_kv_heads;
+    a.stored = (int32_t)stored;
+    const int32_t forced = l.lazy ? ctx->keys_lazy : ctx->keys_full;
+    a.keys_per_block = forced > 0 ? forced : choose_keys_per_block(stored, (int64_t)c.batch * c.n_kv_heads, l.lazy, ctx->splits_cap);
+    a.n_splits = (int32_t)ceil_div(stored, a.keys_per_block);
+    if (a.n_splits > ctx->splits_cap) return LT_ERR_CAPACITY;
+    a.scale_log2e = c.softmax_scale * kLog2e;
+    a.lazy_tag = l.lazy ? 1 : 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    {
+        ScopedEvents ev(ctx, s, l.lazy ? LT_KERNEL_DECODE_LAZY : LT_KERNEL_DECODE_FULL);
+        if (ltk::decode_partial(a, s) != hipSuccess) return LT_ERR_HIP;
+    }
+    {
+        ScopedEvents ev(ctx, s, LT_KERNEL_MERGE);
+        if (ltk::decode_merge(a, s) != hipSuccess) return LT_ERR_HIP;
+    }
+    return LT_OK;
+}
+
+// ---- tuning and measurement --------------------------------------------------------------------
+
+lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy)
+{
+    if (ctx == nullptr || keys_per_block_full < 0 || keys_per_block_lazy < 0) return LT_ERR_INVALID_ARG;
+    if (keys_per_block_full % ltk::kKeyGranule != 0 || keys_per_block_lazy % ltk::kKeyGranule != 0) return LT_ERR_INVALID_ARG;
+    if (keys_per_block_full > 0 && ceil_div(ctx->cfg.max_tokens, keys_per_block_full) > ctx->splits_cap) return LT_ERR_CAPACITY;
+    if (keys_per_block_lazy > 0 && ceil_div(std::max<int64_t>(window_of(&ctx->cfg), 1), keys_per_block_lazy) > ctx->splits_cap)
+        return LT_ERR_CAPACITY;
+    ctx->keys_full = keys_per_block_full;
+    ctx->keys_lazy = keys_per_block_lazy;
+    return LT_OK;
+}
+
+lt_status lt_profile_enable(lt_ctx *ctx, int32_t on)
+{
+    if (ctx == nullptr) return LT_ERR_INVALID_ARG;
+    if (on != 0 && ctx->events.empty()) {
+        try {
+            ctx->events.reserve(kMaxEventPairs);
+        } catch (const std::bad_alloc &) {
+            return LT_ERR_NOMEM;
+        }
+        for (int i = 0; i < kMaxEventPairs; ++i) {
+            EventPair p{};
+            if (hipEventCreate(&p.start) != hipSuccess) return LT_ERR_HIP;
+            if (hipEventCreate(&p.stop) != hipSuccess) {
+                (void)hipEventDestroy(p.start);
+                return LT_ERR_HIP;
+            }
+            ctx->events.push_back(p);
+        }
+    }
+    if (on != 0) ctx->events_used = 0;
+    ctx->profiling = on != 0;
+    return LT_OK;
+}
+
+lt_status lt_profile_read(lt_ctx *ctx, int32_t kernel, int64_t *launches, double *total_ms)
+{
+    if (ctx == nullptr || kernel < 0 || kernel >= LT_KERNEL_COUNT || launches == nullptr || total_ms == nullptr)
+        return LT_ERR_INVALID_ARG;
+    int64_t count = 0;
+    double sum = 0.0;
+    for (size_t i = 0; i < ctx->events_used; ++i) {
+        const EventPair &p = ctx->events[i];
+        if (p.kernel != kernel) continue;
+        if (hipEventSynchronize(p.stop) != hipSuccess) return LT_ERR_HIP;
+        float ms = 0.f;
+        if (hipEventElapsedTime(&ms, p.start, p.stop) != hipSuccess) return LT_ERR_HIP;
+        sum += ms;
+        ++count;
+    }
+    *launches = count;
+    *total_ms = sum;
+    return LT_OK;
+}
+
+}  // extern "C"

@@ -1,0 +1,59 @@
+// Internal launch interface between the C-ABI layer (lt_api.cpp) and the gfx950 kernels.
+// Plain pointers and sizes only; every launcher validates nothing (the API layer does) and
+// returns the HIP status of its launches.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace ltk {
+
+constexpr int kHeadDim = 128;          // bf16 elements per key / value / query vector
+constexpr int kMaxGroup = 8;           // query heads per KV head
+constexpr int kDecodeThreads = 256;    // 4 wavefronts per decode workgroup
+constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
+constexpr int kScoreTileKeys = 64;     // keys staged in LDS per step of the scoring kernel
+
+struct AppendArgs {
+    const uint16_t *k_new, *v_new;     // [B][Hkv][n_new][128]
+    uint16_t *k_cache, *v_cache;       // layer blocks
+    int64_t stride_b, stride_h;        // cache strides in elements
+    int64_t n_new, total_before;       // tokens in this call, tokens already in the layer
+    int32_t batch, n_kv_heads;
+    int32_t is_lazy, w_sink, w_recent;
+};
+hipError_t append(const AppendArgs &a, hipStream_t stream);
+
+struct DecodeArgs {
+    const uint16_t *k_cache, *v_cache;
+    const uint16_t *q;                 // [B][Hq][128]
+    float *part_acc;                   // [B][Hq][S][128]  un-normalised partial outputs
+    float *part_ml;                    // [B][Hq][S][2]    running max (log2 units) and sum
+    float *out;                        // [B][Hq][128]
+    float *lse;                        // [B][Hq] or nullptr
+    int64_t stride_b, stride_h;
+    int32_t batch, n_q_heads, n_kv_heads;
+    int32_t stored;                    // cache entries to attend over
+    int32_t keys_per_block, n_splits;
+    float scale_log2e;                 // softmax_scale * log2(e)
+    int32_t lazy_tag;                  // selects the kernel instantiation (name) only
+};
+hipError_t decode_partial(const DecodeArgs &a, hipStream_t stream);
+hipError_t decode_merge(const DecodeArgs &a, hipStream_t stream);
+
+struct ScoreArgs {
+    const uint16_t *q_last;            // [B][Hq][w][128]
+    const uint16_t *k;
+    int64_t k_stride_b, k_stride_h, k_stride_t;
+    int64_t n;
+    int32_t w_last, batch, n_q_heads, n_kv_heads;
+    int32_t w_sink, w_recent, fixed_mode;
+    int32_t keys_per_block, n_chunks;
+    float scale_log2e;
+    float *part;                       // [B][Hq][w][2*n_chunks][3]: max (log2 units), causal sum, kept sum
+    float *seq_scratch;                // [B]
+    float *rho, *ratio_seq, *ratio_mean;
+};
+hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);
+
+}  // namespace ltk

@@ -1,0 +1,302 @@
+// Lazy-ratio scoring for gfx950 (Eq. 1): the last w prompt queries of every head against all
+// prompt keys, as a dense bf16 contraction on the matrix cores with fp32 accumulation, reduced
+// on the fly to two sums per query -- the softmax denominator over the causal set and the part
+// of it that falls on the initial + recent keys.  No attention matrix and no V are touched.
+//
+// One workgroup = one (sequence, KV head, range of keys); wavefront i of the workgroup owns
+// query head g*G + i, so the G heads that share the KV head read each key tile from LDS once.
+// S^T = K Q^T is formed with v_mfma_f32_32x32x16_bf16: keys are the rows, queries the columns,
+// so each lane keeps 16 key logits of ONE query per instruction and the running max / sums
+// stay private to the lane until the final merge.
+#include "lt_kernels.h"
+
+namespace ltk {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;   // 16 bytes moved as one register quad
+
+constexpr int kRowPad = 8;                                  // bf16 elements of padding per key row in LDS
+constexpr int kRowElems = kHeadDim + kRowPad;               // 272-byte rows: 16-byte reads of 8 rows hit 8 bank groups
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+struct LaneState {
+    float m, sum_causal, sum_kept;
+};
+
+// Uniform description of a 32-key sub-tile relative to the masks.
+struct TileClass {
+    bool fast;      // every (key, query) pair is causal and the kept/dropped decision is the same for all pairs
+    bool kept;      // on the fast path: all pairs are kept
+};
+
+__device__ __forceinline__ TileClass classify(int64_t j0, int64_t n, int w, int w_sink, int w_recent, int fixed_mode)
+{
+    const int64_t j1 = j0 + 31;
+    const int64_t p_min = n - w, p_max = n - 1;
+    TileClass c;
+    const bool all_causal = j1 <= p_min;
+    bool all_kept, none_kept;
+    if (fixed_mode) {
+        all_kept = (j1 < w_sink) || (j0 >= n - w_recent);
+        none_kept = (j0 >= w_sink) && (j1 < n - w_recent);
+    } else {
+        all_kept = (j1 < w_sink) || (j0 > p_max - w_recent);
+        none_kept = (j0 >= w_sink) && (j1 <= p_min - w_recent);
+    }
+    c.fast = all_causal && (all_kept || none_kept);
+    c.kept = all_kept;
+    return c;
+}
+
+__device__ __forceinline__ void update_fast(const floatx16_t &c, LaneState &st, float scale_log2e, bool kept)
+{
+    float tmax = c[0];
+#pragma unroll
+    for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, c[i]);
+    const float m_new = fmaxf(st.m, tmax * scale_log2e);
+    const float alpha = fast_exp2(st.m - m_new);              // 0 on the first tile (m = -inf)
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(c[i], scale_log2e, -m_new));
+    st.sum_causal = st.sum_causal * alpha + sum;
+    st.sum_kept = st.sum_kept * alpha + (kept ? sum : 0.f);
+    st.m = m_new;
+}
+
+__device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st, float scale_log2e, int64_t j_base,
+                                              int64_t p, int64_t n, int w_sink, int w_recent, int fixed_mode)
+{
+    // key row of accumulator register i in this lane: j_base + 8*(i/4) + (i%4)
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t j = j_base + 8 * (i >> 2) + (i & 3);
+        if (j <= p) tmax = fmaxf(tmax, c[i]);
+    }
+    const float m_new = fmaxf(st.m, tmax * scale_log2e);
+    if (m_new == -INFINITY) return;                           // nothing causal seen so far
+    const float alpha = fast_exp2(st.m - m_new);
+    float sum = 0.f, kept = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int64_t j = j_base + 8 * (i >> 2) + (i & 3);
+        const bool causal = j <= p;
+        const bool recent = fixed_mode ? (j >= n - w_recent) : (j > p - w_recent);
+        const float e = causal ? fast_exp2(fmaf(c[i], scale_log2e, -m_new)) : 0.f;
+        sum += e;
+        kept += (j < w_sink || recent) ? e : 0.f;
+    }
+    st.sum_causal = st.sum_causal * alpha + sum;
+    st.sum_kept = st.sum_kept * alpha + kept;
+    st.m = m_new;
+}
+
+// A 64-key tile is 1024 16-byte pieces (coalesced rows of 256 B) spread over the workgroup.
+// fetch_tile() starts the global loads into registers, commit_tile() parks them in LDS; the MFMA
+// work of the current tile runs between the two so the load latency is covered.
+template <int G>
+struct Staging {
+    static constexpr int kThreads = 64 * G;
+    static constexpr int kTotal = kScoreTileKeys * 16;
+    static constexpr int kPieces = (kTotal + kThreads - 1) / kThreads;
+};
+
+template <int G>
+__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Staging<G>::kPieces], const uint16_t *kb, int64_t stride_t, int64_t j0,
+                                           int64_t n)
+{
+#pragma unroll
+    for (int i = 0; i < Staging<G>::kPieces; ++i) {
+        int idx = threadIdx.x + i * Staging<G>::kThreads;
+        idx = idx < Staging<G>::kTotal ? idx : Staging<G>::kTotal - 1;   // surplus threads re-read the last piece
+        int64_t j = j0 + (idx >> 4);
+        j = j < n ? j : n - 1;                                          // clamp; such keys are masked as non-causal
+        pre[i] = *reinterpret_cast<const u32x4_t *>(kb + j * stride_t + (idx & 15) * 8);
+    }
+}
+
+template <int G>
+__device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Staging<G>::kPieces], uint16_t *sh)
+{
+#pragma unroll
+    for (int i = 0; i < Staging<G>::kPieces; ++i) {
+        const int idx = threadIdx.x + i * Staging<G>::kThreads;
+        if (idx < Staging<G>::kTotal) *reinterpret_cast<u32x4_t *>(&sh[(idx >> 4) * kRowElems + (idx & 15) * 8]) = pre[i];
+    }
+}
+
+// G: query heads per KV head (wavefronts per workgroup).
+// NT: 32-query column tiles per head: 1 (w <= 32) or 2 (w <= 64).
+template <int G, int NT>
+__global__ __launch_bounds__(64 * G) void lt_lazy_ratio_partial_kernel(ScoreArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint16_t sh_k[2][kScoreTileKeys * kRowElems];
+
+    constexpr int kPieces = Staging<G>::kPieces;
+    const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+    const int h = g * G + wave;
+
+    const int64_t begin_key = (int64_t)chunk * a.keys_per_block;
+    const int64_t end_key = min(a.n, begin_key + (int64_t)a.keys_per_block);
+    const int n_tiles = (int)((end_key - begin_key + kScoreTileKeys - 1) / kScoreTileKeys);
+    const uint16_t *kb = a.k + (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
+
+    // Q^T fragments (B operand): lane holds, for its query column, the 8 dims 16*s + 8*half .. +7
+    bf16x8_t qf[NT][8];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int t = nt * 32 + col;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            uint4 u = make_uint4(0u, 0u, 0u, 0u);
+            if (t < a.w_last)
+                u = *reinterpret_cast<const uint4 *>(a.q_last + (((int64_t)b * a.n_q_heads + h) * a.w_last + t) * kHeadDim +
+                                                     16 * s + 8 * half);
+            qf[nt][s] = __builtin_bit_cast(bf16x8_t, u);
+        }
+    }
+
+    LaneState st[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) { st[nt].m = -INFINITY; st[nt].sum_causal = 0.f; st[nt].sum_kept = 0.f; }
+
+    u32x4_t pre[kPieces];
+    if (n_tiles > 0) {
+        fetch_tile<G>(pre, kb, a.k_stride_t, begin_key, a.n);
+        commit_tile<G>(pre, sh_k[0]);
+    }
+    __syncthreads();
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        const int buf = tile & 1;
+        const bool more = tile + 1 < n_tiles;
+        if (more) fetch_tile<G>(pre, kb, a.k_stride_t, begin_key + (int64_t)(tile + 1) * kScoreTileKeys, a.n);
+#pragma unroll
+        for (int kt = 0; kt < kScoreTileKeys / 32; ++kt) {
+            const int64_t j0 = begin_key + (int64_t)tile * kScoreTileKeys + 32 * kt;
+            if (j0 >= end_key) break;
+            floatx16_t c[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const uint4 u = *reinterpret_cast<const uint4 *>(&sh_k[buf][(32 * kt + col) * kRowElems + 16 * s + 8 * half]);
+                const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, u);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
+            }
+            const TileClass cls = classify(j0, a.n, a.w_last, a.w_sink, a.w_recent, a.fixed_mode);
+            if (cls.fast) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) update_fast(c[nt], st[nt], a.scale_log2e, cls.kept);
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const int64_t p = a.n - a.w_last + nt * 32 + col;   // query position of this lane's column
+                    update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, p, a.n, a.w_sink, a.w_recent, a.fixed_mode);
+                }
+            }
+        }
+        if (more) commit_tile<G>(pre, sh_k[buf ^ 1]);
+        __syncthreads();
+    }
+
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int t = nt * 32 + col;
+        if (t < a.w_last) {
+            float *dst = a.part + (((((int64_t)b * a.n_q_heads + h) * a.w_last + t) * (2 * a.n_chunks)) + 2 * chunk + half) * 3;
+            dst[0] = st[nt].m;
+            dst[1] = st[nt].sum_causal;
+            dst[2] = st[nt].sum_kept;
+        }
+    }
+}
+
+// rho per (sequence, head, query) and the per-sequence mean.  One workgroup per sequence,
+// fixed-order reductions so the result does not depend on scheduling.
+__global__ __launch_bounds__(256) void lt_lazy_ratio_finish_kernel(ScoreArgs a)
+{
+    __shared__ float sh_sum[256];
+    const int b = blockIdx.x;
+    const int per_seq = a.n_q_heads * a.w_last;
+    const int n_part = 2 * a.n_chunks;
+    float local = 0.f;
+    for (int idx = threadIdx.x; idx < per_seq; idx += 256) {
+        const float *src = a.part + ((int64_t)b * per_seq + idx) * n_part * 3;
+        float mx = -INFINITY;
+        for (int c = 0; c < n_part; ++c) mx = fmaxf(mx, src[3 * c]);
+        float causal = 0.f, kept = 0.f;
+        for (int c = 0; c < n_part; ++c) {
+            const float m = src[3 * c];
+            const float wgt = (m == -INFINITY) ? 0.f : fast_exp2(m - mx);
+            causal += wgt * src[3 * c + 1];
+            kept += wgt * src[3 * c + 2];
+        }
+        const float rho = kept / causal;
+        if (a.rho != nullptr) a.rho[(int64_t)b * per_seq + idx] = rho;
+        local += rho;
+    }
+    sh_sum[threadIdx.x] = local;
+    __syncthreads();
+    for (int step = 128; step > 0; step >>= 1) {
+        if ((int)threadIdx.x < step) sh_sum[threadIdx.x] += sh_sum[threadIdx.x + step];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const float r = sh_sum[0] / (float)per_seq;
+        a.seq_scratch[b] = r;
+        if (a.ratio_seq != nullptr) a.ratio_seq[b] = r;
+    }
+}
+
+__global__ void lt_lazy_ratio_mean_kernel(ScoreArgs a)
+{
+    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    float total = 0.f;
+    for (int b = 0; b < a.batch; ++b) total += a.seq_scratch[b];
+    a.ratio_mean[0] = total / (float)a.batch;
+}
+
+template <int G>
+hipError_t launch_partial(const ScoreArgs &a, hipStream_t stream)
+{
+    const dim3 grid(a.n_chunks, a.n_kv_heads, a.batch);
+    if (a.w_last <= 32)
+        hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 1>), grid, dim3(64 * G), 0, stream, a);
+    else
+        hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 2>), grid, dim3(64 * G), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream)
+{
+    hipError_t e;
+    switch (a.n_q_heads / a.n_kv_heads) {
+    case 1: e = launch_partial<1>(a, stream); break;
+    case 2: e = launch_partial<2>(a, stream); break;
+    case 3: e = launch_partial<3>(a, stream); break;
+    case 4: e = launch_partial<4>(a, stream); break;
+    case 5: e = launch_partial<5>(a, stream); break;
+    case 6: e = launch_partial<6>(a, stream); break;
+    case 7: e = launch_partial<7>(a, stream); break;
+    case 8: e = launch_partial<8>(a, stream); break;
+    default: e = hipErrorInvalidValue; break;
+    }
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(lt_lazy_ratio_finish_kernel, dim3(a.batch), dim3(256), 0, stream, a);
+    e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(lt_lazy_ratio_mean_kernel, dim3(1), dim3(64), 0, stream, a);
+    return hipGetLastError();
+}
+
+}  // namespace ltk

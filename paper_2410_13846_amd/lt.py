@@ -1,0 +1,264 @@
+"""ctypes binding with the names of include/lt.h.  Argument marshalling only: every step of the
+path runs in the library's kernels.  Device tensors are torch tensors used as plain memory; the
+stream is torch's current stream unless one is given."""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+from . import build as _build
+
+OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_STATE, ERR_HIP, ERR_NOMEM = range(7)
+RECENT_PER_QUERY, RECENT_FIXED = 0, 1
+KERNEL_DECODE_FULL, KERNEL_DECODE_LAZY, KERNEL_MERGE, KERNEL_APPEND = range(4)
+
+EXPORTS = [
+    "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
+    "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn",
+    "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
+]
+
+
+class LtError(RuntimeError):
+    def __init__(self, status: int, what: str):
+        self.status = status
+        super().__init__("%s failed: %s (status %d)" % (what, status_str(status), status))
+
+
+class Config(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("batch", ctypes.c_int32), ("n_q_heads", ctypes.c_int32),
+        ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32), ("w_sink", ctypes.c_int32),
+        ("w_recent", ctypes.c_int32), ("max_tokens", ctypes.c_int64), ("softmax_scale", ctypes.c_float),
+    ]
+
+
+_lib = None
+
+
+def library_path() -> str:
+    return _build.LIB_PATH
+
+
+def load() -> ctypes.CDLL:
+    """Load liblt_hip.so, building it first only when no built library exists."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_build.LIB_PATH):
+        _build.build(force=True)            # raises if hipcc is unavailable: there is no fallback path
+    lib = ctypes.CDLL(_build.LIB_PATH)
+    vp, sz, i32, i64 = ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int32, ctypes.c_int64
+    cfgp = ctypes.POINTER(Config)
+    lib.lt_kv_bytes.argtypes = [cfgp, vp]
+    lib.lt_kv_bytes.restype = sz
+    lib.lt_workspace_bytes.argtypes = [cfgp]
+    lib.lt_workspace_bytes.restype = sz
+    lib.lt_create.argtypes = [cfgp, vp, vp, sz, vp, sz, ctypes.POINTER(vp)]
+    lib.lt_create.restype = ctypes.c_int
+    lib.lt_destroy.argtypes = [vp]
+    lib.lt_destroy.restype = None
+    lib.lt_reset.argtypes = [vp]
+    lib.lt_reset.restype = ctypes.c_int
+    lib.lt_layer_len.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.lt_layer_len.restype = ctypes.c_int
+    lib.lt_layer_view.argtypes = [vp, i32, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(i64),
+                                  ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i32)]
+    lib.lt_layer_view.restype = ctypes.c_int
+    lib.lt_lazy_ratio_workspace_bytes.argtypes = [cfgp, i64, i32]
+    lib.lt_lazy_ratio_workspace_bytes.restype = sz
+    lib.lt_lazy_ratio.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, sz, vp, vp, vp, vp]
+    lib.lt_lazy_ratio.restype = ctypes.c_int
+    lib.lt_select_lazy.argtypes = [vp, i32, i32, vp, vp]
+    lib.lt_select_lazy.restype = ctypes.c_int
+    lib.lt_append_kv.argtypes = [vp, i32, vp, vp, i64, vp]
+    lib.lt_append_kv.restype = ctypes.c_int
+    lib.lt_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp]
+    lib.lt_decode_attn.restype = ctypes.c_int
+    lib.lt_set_split.argtypes = [vp, i32, i32]
+    lib.lt_set_split.restype = ctypes.c_int
+    lib.lt_profile_enable.argtypes = [vp, i32]
+    lib.lt_profile_enable.restype = ctypes.c_int
+    lib.lt_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
+    lib.lt_profile_read.restype = ctypes.c_int
+    lib.lt_status_str.argtypes = [ctypes.c_int]
+    lib.lt_status_str.restype = ctypes.c_char_p
+    _lib = lib
+    return lib
+
+
+def status_str(status: int) -> str:
+    return load().lt_status_str(int(status)).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != OK:
+        raise LtError(status, what)
+
+
+def make_config(n_layers, batch, n_q_heads, n_kv_heads, head_dim, w_sink, w_recent, max_tokens, softmax_scale=0.0) -> Config:
+    return Config(int(n_layers), int(batch), int(n_q_heads), int(n_kv_heads), int(head_dim), int(w_sink),
+                  int(w_recent), int(max_tokens), float(softmax_scale))
+
+
+def _mask_array(is_lazy: Sequence[int]) -> np.ndarray:
+    return np.ascontiguousarray(np.asarray(is_lazy, dtype=np.uint8))
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype, what: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda or t.dtype != dtype or not t.is_contiguous():
+        raise TypeError("%s must be a contiguous device tensor of %s" % (what, dtype))
+    return t.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def kv_bytes(cfg: Config, is_lazy) -> int:
+    m = _mask_array(is_lazy)
+    return int(load().lt_kv_bytes(ctypes.byref(cfg), m.ctypes.data))
+
+
+def workspace_bytes(cfg: Config) -> int:
+    return int(load().lt_workspace_bytes(ctypes.byref(cfg)))
+
+
+def lazy_ratio_workspace_bytes(cfg: Config, n: int, w_last: int) -> int:
+    return int(load().lt_lazy_ratio_workspace_bytes(ctypes.byref(cfg), int(n), int(w_last)))
+
+
+def select_lazy(ratios, n_lazy: int):
+    """Host-only.  Returns (is_lazy uint8 [L], order int32 [L])."""
+    r = np.ascontiguousarray(np.asarray(ratios, dtype=np.float32))
+    L = int(r.shape[0])
+    is_lazy = np.zeros(L, dtype=np.uint8)
+    order = np.zeros(L, dtype=np.int32)
+    st = load().lt_select_lazy(r.ctypes.data, L, int(n_lazy), is_lazy.ctypes.data, order.ctypes.data)
+    _check(st, "lt_select_lazy")
+    return is_lazy, order
+
+
+def lazy_ratio(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_last: int, mode: int = RECENT_PER_QUERY,
+               workspace: Optional[torch.Tensor] = None, want_rho: bool = False, stream=None):
+    """q_last bf16 [B,Hq,w,128]; k bf16 [B,Hkv,>=n,128] (any strides with contiguous dims).
+
+    Returns device tensors (ratio_mean [1], ratio_seq [B], rho [B,Hq,w] or None)."""
+    lib = load()
+    if q_last.dtype != torch.bfloat16 or k.dtype != torch.bfloat16 or not q_last.is_cuda or not k.is_cuda:
+        raise TypeError("q_last and k must be bf16 device tensors")
+    if not q_last.is_contiguous() or k.dim() != 4 or k.stride(3) != 1:
+        raise TypeError("q_last must be contiguous and k must have contiguous head_dim")
+    need = lazy_ratio_workspace_bytes(cfg, n, w_last)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_last.device)
+    dev = q_last.device
+    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    seq = torch.empty(cfg.batch, dtype=torch.float32, device=dev)
+    rho = torch.empty((cfg.batch, cfg.n_q_heads, w_last), dtype=torch.float32, device=dev) if want_rho else None
+    st = lib.lt_lazy_ratio(ctypes.byref(cfg), q_last.data_ptr(), k.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
+                           int(n), int(w_last), int(mode), workspace.data_ptr(), workspace.numel(),
+                           rho.data_ptr() if rho is not None else None, seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
+    _check(st, "lt_lazy_ratio")
+    return mean, seq, rho
+
+
+class Context:
+    """Owns the torch tensors used as KV slab and workspace, and the library's host-side context."""
+
+    def __init__(self, cfg: Config, is_lazy, device="cuda:0"):
+        lib = load()
+        self.cfg = cfg
+        self.is_lazy = _mask_array(is_lazy)
+        if self.is_lazy.shape[0] != cfg.n_layers:
+            raise ValueError("is_lazy needs one entry per layer")
+        kvb, wsb = kv_bytes(cfg, self.is_lazy), workspace_bytes(cfg)
+        if kvb == 0 or wsb == 0:
+            raise LtError(ERR_INVALID_ARG, "lt_kv_bytes / lt_workspace_bytes")
+        self.device = torch.device(device)
+        self.kv_slab = torch.empty(kvb, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.empty(wsb, dtype=torch.uint8, device=self.device)
+        handle = ctypes.c_void_p()
+        st = lib.lt_create(ctypes.byref(cfg), self.is_lazy.ctypes.data, self.kv_slab.data_ptr(), kvb,
+                           self.workspace.data_ptr(), wsb, ctypes.byref(handle))
+        _check(st, "lt_create")
+        self._h = handle
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().lt_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def reset(self):
+        _check(load().lt_reset(self._h), "lt_reset")
+
+    def layer_len(self, layer: int):
+        total, stored = ctypes.c_int64(), ctypes.c_int64()
+        _check(load().lt_layer_len(self._h, int(layer), ctypes.byref(total), ctypes.byref(stored)), "lt_layer_len")
+        return total.value, stored.value
+
+    def layer_view(self, layer: int):
+        k, v = ctypes.c_void_p(), ctypes.c_void_p()
+        sb, sh, cap, lazy = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+        _check(load().lt_layer_view(self._h, int(layer), ctypes.byref(k), ctypes.byref(v), ctypes.byref(sb),
+                                    ctypes.byref(sh), ctypes.byref(cap), ctypes.byref(lazy)), "lt_layer_view")
+        return {"k": k.value, "v": v.value, "stride_b": sb.value, "stride_h": sh.value, "capacity": cap.value,
+                "is_lazy": bool(lazy.value)}
+
+    def layer_tensors(self, layer: int):
+        """Views of a layer's K and V blocks inside the slab: bf16 [B, Hkv, capacity, 128]."""
+        view = self.layer_view(layer)
+        shape = (self.cfg.batch, self.cfg.n_kv_heads, view["capacity"], self.cfg.head_dim)
+        count = int(np.prod(shape))
+        base = self.kv_slab.data_ptr()
+        out = []
+        for key in ("k", "v"):
+            off = view[key] - base
+            out.append(self.kv_slab[off: off + 2 * count].view(torch.bfloat16).view(shape))
+        return out[0], out[1]
+
+    def append_kv(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, stream=None):
+        kp, vp = _dev_ptr(k_new, torch.bfloat16, "k_new"), _dev_ptr(v_new, torch.bfloat16, "v_new")
+        expect = (self.cfg.batch, self.cfg.n_kv_heads, k_new.shape[2] if k_new.dim() == 4 else -1, self.cfg.head_dim)
+        if tuple(k_new.shape) != expect or tuple(v_new.shape) != expect:
+            raise LtError(ERR_SHAPE, "lt_append_kv (k_new / v_new must be [B,Hkv,n_new,128])")
+        st = load().lt_append_kv(self._h, int(layer), kp, vp, int(k_new.shape[2]), _stream_ptr(stream))
+        _check(st, "lt_append_kv")
+
+    def decode_attn(self, layer: int, q: torch.Tensor, out: Optional[torch.Tensor] = None,
+                    lse: Optional[torch.Tensor] = None, want_lse: bool = False, stream=None):
+        qp = _dev_ptr(q, torch.bfloat16, "q")
+        if tuple(q.shape) != (self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim):
+            raise LtError(ERR_SHAPE, "lt_decode_attn (q must be [B,Hq,128])")
+        if out is None:
+            out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=torch.float32, device=q.device)
+        if lse is None and want_lse:
+            lse = torch.empty((self.cfg.batch, self.cfg.n_q_heads), dtype=torch.float32, device=q.device)
+        st = load().lt_decode_attn(self._h, int(layer), qp, _dev_ptr(out, torch.float32, "out"),
+                                   _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
+        _check(st, "lt_decode_attn")
+        return (out, lse) if (want_lse or lse is not None) else out
+
+    def set_split(self, keys_full: int = 0, keys_lazy: int = 0):
+        _check(load().lt_set_split(self._h, int(keys_full), int(keys_lazy)), "lt_set_split")
+
+    def profile_enable(self, on: bool = True):
+        _check(load().lt_profile_enable(self._h, 1 if on else 0), "lt_profile_enable")
+
+    def profile_read(self, kernel: int):
+        n, ms = ctypes.c_int64(), ctypes.c_double()
+        _check(load().lt_profile_read(self._h, int(kernel), ctypes.byref(n), ctypes.byref(ms)), "lt_profile_read")
+        return n.value, ms.value

@@ -1,0 +1,162 @@
+"""GPU parity: lt_append_kv + lt_decode_attn through the C ABI against the CPU oracle, element by
+element on seeded inputs.  The oracle keeps the whole history and applies the streaming set
+positionally; the GPU side keeps a ring, so these tests also validate the ring."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL_LSE, TOL_OUT, bits, f64, randn_bf16, say
+from paper_2410_13846_amd import lt
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def run_case(B, Hq, Hkv, n_prefill, steps, w_sink, w_recent, seed, split=None, max_extra=0):
+    say("decode case", dict(B=B, Hq=Hq, Hkv=Hkv, n=n_prefill, steps=steps, ws=w_sink, wr=w_recent, seed=seed, split=split))
+    cfg = lt.make_config(2, B, Hq, Hkv, 128, w_sink, w_recent, n_prefill + steps + max_extra)
+    mask = [0, 1]
+    ctx = lt.Context(cfg, mask, DEV)
+    if split is not None:
+        ctx.set_split(*split)
+    hist = oracle.History(2, mask, w_sink, w_recent)
+    worst = 0.0
+    if n_prefill > 0:
+        for layer in range(2):
+            k = randn_bf16((B, Hkv, n_prefill, 128), seed + 10 + layer)
+            v = randn_bf16((B, Hkv, n_prefill, 128), seed + 20 + layer)
+            ctx.append_kv(layer, k, v)
+            hist.append(layer, bits(k), bits(v))
+    for step in range(steps):
+        for layer in range(2):
+            q = randn_bf16((B, Hq, 128), seed + 1000 * (step + 1) + layer, scale=1.5)
+            k = randn_bf16((B, Hkv, 1, 128), seed + 1000 * (step + 1) + 30 + layer)
+            v = randn_bf16((B, Hkv, 1, 128), seed + 1000 * (step + 1) + 40 + layer)
+            ctx.append_kv(layer, k, v)
+            out, lse = ctx.decode_attn(layer, q, want_lse=True)
+            hist.append(layer, bits(k), bits(v))
+            ref, ref_lse = hist.decode(layer, bits(q))
+            err = np.abs(f64(out) - ref).max()
+            err_lse = np.abs(f64(lse) - ref_lse).max()
+            assert err <= TOL_OUT, (layer, step, err)
+            assert err_lse <= TOL_LSE, (layer, step, err_lse)
+            worst = max(worst, err)
+            total, stored = ctx.layer_len(layer)
+            assert total == hist.length(layer)
+            assert stored == (min(total, w_sink + w_recent) if mask[layer] else total)
+    ctx.close()
+    return worst
+
+
+@pytest.mark.parametrize("n_prefill", [0, 1, 15, 16, 17, 63, 64, 65, 300, 1027, 2500])
+def test_prefill_lengths_span_tiles_and_ragged_tails(n_prefill):
+    run_case(B=2, Hq=8, Hkv=2, n_prefill=n_prefill, steps=3, w_sink=4, w_recent=60, seed=100 + n_prefill)
+
+
+@pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 6, 7, 8])
+def test_every_query_group_size(group):
+    run_case(B=1, Hq=2 * group, Hkv=2, n_prefill=333, steps=2, w_sink=4, w_recent=124, seed=200 + group)
+
+
+@pytest.mark.parametrize("ws,wr", [(0, 7), (4, 0), (1, 1), (4, 1020), (6, 252), (2, 508), (0, 2044), (300, 5)])
+def test_window_shapes_including_the_paper_grid(ws, wr):
+    run_case(B=1, Hq=8, Hkv=2, n_prefill=2300, steps=3, w_sink=ws, w_recent=wr, seed=300 + ws + wr)
+
+
+def test_ring_wraps_many_times_with_single_token_appends():
+    # window of 4 + 12 entries, 70 decode steps from an empty cache: the ring wraps five times
+    run_case(B=2, Hq=4, Hkv=1, n_prefill=0, steps=70, w_sink=4, w_recent=12, seed=400)
+
+
+@pytest.mark.parametrize("split", [(256, 64), (512, 128), (2048, 2048)])
+def test_result_does_not_depend_on_the_split(split):
+    run_case(B=1, Hq=8, Hkv=2, n_prefill=3000, steps=2, w_sink=4, w_recent=1020, seed=500, split=split)
+
+
+def test_streaming_equals_full_when_window_covers_history():
+    B, Hq, Hkv, n = 1, 8, 2, 200
+    cfg = lt.make_config(2, B, Hq, Hkv, 128, 4, 1020, n + 1)
+    ctx = lt.Context(cfg, [0, 1], DEV)
+    k, v = randn_bf16((B, Hkv, n, 128), 601), randn_bf16((B, Hkv, n, 128), 602)
+    q = randn_bf16((B, Hq, 128), 603)
+    say("streaming == full, n", n)
+    outs = []
+    for layer in range(2):
+        ctx.append_kv(layer, k, v)
+        outs.append(ctx.decode_attn(layer, q))
+    assert (outs[0] - outs[1]).abs().max().item() <= 1e-6     # same entries, possibly split differently
+    ctx.set_split(256, 256)
+    outs = [ctx.decode_attn(layer, q) for layer in range(2)]
+    assert torch.equal(outs[0], outs[1])                      # same kernel, same entries, same split: same bits
+    ctx.close()
+
+
+def test_uniform_keys_give_mean_of_values():
+    B, Hq, Hkv, n = 1, 8, 2, 777
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, 4, 60, n)
+    ctx = lt.Context(cfg, [0], DEV)
+    k = randn_bf16((B, Hkv, 1, 128), 611).expand(B, Hkv, n, 128).contiguous()
+    v = randn_bf16((B, Hkv, n, 128), 612)
+    say("uniform keys, n", n)
+    ctx.append_kv(0, k, v)
+    out = ctx.decode_attn(0, randn_bf16((B, Hq, 128), 613))
+    mean = v.double().mean(dim=2).repeat_interleave(Hq // Hkv, dim=1)
+    assert (out.double() - mean).abs().max().item() <= 1e-5
+    ctx.close()
+
+
+def test_ring_slots_hold_exactly_the_kept_tokens():
+    """Byte-exact: after a bulk prefill and some single appends, slot s of the ring holds the token
+    the slot rule assigns to it, and a full layer holds every token in order."""
+    B, Hkv, ws, wr, n, steps = 2, 2, 4, 28, 100, 45
+    cfg = lt.make_config(2, B, 8, Hkv, 128, ws, wr, n + steps)
+    ctx = lt.Context(cfg, [0, 1], DEV)
+    ks = [randn_bf16((B, Hkv, n, 128), 621)]
+    vs = [randn_bf16((B, Hkv, n, 128), 622)]
+    say("ring slots")
+    for layer in range(2):
+        ctx.append_kv(layer, ks[0], vs[0])
+    for s in range(steps):
+        ks.append(randn_bf16((B, Hkv, 1, 128), 630 + s))
+        vs.append(randn_bf16((B, Hkv, 1, 128), 730 + s))
+        for layer in range(2):
+            ctx.append_kv(layer, ks[-1], vs[-1])
+    K, V = torch.cat(ks, 2), torch.cat(vs, 2)
+    T = n + steps
+    kf, vf = ctx.layer_tensors(0)
+    assert torch.equal(kf[:, :, :T].view(torch.int16), K.view(torch.int16))
+    assert torch.equal(vf[:, :, :T].view(torch.int16), V.view(torch.int16))
+    kl, vl = ctx.layer_tensors(1)
+    assert kl.shape[2] == ws + wr
+    for p in list(range(ws)) + list(range(T - wr, T)):
+        slot = p if p < ws else ws + (p - ws) % wr
+        assert torch.equal(kl[:, :, slot].view(torch.int16), K[:, :, p].view(torch.int16)), p
+        assert torch.equal(vl[:, :, slot].view(torch.int16), V[:, :, p].view(torch.int16)), p
+    ctx.close()
+
+
+def test_error_paths_on_the_device():
+    cfg = lt.make_config(2, 1, 8, 2, 128, 4, 12, 10)
+    ctx = lt.Context(cfg, [0, 1], DEV)
+    k = randn_bf16((1, 2, 8, 128), 641)
+    q = randn_bf16((1, 8, 128), 642)
+    with pytest.raises(lt.LtError) as e:
+        ctx.decode_attn(0, q)
+    assert e.value.status == lt.ERR_STATE
+    ctx.append_kv(0, k, k)
+    with pytest.raises(lt.LtError) as e:
+        ctx.append_kv(0, k, k)                          # 16 > max_tokens = 10
+    assert e.value.status == lt.ERR_CAPACITY
+    assert ctx.layer_len(0) == (8, 8)
+    for _ in range(5):
+        ctx.append_kv(1, k, k)                          # a lazy layer never overflows
+    assert ctx.layer_len(1) == (40, 16)
+    with pytest.raises(lt.LtError) as e:
+        ctx.append_kv(0, k[:, :1], k[:, :1])
+    assert e.value.status == lt.ERR_SHAPE
+    out = ctx.decode_attn(0, q)
+    assert torch.isfinite(out).all()
+    ctx.reset()
+    assert ctx.layer_len(1) == (0, 0)
+    ctx.close()

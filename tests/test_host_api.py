@@ -1,0 +1,163 @@
+"""Host-side behaviour of the C-ABI library that needs no GPU: exported symbols, size queries,
+argument validation (which happens before any launch), and lazy-layer selection."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2410_13846_amd import lt
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE_DEV = 0x10000000          # aligned, never dereferenced: no call below reaches a launch
+
+
+def cfg(**kw):
+    base = dict(n_layers=4, batch=2, n_q_heads=8, n_kv_heads=2, head_dim=128, w_sink=4, w_recent=60, max_tokens=1000)
+    base.update(kw)
+    return lt.make_config(**base)
+
+
+def test_library_exports_every_declared_symbol():
+    lib = lt.load()
+    header = open(os.path.join(ROOT, "include", "lt.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    declared = set(re.findall(r"\b(lt_[a-z_]+)\s*\(", header))
+    assert declared, "no declarations found in lt.h"
+    assert declared == set(lt.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_kv_and_workspace_sizes():
+    c = cfg()
+    per_token = 2 * 2 * 128 * 2            # B * Hkv * d * sizeof(bf16)
+    full, lazy = per_token * 1000, per_token * 64
+    assert lt.kv_bytes(c, [0, 0, 0, 0]) == 4 * 2 * full
+    assert lt.kv_bytes(c, [1, 0, 1, 0]) == 2 * 2 * full + 2 * 2 * lazy
+    assert lt.kv_bytes(c, [1, 1, 1, 1]) == 4 * 2 * lazy
+    assert lt.workspace_bytes(c) > 0
+    # the 128K, batch 16 configuration: 16 full layers of 8.59 GB + 16 rings, 64-bit sizes
+    big = lt.make_config(32, 16, 32, 8, 128, 4, 4092, 131072 + 32)
+    mask = [1] * 16 + [0] * 16
+    expect = 16 * 2 * (16 * 8 * (131072 + 32) * 128 * 2) + 16 * 2 * (16 * 8 * 4096 * 128 * 2)
+    assert lt.kv_bytes(big, mask) == expect
+    assert expect > 2 ** 37
+
+
+@pytest.mark.parametrize("bad", [dict(head_dim=64), dict(n_q_heads=7), dict(n_q_heads=32, n_kv_heads=2), dict(batch=0),
+                                 dict(max_tokens=0), dict(w_sink=-1), dict(max_tokens=2 ** 31)])
+def test_invalid_configurations_are_rejected(bad):
+    c = cfg(**bad)
+    assert lt.kv_bytes(c, [0, 0, 0, 0]) == 0
+    assert lt.workspace_bytes(c) == 0
+    handle = ctypes.c_void_p()
+    st = lt.load().lt_create(ctypes.byref(c), np.zeros(4, np.uint8).ctypes.data, FAKE_DEV, 1 << 40, FAKE_DEV, 1 << 40,
+                             ctypes.byref(handle))
+    assert st in (lt.ERR_INVALID_ARG, lt.ERR_SHAPE) and not handle.value
+
+
+def make_ctx(c, mask):
+    handle = ctypes.c_void_p()
+    m = np.asarray(mask, np.uint8)
+    st = lt.load().lt_create(ctypes.byref(c), m.ctypes.data, FAKE_DEV, lt.kv_bytes(c, mask), FAKE_DEV + (1 << 34),
+                             lt.workspace_bytes(c), ctypes.byref(handle))
+    assert st == lt.OK
+    return handle
+
+
+def test_create_validates_buffers_and_lays_out_layers():
+    lib, c, mask = lt.load(), cfg(), [0, 1, 0, 1]
+    m = np.asarray(mask, np.uint8)
+    handle = ctypes.c_void_p()
+    kvb, wsb = lt.kv_bytes(c, mask), lt.workspace_bytes(c)
+    assert lib.lt_create(ctypes.byref(c), m.ctypes.data, FAKE_DEV, kvb - 1, FAKE_DEV, wsb, ctypes.byref(handle)) == lt.ERR_CAPACITY
+    assert lib.lt_create(ctypes.byref(c), m.ctypes.data, FAKE_DEV, kvb, FAKE_DEV, wsb - 1, ctypes.byref(handle)) == lt.ERR_CAPACITY
+    assert lib.lt_create(ctypes.byref(c), m.ctypes.data, FAKE_DEV + 8, kvb, FAKE_DEV, wsb, ctypes.byref(handle)) == lt.ERR_INVALID_ARG
+    assert lib.lt_create(ctypes.byref(c), m.ctypes.data, None, kvb, FAKE_DEV, wsb, ctypes.byref(handle)) == lt.ERR_INVALID_ARG
+    h = make_ctx(c, mask)
+    # blocks are laid out back to back in layer order: K then V, full = 1000 tokens, lazy = 64
+    cursor = FAKE_DEV
+    for layer in range(4):
+        k, v = ctypes.c_void_p(), ctypes.c_void_p()
+        sb, sh, cap, lazy = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+        assert lib.lt_layer_view(h, layer, ctypes.byref(k), ctypes.byref(v), ctypes.byref(sb), ctypes.byref(sh),
+                                 ctypes.byref(cap), ctypes.byref(lazy)) == lt.OK
+        tokens = 64 if mask[layer] else 1000
+        block = 2 * 2 * tokens * 128 * 2
+        assert (k.value, v.value) == (cursor, cursor + block)
+        assert (cap.value, lazy.value, sh.value, sb.value) == (tokens, mask[layer], tokens * 128, tokens * 128 * 2)
+        cursor += 2 * block
+    assert lib.lt_layer_view(h, 4, None, None, None, None, None, None) == lt.ERR_INVALID_ARG
+    lib.lt_destroy(h)
+    lib.lt_destroy(None)
+
+
+def test_calls_out_of_order_or_over_capacity_fail_before_any_launch():
+    lib, c = lt.load(), cfg()
+    h = make_ctx(c, [0, 1, 0, 1])
+    # decode on an empty layer
+    assert lib.lt_decode_attn(h, 0, FAKE_DEV, FAKE_DEV, None, None) == lt.ERR_STATE
+    assert lib.lt_decode_attn(h, 9, FAKE_DEV, FAKE_DEV, None, None) == lt.ERR_INVALID_ARG
+    assert lib.lt_decode_attn(h, 0, None, FAKE_DEV, None, None) == lt.ERR_INVALID_ARG
+    # a full layer cannot take more than max_tokens; the failed call leaves the count unchanged
+    assert lib.lt_append_kv(h, 0, FAKE_DEV, FAKE_DEV, 1001, None) == lt.ERR_CAPACITY
+    assert lib.lt_append_kv(h, 0, FAKE_DEV, FAKE_DEV, 0, None) == lt.ERR_INVALID_ARG
+    assert lib.lt_append_kv(h, 0, FAKE_DEV + 2, FAKE_DEV, 1, None) == lt.ERR_INVALID_ARG
+    total, stored = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    assert lib.lt_layer_len(h, 0, ctypes.byref(total), ctypes.byref(stored)) == lt.OK
+    assert (total.value, stored.value) == (0, 0)
+    # split sizes: multiples of 64, and never more splits than the workspace holds
+    assert lib.lt_set_split(h, 100, 0) == lt.ERR_INVALID_ARG
+    assert lib.lt_set_split(h, 64, 0) == lt.ERR_CAPACITY
+    assert lib.lt_set_split(h, 512, 64) == lt.OK
+    assert lib.lt_profile_read(h, 7, ctypes.byref(total), ctypes.byref(ctypes.c_double())) == lt.ERR_INVALID_ARG
+    lib.lt_destroy(h)
+
+
+def test_lazy_ratio_argument_validation():
+    lib, c = lt.load(), cfg()
+    need = lt.lazy_ratio_workspace_bytes(c, 500, 16)
+    assert need > 0
+    assert lt.lazy_ratio_workspace_bytes(c, 500, 65) == 0
+    assert lt.lazy_ratio_workspace_bytes(c, 0, 16) == 0
+
+    def call(n=500, w=16, mode=0, ws=need, sb=500 * 128 * 2, sh=500 * 128, st=128, q=FAKE_DEV, mean=FAKE_DEV):
+        return lib.lt_lazy_ratio(ctypes.byref(c), q, FAKE_DEV, sb, sh, st, n, w, mode, FAKE_DEV, ws, None, None, mean, None)
+
+    assert call(w=0) == lt.ERR_INVALID_ARG
+    assert call(mode=3) == lt.ERR_INVALID_ARG
+    assert call(q=None) == lt.ERR_INVALID_ARG
+    assert call(mean=None) == lt.ERR_INVALID_ARG
+    assert call(n=8, w=16) == lt.ERR_SHAPE              # more scored queries than prompt tokens
+    assert call(w=65) == lt.ERR_SHAPE
+    assert call(st=64) == lt.ERR_SHAPE                  # rows would overlap
+    assert call(sh=500 * 128 + 4) == lt.ERR_SHAPE       # 16-byte alignment of rows
+    assert call(ws=need - 1) == lt.ERR_CAPACITY
+
+
+def test_select_lazy_matches_the_oracle_and_the_queue():
+    rng = np.random.default_rng(7)
+    for L in (1, 2, 32, 64):
+        for trial in range(10):
+            r = rng.random(L).astype(np.float32)
+            if trial % 2:
+                r = (np.round(r * 4) / 4).astype(np.float32)        # ties
+            for n_lazy in {0, L // 4, L // 2, L}:
+                got, order = lt.select_lazy(r, n_lazy)
+                ref, ref_order = oracle.select_lazy(r.astype(np.float64), n_lazy)
+                queue, _ = oracle.select_lazy_queue(r.astype(np.float64), n_lazy)
+                np.testing.assert_array_equal(got, ref)
+                np.testing.assert_array_equal(got, queue)
+                np.testing.assert_array_equal(order, ref_order)
+
+
+def test_select_lazy_rejects_bad_input():
+    with pytest.raises(lt.LtError) as e:
+        lt.select_lazy(np.array([0.5, np.nan], np.float32), 1)
+    assert e.value.status == lt.ERR_INVALID_ARG
+    with pytest.raises(lt.LtError):
+        lt.select_lazy(np.array([0.5, 0.1], np.float32), 3)
+    assert lt.status_str(lt.ERR_CAPACITY) == "capacity exceeded"
