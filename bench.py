@@ -1,0 +1,317 @@
+#!/usr/bin/env python3
+"""Benchmark of the LightTransfer hot path on one MI355X.
+
+A step is one decode step of the whole hybrid stack: for every layer, lt_append_kv of the new
+token's K/V and lt_decode_attn over that layer's cache (full layers: the whole growing cache;
+lazy layers: the sink + recent ring).  Before the timed region the stack is set up the way the
+method prescribes: lt_lazy_ratio scores every layer on the last w_last prompt queries,
+lt_select_lazy picks the lazy layers, and the prompt K/V are appended; those calls are timed
+separately and reported under "scoring".  All inputs are seeded synthetic tensors resident in
+HBM before timing starts.
+
+Prints one JSON line: tokens/s (value), the roofline of the dominant kernel (split decode over
+full layers, HBM-bound) and the CPU oracle timed on a bounded sample of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16, published
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="llama3_8b_32k")
+    ap.add_argument("--n-lazy", type=int, default=None, help="override the number of lazy layers")
+    ap.add_argument("--keys-full", type=int, default=0, help="keys per workgroup in full layers (0 = built-in)")
+    ap.add_argument("--keys-lazy", type=int, default=0)
+    ap.add_argument("--no-speedup", action="store_true", help="skip the all-full comparison run")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile-pass", action="store_true", help="skip the second pass that times kernels with HIP events")
+    return ap.parse_args()
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Stack:
+    """A hybrid stack with its decode inputs pre-generated on the device."""
+
+    def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0):
+        import torch
+
+        self.lt, self.wl, self.is_lazy, self.dev = lt, wl, list(map(int, is_lazy)), dev
+        self.cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink,
+                                  wl.w_recent, wl.context + total_steps)
+        self.ctx = lt.Context(self.cfg, self.is_lazy, dev)
+        if keys_full or keys_lazy:
+            self.ctx.set_split(keys_full, keys_lazy)
+        for layer in range(wl.n_layers):
+            k, v = W.prefill_kv(wl, layer, dev)
+            self.ctx.append_kv(layer, k, v)
+            del k, v
+        self.q, self.k, self.v = [], [], []
+        for layer in range(wl.n_layers):
+            q, k, v = W.decode_qkv_block(wl, layer, 0, total_steps, dev)
+            self.q.append(q)
+            self.k.append(k)
+            self.v.append(v)
+        self.out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+        self.step = 0
+        torch.cuda.synchronize()
+        # raw pointers so the timed loop is ctypes calls only
+        self._lib = lt.load()
+        self._h = self.ctx._h
+        self._stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+        esz_q = wl.batch * wl.n_q_heads * wl.head_dim * 2
+        esz_kv = wl.batch * wl.n_kv_heads * wl.head_dim * 2
+        self._ptrs = [(self.q[l].data_ptr(), esz_q, self.k[l].data_ptr(), self.v[l].data_ptr(), esz_kv,
+                       self.out[l].data_ptr()) for l in range(wl.n_layers)]
+
+    def run(self, n_steps):
+        lib, h, stream = self._lib, self._h, self._stream
+        for _ in range(n_steps):
+            s = self.step
+            for layer, (qp, qs, kp, vp, kvs, op) in enumerate(self._ptrs):
+                st = lib.lt_append_kv(h, layer, kp + s * kvs, vp + s * kvs, 1, stream)
+                if st != 0:
+                    raise self.lt.LtError(st, "lt_append_kv")
+                st = lib.lt_decode_attn(h, layer, qp + s * qs, op, None, stream)
+                if st != 0:
+                    raise self.lt.LtError(st, "lt_decode_attn")
+            self.step += 1
+
+    def tokens_now(self):
+        return self.wl.context + self.step
+
+    def close(self):
+        self.ctx.close()
+
+
+def timed(stack, n_steps):
+    import torch
+
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    stack.run(n_steps)
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def score_layers(lt, W, wl, dev):
+    """lt_lazy_ratio on every layer (prompt regenerated per layer), timed with events on the launch stream."""
+    import torch
+
+    cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink, wl.w_recent, wl.context)
+    ws = torch.empty(max(lt.lazy_ratio_workspace_bytes(cfg, wl.context, wl.w_last), 256), dtype=torch.uint8, device=dev)
+    ratios, ms = [], []
+    for layer in range(wl.n_layers):
+        k, _ = W.prefill_kv(wl, layer, dev)
+        q_last = W.last_queries(wl, layer, dev)
+        if layer == 0:                                     # warm-up launch, not timed
+            lt.lazy_ratio(cfg, q_last, k, wl.context, wl.w_last, workspace=ws)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        mean, _, _ = lt.lazy_ratio(cfg, q_last, k, wl.context, wl.w_last, workspace=ws)
+        e1.record()
+        e1.synchronize()
+        ms.append(e0.elapsed_time(e1))
+        ratios.append(float(mean.cpu()[0]))
+        del k, q_last
+    return ratios, ms
+
+
+def cpu_baseline(W, wl, stack, is_lazy):
+    """The oracle, as it stands, on one sequence of one full and one lazy layer at the real length."""
+    import numpy as np
+    import torch
+
+    import oracle
+
+    T = stack.tokens_now()
+    per_kind = {}
+    for kind in (0, 1):
+        layers = [l for l in range(wl.n_layers) if is_lazy[l] == kind]
+        if not layers:
+            continue
+        layer = layers[0]
+        # rebuild sequence 0's whole history of this layer on the host (the oracle keeps every token)
+        k, v = W.prefill_kv(wl, layer, stack.dev)
+        K = np.concatenate([W.bf16_bits(k[:1]), W.bf16_bits(stack.k[layer][: stack.step, :1, :, 0].permute(1, 2, 0, 3).contiguous())], axis=2)
+        V = np.concatenate([W.bf16_bits(v[:1]), W.bf16_bits(stack.v[layer][: stack.step, :1, :, 0].permute(1, 2, 0, 3).contiguous())], axis=2)
+        del k, v
+        q = W.bf16_bits(stack.q[layer][stack.step - 1, :1].contiguous())
+        mode = oracle.MODE_LAZY if kind else oracle.MODE_FULL
+        oracle.decode_attn(q, K, V, mode, wl.w_sink, wl.w_recent)            # touch memory once
+        reps, t0 = 0, time.perf_counter()
+        while reps < 3 or (time.perf_counter() - t0 < 5.0 and reps < 50):
+            ref, _ = oracle.decode_attn(q, K, V, mode, wl.w_sink, wl.w_recent)
+            reps += 1
+        per_kind[kind] = (time.perf_counter() - t0) / reps
+        err = float(np.abs(stack.out[layer, 0].cpu().numpy().astype(np.float64) - ref[0]).max())
+        log("cpu_baseline: layer %d (%s) T=%d: %.4f s per sequence-step, max |gpu - oracle| = %.3g"
+            % (layer, "lazy" if kind else "full", T, per_kind[kind], err))
+        if err > 2e-3:
+            raise RuntimeError("GPU output of the timed run disagrees with the oracle: %g" % err)
+    n_lazy = sum(is_lazy)
+    per_token = (wl.n_layers - n_lazy) * per_kind.get(0, 0.0) + n_lazy * per_kind.get(1, 0.0)
+    return {
+        "value": 1.0 / per_token, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": "sequence 0 of one full and one lazy layer, one decode step each at T=%d, repeated >=3 times; "
+                  "extrapolated linearly to %d layers x %d sequences" % (T, wl.n_layers, wl.batch),
+    }
+
+
+def main():
+    args = parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only; --gpus %d is not supported (no collectives, no sharding)" % args.gpus,
+              file=sys.stderr)
+        return 2
+    import numpy as np
+    import torch
+
+    import lt_workloads as W
+    from paper_2410_13846_amd import lt
+
+    if not torch.cuda.is_available():
+        print("bench.py needs a GPU", file=sys.stderr)
+        return 2
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    wl = W.WORKLOADS[args.workload]
+    if args.n_lazy is not None:
+        wl = wl.scaled(n_lazy=args.n_lazy)
+    K, Wm = args.steps, args.warmup
+    log("workload %s: L=%d B=%d Hq=%d Hkv=%d n=%d window=%d+%d lazy=%d" % (
+        wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.context, wl.w_sink, wl.w_recent, wl.n_lazy))
+
+    # ---- identification: score every layer, select ------------------------------------------------
+    t0 = time.perf_counter()
+    ratios, score_ms = score_layers(lt, W, wl, dev)
+    t_sel = time.perf_counter()
+    is_lazy, _ = lt.select_lazy(ratios, wl.n_lazy)
+    select_us = (time.perf_counter() - t_sel) * 1e6
+    log("scoring + selection: %.1f s wall, lazy layers %s" % (time.perf_counter() - t0, list(np.nonzero(is_lazy)[0])))
+    if wl.bias == "planted" and list(np.nonzero(is_lazy)[0]) != W.planted_lazy_layers(wl):
+        raise RuntimeError("selection did not recover the planted lazy layers")
+    score_flops = 2.0 * wl.batch * wl.n_q_heads * wl.w_last * wl.context * wl.head_dim
+    score_bytes = wl.batch * wl.n_kv_heads * wl.context * wl.head_dim * 2.0
+    med_ms = float(np.median(score_ms))
+    scoring = {
+        "ms_per_layer": med_ms, "tflops": score_flops / med_ms / 1e9, "mfma_frac": score_flops / med_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+        "k_gbs": score_bytes / med_ms / 1e6, "hbm_frac": score_bytes / med_ms / 1e6 / HBM_PEAK_GBS, "select_us": select_us,
+        "w_last": wl.w_last, "ratio_min": min(ratios), "ratio_max": max(ratios),
+    }
+
+    # ---- decode -----------------------------------------------------------------------------------------
+    profile_pass = not args.no_profile_pass
+    total_steps = Wm + K + (K if profile_pass else 0)
+    stack = Stack(lt, W, wl, is_lazy, total_steps, dev, args.keys_full, args.keys_lazy)
+    log("stack ready: KV slab %.2f GB" % (stack.ctx.kv_slab.numel() / 1e9))
+    stack.run(Wm)
+    T_first = stack.tokens_now() + 1
+    elapsed = timed(stack, K)
+    T_last = stack.tokens_now()
+    ms_per_step = elapsed / K * 1e3
+    tokens_per_s = wl.batch * K / elapsed
+    T_mean = 0.5 * (T_first + T_last)
+    step_bytes = W.kv_bytes_per_step(wl, is_lazy, int(T_mean))
+    log("timed %d steps: %.3f ms/step, %.1f tokens/s, %.1f GB/s of KV" % (K, ms_per_step, tokens_per_s, step_bytes / ms_per_step / 1e6))
+
+    # ---- roofline of the dominant kernel: split decode over one full layer -----------------------------------
+    roofline = None
+    if profile_pass:
+        stack.ctx.profile_enable(True)
+        Tp_first = stack.tokens_now() + 1
+        elapsed_p = timed(stack, K)
+        Tp_mean = 0.5 * (Tp_first + stack.tokens_now())
+        stack.ctx.profile_enable(False)
+        kernel = lt.KERNEL_DECODE_FULL if sum(is_lazy) < wl.n_layers else lt.KERNEL_DECODE_LAZY
+        launches, total_ms = stack.ctx.profile_read(kernel)
+        per_kernel = {}
+        for name, kid in (("decode_full", lt.KERNEL_DECODE_FULL), ("decode_lazy", lt.KERNEL_DECODE_LAZY),
+                          ("merge", lt.KERNEL_MERGE), ("append", lt.KERNEL_APPEND)):
+            n, ms = stack.ctx.profile_read(kid)
+            per_kernel[name] = {"launches": n, "avg_us": (ms / n * 1e3) if n else None}
+        stored = Tp_mean if kernel == lt.KERNEL_DECODE_FULL else min(Tp_mean, wl.w_sink + wl.w_recent)
+        # algorithmic bytes of one launch (one layer, all sequences): stored K+V entries once, q in, out, appended K/V
+        per_seq = (2 * wl.n_kv_heads * wl.head_dim * 2) * stored + wl.n_q_heads * wl.head_dim * (2 + 4) \
+            + wl.n_kv_heads * wl.head_dim * 2 * 2
+        launch_bytes = wl.batch * per_seq
+        avg_ms = total_ms / max(launches, 1)
+        achieved = launch_bytes / avg_ms / 1e6
+        roofline = {
+            "bound": "hbm", "kernel": "lt_decode_partial_kernel (full layers)" if kernel == lt.KERNEL_DECODE_FULL
+            else "lt_decode_partial_kernel (lazy layers)",
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": read_traffic(wl.name), "launches": launches, "avg_launch_us": avg_ms * 1e3,
+            "bytes_per_launch": launch_bytes, "ms_per_step_with_events": elapsed_p / K * 1e3, "kernels": per_kernel,
+        }
+        log("roofline pass: %d launches, %.1f us each, %.1f GB/s (%.1f%% of 8 TB/s)" % (launches, avg_ms * 1e3, achieved, achieved / 80))
+
+    # ---- oracle on host cores --------------------------------------------------------------------------------
+    cpu = None if args.no_cpu_baseline else cpu_baseline(W, wl, stack, [int(x) for x in is_lazy])
+    stack.close()
+    del stack
+    torch.cuda.empty_cache()
+
+    # ---- all-full comparison: attention-time speedup of the hybrid stack -------------------------------------------
+    speedup = None
+    if not args.no_speedup and wl.n_lazy > 0:
+        steps0 = min(K, 16)
+        full = Stack(lt, W, wl, [0] * wl.n_layers, Wm + steps0, dev, args.keys_full, args.keys_lazy)
+        full.run(Wm)
+        e0 = timed(full, steps0)
+        full.close()
+        del full
+        ms0 = e0 / steps0 * 1e3
+        window = wl.w_sink + wl.w_recent
+        f = wl.n_lazy / wl.n_layers
+        speedup = {"ms_per_step_all_full": ms0, "measured": ms0 / ms_per_step,
+                   "byte_ratio_ideal": 1.0 / (1.0 - f + f * min(window, T_mean) / T_mean), "lazy_fraction": f}
+        log("all-full stack: %.3f ms/step -> speedup %.3fx" % (ms0, ms0 / ms_per_step))
+
+    line = {
+        "metric": "hybrid decode-attn tokens/s + achieved HBM GB/s (% peak), 1 MI355X",
+        "value": tokens_per_s, "unit": "tokens/s", "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16 storage, fp32 accumulate", "data": "synthetic",
+        "config": {"workload": wl.name, "layers": wl.n_layers, "lazy_layers": int(sum(is_lazy)), "batch": wl.batch,
+                   "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads, "head_dim": wl.head_dim, "context": wl.context,
+                   "w_sink": wl.w_sink, "w_recent": wl.w_recent, "tokens_first_step": T_first, "tokens_last_step": T_last},
+        "kv_gbs": step_bytes / ms_per_step / 1e6, "kv_hbm_frac": step_bytes / ms_per_step / 1e6 / HBM_PEAK_GBS,
+        "roofline": roofline, "cpu_baseline": cpu, "scoring": scoring, "speedup_hybrid_vs_all_full": speedup,
+    }
+    print(json.dumps(line))
+    return 0
+
+
+def read_traffic(workload):
+    """HBM bytes per launch of the dominant kernel, from the committed rocprofv3 --pmc summary (None if absent)."""
+    path = os.path.join(ROOT, "profiles", "decode_full_%s_traffic.txt" % workload)
+    try:
+        with open(path) as f:
+            for ln in f:
+                if ln.startswith("traffic_bytes_per_launch:"):
+                    return float(ln.split(":", 1)[1])
+    except OSError:
+        pass
+    return None
+
+
+if __name__ == "__main__":
+    sys.exit(main())

@@ -174,6 +174,19 @@ def decode_qkv(wl: Workload, layer: int, step: int, device="cpu"):
     return _bias_queries(wl, layer, q), k, v
 
 
+def decode_qkv_block(wl: Workload, layer: int, first_step: int, n_steps: int, device="cpu"):
+    """Inputs of n_steps consecutive decode steps of one layer, drawn in one go (benchmark use):
+    q [S,B,Hq,d], k/v [S,B,Hkv,1,d], bf16.  Not the same numbers as decode_qkv."""
+    q = randn_bf16((n_steps, wl.batch, wl.n_q_heads, wl.head_dim), seed_for(wl, layer, first_step, stream=13), device)
+    k = randn_bf16((n_steps, wl.batch, wl.n_kv_heads, 1, wl.head_dim), seed_for(wl, layer, first_step, stream=11), device)
+    v = randn_bf16((n_steps, wl.batch, wl.n_kv_heads, 1, wl.head_dim), seed_for(wl, layer, first_step, stream=12), device)
+    c = _bias_coeff(wl, layer)
+    if c > 0.0:
+        u = (_bias_direction(wl, layer, device) * c).repeat_interleave(wl.group, dim=1)     # [B,Hq,d]
+        q = (q.float() + u.unsqueeze(0)).to(torch.bfloat16)
+    return q, k, v
+
+
 def kv_bytes_per_step(wl: Workload, is_lazy, total_tokens: int) -> int:
     """Algorithmic K+V bytes one decode step reads: every stored entry once (2 tensors, bf16)."""
     per_token = 2 * wl.n_kv_heads * wl.head_dim * 2

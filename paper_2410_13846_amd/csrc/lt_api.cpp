@@ -90,15 +90,22 @@ struct lt_ctx {
 
 namespace {
 
-// Keys per workgroup: enough workgroups to cover the chip several times, but not so small that
-// the partial results rival the KV bytes.  `streams` = B * Hkv independent key streams.
+// Keys per workgroup.  The decode kernel keeps kResidentBlocks workgroups on the chip at once
+// (3 per compute unit at its register budget); a launch whose workgroup count is just above a
+// multiple of that leaves the chip idle in a tail, so the split count per key stream is chosen
+// to fill whole rounds.  `streams` = B * Hkv independent key streams.
 int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t splits_cap)
 {
-    const int64_t target_blocks = 256 * 8;                         // 256 compute units, several workgroups each
-    int64_t keys = ceil_div(stored * streams, target_blocks);
-    keys = ceil_div(keys, ltk::kKeyGranule) * ltk::kKeyGranule;
-    const int64_t lo = lazy ? 128 : 256, hi = 2048;
-    keys = std::min(std::max(keys, lo), hi);
+    constexpr int64_t kResidentBlocks = 256 * 3;
+    const int64_t lo = lazy ? 128 : 256;                            // not so small that partial results rival the KV bytes
+    int64_t splits = std::max<int64_t>(kResidentBlocks / streams, 1);
+    int64_t keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
+    if (keys > 4096) {                                              // long streams: several full rounds
+        const int64_t rounds = ceil_div(keys, 4096);
+        splits *= rounds;
+        keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
+    }
+    keys = std::max(keys, lo);
     while (ceil_div(stored, keys) > splits_cap) keys += ltk::kKeyGranule;
     return (int)keys;
 }

@@ -38,7 +38,15 @@ __device__ __forceinline__ float row16_allsum(float x)
     return x;
 }
 
-__device__ __forceinline__ uint4 load16(const uint16_t *p) { return *reinterpret_cast<const uint4 *>(p); }
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;   // 16 bytes as one register quad
+
+__device__ __forceinline__ u32x4_t load16(const uint16_t *p) { return *reinterpret_cast<const u32x4_t *>(p); }
+
+// K and V are read exactly once per decode step: stream them past the caches.
+__device__ __forceinline__ u32x4_t load16_stream(const uint16_t *p)
+{
+    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+}
 
 // ---------------------------------------------------------------------------------------------
 // append: one thread moves 16 bytes of K and 16 bytes of V.
@@ -62,8 +70,8 @@ __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
     }
     const int64_t src = (((int64_t)b * a.n_kv_heads + g) * a.n_new + j) * kHeadDim + c * 8;
     const int64_t dst = (int64_t)b * a.stride_b + (int64_t)g * a.stride_h + slot * kHeadDim + c * 8;
-    *reinterpret_cast<uint4 *>(a.k_cache + dst) = load16(a.k_new + src);
-    *reinterpret_cast<uint4 *>(a.v_cache + dst) = load16(a.v_new + src);
+    *reinterpret_cast<u32x4_t *>(a.k_cache + dst) = load16(a.k_new + src);
+    *reinterpret_cast<u32x4_t *>(a.v_cache + dst) = load16(a.v_new + src);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -77,8 +85,8 @@ __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
 // and wavefronts are merged once at the end.
 // ---------------------------------------------------------------------------------------------
 struct Tile {
-    uint4 k[4];
-    uint4 v[4];
+    u32x4_t k[4];
+    u32x4_t v[4];
 };
 
 __device__ __forceinline__ void load_tile(Tile &t, const uint16_t *kb, const uint16_t *vb, int key0, int sub, int chunk,
@@ -89,8 +97,8 @@ __device__ __forceinline__ void load_tile(Tile &t, const uint16_t *kb, const uin
         int key = key0 + 4 * i + sub;
         key = key < last_key ? key : last_key;                      // clamp: masked later
         const int64_t off = (int64_t)key * kHeadDim + chunk * 8;
-        t.k[i] = load16(kb + off);
-        t.v[i] = load16(vb + off);
+        t.k[i] = load16_stream(kb + off);
+        t.v[i] = load16_stream(vb + off);
     }
 }
 
@@ -111,10 +119,10 @@ __device__ __forceinline__ void process_tile(const Tile &t, const uint32_t (&qf)
         const bool valid = key0 + 4 * i + sub < end_key;
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            float x = dot2_bf16(t.k[i].x, qf[h][0], 0.f);
-            x = dot2_bf16(t.k[i].y, qf[h][1], x);
-            x = dot2_bf16(t.k[i].z, qf[h][2], x);
-            x = dot2_bf16(t.k[i].w, qf[h][3], x);
+            float x = dot2_bf16(t.k[i][0], qf[h][0], 0.f);
+            x = dot2_bf16(t.k[i][1], qf[h][1], x);
+            x = dot2_bf16(t.k[i][2], qf[h][2], x);
+            x = dot2_bf16(t.k[i][3], qf[h][3], x);
             x = row16_allsum(x) * scale_log2e;
             s[i][h] = valid ? x : -INFINITY;
         }
@@ -150,10 +158,8 @@ __device__ __forceinline__ void process_tile(const Tile &t, const uint32_t (&qf)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float vf[8];
-        vf[0] = bf16_lo(t.v[i].x); vf[1] = bf16_hi(t.v[i].x);
-        vf[2] = bf16_lo(t.v[i].y); vf[3] = bf16_hi(t.v[i].y);
-        vf[4] = bf16_lo(t.v[i].z); vf[5] = bf16_hi(t.v[i].z);
-        vf[6] = bf16_lo(t.v[i].w); vf[7] = bf16_hi(t.v[i].w);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { vf[2 * e] = bf16_lo(t.v[i][e]); vf[2 * e + 1] = bf16_hi(t.v[i][e]); }
 #pragma unroll
         for (int h = 0; h < G; ++h)
 #pragma unroll
@@ -182,8 +188,8 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_partial_kernel(Decod
     uint32_t qf[G][4];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        const uint4 u = load16(a.q + ((int64_t)b * a.n_q_heads + g * G + h) * kHeadDim + chunk * 8);
-        qf[h][0] = u.x; qf[h][1] = u.y; qf[h][2] = u.z; qf[h][3] = u.w;
+        const u32x4_t u = load16(a.q + ((int64_t)b * a.n_q_heads + g * G + h) * kHeadDim + chunk * 8);
+        qf[h][0] = u[0]; qf[h][1] = u[1]; qf[h][2] = u[2]; qf[h][3] = u[3];
     }
 
     RowState<G> st;
