@@ -1,9 +1,9 @@
 #!/usr/bin/env python3
 """Benchmark of the LightTransfer hot path on one MI355X.
 
-A step is one decode step of the whole hybrid stack: for every layer, lt_append_kv of the new
-token's K/V and lt_decode_attn over that layer's cache (full layers: the whole growing cache;
-lazy layers: the sink + recent ring).  Before the timed region the stack is set up the way the
+A step is one decode step of the whole hybrid stack: for every layer, lt_decode_step = append of
+the new token's K/V + attention over that layer's cache + merge of the key-axis splits, in one
+launch (full layers: the whole growing cache; lazy layers: the sink + recent ring).  Before the timed region the stack is set up the way the
 method prescribes: lt_lazy_ratio scores every layer on the last w_last prompt queries,
 lt_select_lazy picks the lazy layers, and the prompt K/V are appended; those calls are timed
 separately and reported under "scoring".  All inputs are seeded synthetic tensors resident in
@@ -87,12 +87,9 @@ class Stack:
         for _ in range(n_steps):
             s = self.step
             for layer, (qp, qs, kp, vp, kvs, op) in enumerate(self._ptrs):
-                st = lib.lt_append_kv(h, layer, kp + s * kvs, vp + s * kvs, 1, stream)
+                st = lib.lt_decode_step(h, layer, qp + s * qs, kp + s * kvs, vp + s * kvs, op, None, stream)
                 if st != 0:
-                    raise self.lt.LtError(st, "lt_append_kv")
-                st = lib.lt_decode_attn(h, layer, qp + s * qs, op, None, stream)
-                if st != 0:
-                    raise self.lt.LtError(st, "lt_decode_attn")
+                    raise self.lt.LtError(st, "lt_decode_step")
             self.step += 1
 
     def tokens_now(self):
@@ -244,8 +241,7 @@ def main():
         kernel = lt.KERNEL_DECODE_FULL if sum(is_lazy) < wl.n_layers else lt.KERNEL_DECODE_LAZY
         launches, total_ms = stack.ctx.profile_read(kernel)
         per_kernel = {}
-        for name, kid in (("decode_full", lt.KERNEL_DECODE_FULL), ("decode_lazy", lt.KERNEL_DECODE_LAZY),
-                          ("merge", lt.KERNEL_MERGE), ("append", lt.KERNEL_APPEND)):
+        for name, kid in (("decode_full", lt.KERNEL_DECODE_FULL), ("decode_lazy", lt.KERNEL_DECODE_LAZY)):
             n, ms = stack.ctx.profile_read(kid)
             per_kernel[name] = {"launches": n, "avg_us": (ms / n * 1e3) if n else None}
         stored = Tp_mean if kernel == lt.KERNEL_DECODE_FULL else min(Tp_mean, wl.w_sink + wl.w_recent)
@@ -256,8 +252,8 @@ def main():
         avg_ms = total_ms / max(launches, 1)
         achieved = launch_bytes / avg_ms / 1e6
         roofline = {
-            "bound": "hbm", "kernel": "lt_decode_partial_kernel (full layers)" if kernel == lt.KERNEL_DECODE_FULL
-            else "lt_decode_partial_kernel (lazy layers)",
+            "bound": "hbm", "kernel": "lt_decode_kernel<4,0> (full layers)" if kernel == lt.KERNEL_DECODE_FULL
+            else "lt_decode_kernel<4,1> (lazy layers)",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": read_traffic(wl.name), "launches": launches, "avg_launch_us": avg_ms * 1e3,
             "bytes_per_launch": launch_bytes, "ms_per_step_with_events": elapsed_p / K * 1e3, "kernels": per_kernel,

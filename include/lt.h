@@ -74,8 +74,10 @@ typedef struct lt_config {
  * is_lazy: host, L entries, non-zero = lazy. */
 size_t lt_kv_bytes(const lt_config *cfg, const uint8_t *is_lazy);
 
-/* Bytes of device workspace lt_decode_attn needs (partial results of the split over the key
- * axis; fp32).  Returns 0 on invalid arguments. */
+/* Bytes of device workspace lt_decode_attn / lt_decode_step need (fp32 partial results of the
+ * split over the key axis, and one counter per (sequence, KV head)).  The first decode call on a
+ * context zeroes the counters on its stream; use one stream at a time per context.  Returns 0 on
+ * invalid arguments. */
 size_t lt_workspace_bytes(const lt_config *cfg);
 
 /* Create the host-side state of a hybrid stack over caller-owned device memory.
@@ -152,8 +154,17 @@ lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void
  *   q        device, bf16 [B][Hq][128]
  *   out      device, fp32 [B][Hq][128]: sum_j softmax_j(softmax_scale * q.k_j) v_j over the stored entries
  *   lse_out  device, fp32 [B][Hq]: natural-log of the softmax denominator; may be NULL
- * LT_ERR_STATE if the layer is empty. */
+ * One launch: workgroups each take a range of the stored entries and the last one to finish
+ * merges the ranges by their log-sum-exp.  LT_ERR_STATE if the layer is empty. */
 lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream);
+
+/* One decoding step of a layer in a single launch: lt_append_kv of one token followed by
+ * lt_decode_attn, with the same result and the same effect on the cache and the token count.
+ *   k_new, v_new  device, bf16 [B][Hkv][128], the K/V of the token being generated
+ * The decode kernel takes the new token from k_new / v_new and stores it into its cache slot on
+ * the way.  LT_ERR_CAPACITY as for lt_append_kv; on error nothing is enqueued or counted. */
+lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out,
+                         float *lse_out, void *stream);
 
 /* ---- tuning and measurement ---------------------------------------------------------------- */
 
@@ -161,8 +172,7 @@ lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, 
  * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
 lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
 
-enum { LT_KERNEL_DECODE_FULL = 0, LT_KERNEL_DECODE_LAZY = 1, LT_KERNEL_MERGE = 2, LT_KERNEL_APPEND = 3,
-       LT_KERNEL_COUNT = 4 };
+enum { LT_KERNEL_DECODE_FULL = 0, LT_KERNEL_DECODE_LAZY = 1, LT_KERNEL_APPEND = 2, LT_KERNEL_COUNT = 3 };
 
 /* Bracket every later kernel launch of this context with a pair of HIP events on the launch
  * stream (on != 0), or stop doing so (on == 0).  Enabling discards earlier measurements. */

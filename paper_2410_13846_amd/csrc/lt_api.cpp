@@ -60,7 +60,7 @@ int64_t max_splits(const lt_config *c)
 {
     const int64_t full = ceil_div(c->max_tokens, kMinKeysFull);
     const int64_t lazy = ceil_div(std::max<int64_t>(window_of(c), 1), kMinKeysLazy);
-    return std::max<int64_t>(std::max(full, lazy), 1);
+    return std::min<int64_t>(std::max<int64_t>(std::max(full, lazy), 1), ltk::kMaxSplits);
 }
 
 struct Layer {
@@ -81,6 +81,8 @@ struct lt_ctx {
     lt_config cfg;
     std::vector<Layer> layers;
     float *part_acc = nullptr, *part_ml = nullptr;
+    unsigned int *tickets = nullptr;           // one counter per (sequence, KV head), zero between launches
+    bool tickets_ready = false;                // zeroed by the first decode call (lt_create enqueues nothing)
     int64_t splits_cap = 0;
     int32_t keys_full = 0, keys_lazy = 0;      // 0 = heuristic
     bool profiling = false;
@@ -106,7 +108,7 @@ int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t sp
         keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
     }
     keys = std::max(keys, lo);
-    while (ceil_div(stored, keys) > splits_cap) keys += ltk::kKeyGranule;
+    keys = std::max(keys, ceil_div(ceil_div(stored, splits_cap), ltk::kKeyGranule) * ltk::kKeyGranule);
     return (int)keys;
 }
 
@@ -158,7 +160,8 @@ size_t lt_workspace_bytes(const lt_config *cfg)
 {
     if (!config_ok(cfg) || config_shape(cfg) != LT_OK) return 0;
     const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)max_splits(cfg);
-    return align_up(rows * ltk::kHeadDim * sizeof(float)) + align_up(rows * 2 * sizeof(float));
+    return align_up(rows * ltk::kHeadDim * sizeof(float)) + align_up(rows * 2 * sizeof(float)) +
+           align_up((size_t)cfg->batch * cfg->n_kv_heads * sizeof(unsigned int));
 }
 
 lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab, size_t kv_bytes, void *workspace,
@@ -195,7 +198,10 @@ lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab,
     ctx->splits_cap = max_splits(cfg);
     const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)ctx->splits_cap;
     ctx->part_acc = static_cast<float *>(workspace);
-    ctx->part_ml = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(rows * ltk::kHeadDim * sizeof(float)));
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    ctx->part_ml = reinterpret_cast<float *>(ws + align_up(rows * ltk::kHeadDim * sizeof(float)));
+    ctx->tickets = reinterpret_cast<unsigned int *>(ws + align_up(rows * ltk::kHeadDim * sizeof(float)) +
+                                                    align_up(rows * 2 * sizeof(float)));
     *out = ctx;
     return LT_OK;
 }
@@ -353,18 +359,36 @@ lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void
     return LT_OK;
 }
 
-lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream)
+// Ring / growing-cache slot of the token at absolute position p, or -1 if a lazy layer drops it.
+static int64_t slot_of(const lt_config &c, const Layer &l, int64_t p)
+{
+    if (!l.lazy || p < c.w_sink) return p;
+    if (c.w_recent == 0) return -1;
+    return c.w_sink + (p - c.w_sink) % c.w_recent;
+}
+
+// One launch: optional on-the-fly append of this step's token, split attention, merge.
+static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out,
+                               float *lse_out, void *stream)
 {
     if (ctx == nullptr || q == nullptr || out == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
-    if (((uintptr_t)q % 16) != 0) return LT_ERR_INVALID_ARG;
-    const Layer &l = ctx->layers[layer];
-    const int64_t stored = std::min(l.total, l.capacity);
-    if (stored <= 0) return LT_ERR_STATE;
+    if (((uintptr_t)q % 16) != 0 || ((uintptr_t)k_new % 16) != 0 || ((uintptr_t)v_new % 16) != 0) return LT_ERR_INVALID_ARG;
+    Layer &l = ctx->layers[layer];
     const lt_config &c = ctx->cfg;
+    const bool fused = k_new != nullptr;
+    if (fused && (l.total + 1 > kMaxTokens || (!l.lazy && l.total + 1 > l.capacity))) return LT_ERR_CAPACITY;
+    const int64_t total = l.total + (fused ? 1 : 0);
+    const int64_t stored = std::min(total, l.capacity);
+    if (stored <= 0) return LT_ERR_STATE;
 
     ltk::DecodeArgs a{};
     a.k_cache = l.k;
     a.v_cache = l.v;
+    const int64_t slot = fused ? slot_of(c, l, l.total) : -1;
+    a.k_new = slot >= 0 ? static_cast<const uint16_t *>(k_new) : nullptr;     // a dropped token is simply not stored
+    a.v_new = slot >= 0 ? static_cast<const uint16_t *>(v_new) : nullptr;
+    a.new_slot = (int32_t)slot;
+    a.tickets = ctx->tickets;
     a.q = static_cast<const uint16_t *>(q);
     a.part_acc = ctx->part_acc;
     a.part_ml = ctx->part_ml;
@@ -383,15 +407,28 @@ lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, 
     a.scale_log2e = c.softmax_scale * kLog2e;
     a.lazy_tag = l.lazy ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
+    if (!ctx->tickets_ready) {
+        if (ltk::zero_tickets(ctx->tickets, c.batch * c.n_kv_heads, s) != hipSuccess) return LT_ERR_HIP;
+        ctx->tickets_ready = true;
+    }
     {
         ScopedEvents ev(ctx, s, l.lazy ? LT_KERNEL_DECODE_LAZY : LT_KERNEL_DECODE_FULL);
-        if (ltk::decode_partial(a, s) != hipSuccess) return LT_ERR_HIP;
+        if (ltk::decode(a, s) != hipSuccess) return LT_ERR_HIP;
     }
-    {
-        ScopedEvents ev(ctx, s, LT_KERNEL_MERGE);
-        if (ltk::decode_merge(a, s) != hipSuccess) return LT_ERR_HIP;
-    }
+    l.total = total;
     return LT_OK;
+}
+
+lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream)
+{
+    return launch_decode(ctx, layer, q, nullptr, nullptr, out, lse_out, stream);
+}
+
+lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out,
+                         float *lse_out, void *stream)
+{
+    if (k_new == nullptr || v_new == nullptr) return LT_ERR_INVALID_ARG;
+    return launch_decode(ctx, layer, q, k_new, v_new, out, lse_out, stream);
 }
 
 // ---- tuning and measurement --------------------------------------------------------------------

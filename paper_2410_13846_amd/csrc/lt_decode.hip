@@ -1,5 +1,6 @@
-// Decode-side kernels for gfx950: KV append (growing cache / sink+recent ring), split decode
-// attention over the key axis, and the log-sum-exp merge of the splits.
+// Decode-side kernels for gfx950: KV append (growing cache / sink+recent ring) and split decode
+// attention over the key axis with the log-sum-exp merge of the splits done by the workgroup
+// that finishes last, so one decode step of a layer is a single launch.
 //
 // Attention of one query over a set of keys does not depend on the order of the keys, so a
 // lazy layer's ring is read as a plain array of `stored` entries and both layer kinds share
@@ -22,6 +23,8 @@ __device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+constexpr float kLn2 = 0.69314718055994530942f;
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x)
 {
@@ -40,13 +43,22 @@ __device__ __forceinline__ float row16_allsum(float x)
 
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;   // 16 bytes as one register quad
 
-__device__ __forceinline__ u32x4_t load16(const uint16_t *p) { return *reinterpret_cast<const u32x4_t *>(p); }
+// Every pointer the kernels see is device memory: say so, or a pointer chosen at run time
+// between two buffers is accessed with the slower generic (flat) instructions.
+typedef const __attribute__((address_space(1))) u32x4_t *global_quad_ptr;
+typedef __attribute__((address_space(1))) u32x4_t *global_quad_wptr;
+
+__device__ __forceinline__ u32x4_t load16(const uint16_t *p) { return *(global_quad_ptr)p; }
 
 // K and V are read exactly once per decode step: stream them past the caches.
-__device__ __forceinline__ u32x4_t load16_stream(const uint16_t *p)
-{
-    return __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-}
+__device__ __forceinline__ u32x4_t load16_stream(const uint16_t *p) { return __builtin_nontemporal_load((global_quad_ptr)p); }
+
+__device__ __forceinline__ void store16(uint16_t *p, u32x4_t v) { *(global_quad_wptr)p = v; }
+
+// Device-scope relaxed atomic store / load: coherent between workgroups anywhere on the chip
+// without flushing or invalidating a cache.
+__device__ __forceinline__ void publish(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float observe(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
 // ---------------------------------------------------------------------------------------------
 // append: one thread moves 16 bytes of K and 16 bytes of V.
@@ -70,8 +82,8 @@ __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
     }
     const int64_t src = (((int64_t)b * a.n_kv_heads + g) * a.n_new + j) * kHeadDim + c * 8;
     const int64_t dst = (int64_t)b * a.stride_b + (int64_t)g * a.stride_h + slot * kHeadDim + c * 8;
-    *reinterpret_cast<u32x4_t *>(a.k_cache + dst) = load16(a.k_new + src);
-    *reinterpret_cast<u32x4_t *>(a.v_cache + dst) = load16(a.v_new + src);
+    store16(a.k_cache + dst, load16(a.k_new + src));
+    store16(a.v_cache + dst, load16(a.v_new + src));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -89,16 +101,52 @@ struct Tile {
     u32x4_t v[4];
 };
 
+// new_slot (or -1) is the cache entry of the token generated in this step when the append is
+// fused into the decode: its K/V are read from the caller's k_new / v_new instead of the cache.
+// Every path issues the same eight loads in the same order, so the wait counts of the software
+// pipeline stay exact; only the addresses differ, and only in the one tile that holds new_slot.
 __device__ __forceinline__ void load_tile(Tile &t, const uint16_t *kb, const uint16_t *vb, int key0, int sub, int chunk,
-                                          int last_key)
+                                          int last_key, int new_slot, const uint16_t *k_new, const uint16_t *v_new)
 {
+    const uint16_t *kp[4], *vp[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int key = key0 + 4 * i + sub;
         key = key < last_key ? key : last_key;                      // clamp: masked later
         const int64_t off = (int64_t)key * kHeadDim + chunk * 8;
-        t.k[i] = load16_stream(kb + off);
-        t.v[i] = load16_stream(vb + off);
+        kp[i] = kb + off;
+        vp[i] = vb + off;
+    }
+    if (new_slot >= key0 && new_slot < key0 + 16) {                 // wave-uniform, true for one tile of one workgroup
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int key = key0 + 4 * i + sub;
+            key = key < last_key ? key : last_key;
+            if (key == new_slot) { kp[i] = k_new + chunk * 8; vp[i] = v_new + chunk * 8; }
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        t.k[i] = load16_stream(kp[i]);
+        t.v[i] = load16_stream(vp[i]);
+    }
+}
+
+// The fused append: the lanes that hold the new token write it into its cache entry.  A clamped
+// lane may repeat the store with the same bytes.
+__device__ __forceinline__ void store_new_token(const Tile &t, uint16_t *kb, uint16_t *vb, int key0, int sub, int chunk,
+                                                int last_key, int new_slot)
+{
+    if (new_slot < key0 || new_slot >= key0 + 16) return;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        int key = key0 + 4 * i + sub;
+        key = key < last_key ? key : last_key;
+        if (key == new_slot) {
+            const int64_t off = (int64_t)key * kHeadDim + chunk * 8;
+            store16(kb + off, t.k[i]);
+            store16(vb + off, t.v[i]);
+        }
     }
 }
 
@@ -167,23 +215,38 @@ __device__ __forceinline__ void process_tile(const Tile &t, const uint32_t (&qf)
     }
 }
 
+// LAZY_TAG only gives full and lazy layers distinct kernel names in profiles.
 template <int G, int LAZY_TAG>
-__global__ __launch_bounds__(kDecodeThreads) void lt_decode_partial_kernel(DecodeArgs a)
+__global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
 {
     constexpr int kWaves = kDecodeThreads / 64;
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
     __shared__ float sh_acc[kWaves][G][kHeadDim];
+    __shared__ int sh_is_last;
+    __shared__ float sh_merge_m[G][kMaxSplits];
+    __shared__ float sh_merge_l[G][kMaxSplits];
 
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tile indices stay in SGPRs
     const int sub = lane >> 4, chunk = lane & 15;
 
     const int begin_key = split * a.keys_per_block;
     const int end_key = min(a.stored, begin_key + a.keys_per_block);
     const int n_tiles = (end_key - begin_key + 15) >> 4;
-    const uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
-    const uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
+    uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
+    uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
+    // fused append: the one tile that holds new_slot takes the token from k_new / v_new
+    const int new_slot = a.k_new != nullptr ? a.new_slot : -1;
+    const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
+    const uint16_t *k_new = a.k_new + new_off;
+    const uint16_t *v_new = a.v_new + new_off;
+    auto fetch = [&](Tile &t, int key0) { load_tile(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new); };
+    auto consume = [&](const Tile &t, int key0, RowState<G> &st, const uint32_t (&qf)[G][4]) {
+        store_new_token(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot);
+        process_tile<G>(t, qf, st, key0, sub, end_key, a.scale_log2e);
+    };
 
     uint32_t qf[G][4];
 #pragma unroll
@@ -202,18 +265,17 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_partial_kernel(Decod
     }
 
     // Wavefront w takes tiles w, w+4, ...; two tile buffers alternate so the loads of the next
-    // tile are in flight while the current one is consumed.
+    // tile are in flight while the current one is consumed.  Every fetch is unconditional (keys
+    // past the range are clamped to its last key and never consumed): with a fixed number of
+    // loads between a fetch and its use the wait counts are exact, and a tile is consumed while
+    // the following one is still arriving.
     Tile t0, t1;
-    int t = wave;
-    if (t < n_tiles) load_tile(t0, kb, vb, begin_key + 16 * t, sub, chunk, end_key - 1);
-    while (t < n_tiles) {
-        if (t + kWaves < n_tiles) load_tile(t1, kb, vb, begin_key + 16 * (t + kWaves), sub, chunk, end_key - 1);
-        process_tile<G>(t0, qf, st, begin_key + 16 * t, sub, end_key, a.scale_log2e);
-        t += kWaves;
-        if (t >= n_tiles) break;
-        if (t + kWaves < n_tiles) load_tile(t0, kb, vb, begin_key + 16 * (t + kWaves), sub, chunk, end_key - 1);
-        process_tile<G>(t1, qf, st, begin_key + 16 * t, sub, end_key, a.scale_log2e);
-        t += kWaves;
+    fetch(t0, begin_key + 16 * wave);
+    for (int t = wave; t < n_tiles; t += 2 * kWaves) {
+        fetch(t1, begin_key + 16 * (t + kWaves));
+        consume(t0, begin_key + 16 * t, st, qf);
+        fetch(t0, begin_key + 16 * (t + 2 * kWaves));
+        if (t + kWaves < n_tiles) consume(t1, begin_key + 16 * (t + kWaves), st, qf);
     }
 
     // Merge the four rows of the wavefront.
@@ -245,7 +307,9 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_partial_kernel(Decod
     }
     __syncthreads();
 
-    // Merge the wavefronts and store this split's partial result.
+    // Merge the wavefronts.  With a single split this is the final result; otherwise store the
+    // split's partial result (un-normalised accumulator, running max in log2 units, sum).
+    const bool single = a.n_splits == 1;
     for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kDecodeThreads) {
         const int h = idx / kHeadDim, dim = idx % kHeadDim;
         float mx = sh_m[0][h];
@@ -258,43 +322,87 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_partial_kernel(Decod
             l += wgt * sh_l[w][h];
             o += wgt * sh_acc[w][h][dim];
         }
-        const int64_t row = ((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + split;
-        a.part_acc[row * kHeadDim + dim] = o;
-        if (dim == 0) { a.part_ml[row * 2] = mx; a.part_ml[row * 2 + 1] = l; }
+        const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
+        if (single) {
+            a.out[head * kHeadDim + dim] = o / l;
+            if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
+        } else {
+            const int64_t row = head * a.n_splits + split;
+            publish(&a.part_acc[row * kHeadDim + dim], o);
+            if (dim == 0) { publish(&a.part_ml[row * 2], mx); publish(&a.part_ml[row * 2 + 1], l); }
+        }
     }
+    if (single) return;
+
+    // The workgroup that takes the last ticket of its (sequence, KV head) merges all splits:
+    // softmax over a union of disjoint key sets is the sum of the per-set results weighted by
+    // exp(max_c - max) * l_c.  Partial results travel through device-scope atomic stores and
+    // loads, which are coherent across the chip's L2 slices on their own; what is left to do is
+    // ordering: our stores complete (workgroup release = wait for the store acknowledgements),
+    // then the ticket is taken, and the merge loads are issued only after the last ticket.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    unsigned int *ticket = a.tickets + (int64_t)b * a.n_kv_heads + g;
+    if (threadIdx.x == 0) {
+        const unsigned int t_mine = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_is_last = (t_mine == (unsigned int)(a.n_splits - 1)) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!sh_is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    // Phase 1: every (head, split) pair's running max and sum into LDS, one load round trip.
+    for (int idx = threadIdx.x; idx < G * a.n_splits; idx += kDecodeThreads) {
+        const int h = idx / a.n_splits, c = idx % a.n_splits;
+        const float *ml = a.part_ml + (((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + c) * 2;
+        sh_merge_m[h][c] = observe(ml);
+        sh_merge_l[h][c] = observe(ml + 1);
+    }
+    __syncthreads();
+    // Phase 2: one thread per (head, dim); the partial accumulators are fetched eight splits at
+    // a time so the loads overlap instead of paying one memory latency per split.
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kDecodeThreads) {
+        const int h = idx / kHeadDim, dim = idx % kHeadDim;
+        const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
+        const float *acc = a.part_acc + head * a.n_splits * kHeadDim + dim;
+        float mx = -INFINITY;
+        for (int c = 0; c < a.n_splits; ++c) mx = fmaxf(mx, sh_merge_m[h][c]);
+        float l = 0.f, o = 0.f;
+        for (int c0 = 0; c0 < a.n_splits; c0 += 8) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int c = min(c0 + u, a.n_splits - 1);
+                v[u] = observe(acc + (int64_t)c * kHeadDim);
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (c0 + u < a.n_splits) {
+                    const float wgt = fast_exp2(sh_merge_m[h][c0 + u] - mx);
+                    l += wgt * sh_merge_l[h][c0 + u];
+                    o += wgt * v[u];
+                }
+            }
+        }
+        a.out[head * kHeadDim + dim] = o / l;
+        if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
+    }
+    if (threadIdx.x == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
 }
 
-// ---------------------------------------------------------------------------------------------
-// merge of the splits: softmax over a union of disjoint key sets is the weighted sum of the
-// per-set results with weights exp(max_c - max) * l_c.
-// ---------------------------------------------------------------------------------------------
-__global__ __launch_bounds__(kHeadDim) void lt_decode_merge_kernel(DecodeArgs a)
+__global__ void lt_zero_tickets_kernel(unsigned int *tickets, int n)
 {
-    const int h = blockIdx.x, b = blockIdx.y, dim = threadIdx.x;
-    const int64_t row0 = ((int64_t)b * a.n_q_heads + h) * a.n_splits;
-    const float *ml = a.part_ml + row0 * 2;
-    const float *acc = a.part_acc + row0 * kHeadDim;
-    float mx = -INFINITY;
-    for (int c = 0; c < a.n_splits; ++c) mx = fmaxf(mx, ml[2 * c]);
-    float l = 0.f, o = 0.f;
-    for (int c = 0; c < a.n_splits; ++c) {
-        const float wgt = fast_exp2(ml[2 * c] - mx);
-        l += wgt * ml[2 * c + 1];
-        o += wgt * acc[(int64_t)c * kHeadDim + dim];
-    }
-    a.out[((int64_t)b * a.n_q_heads + h) * kHeadDim + dim] = o / l;
-    if (a.lse != nullptr && dim == 0)
-        a.lse[(int64_t)b * a.n_q_heads + h] = (mx + log2f(l)) * 0.69314718055994530942f;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) tickets[i] = 0u;
 }
 
 template <int G>
-hipError_t launch_partial(const DecodeArgs &a, hipStream_t stream)
+hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
     if (a.lazy_tag)
-        hipLaunchKernelGGL((lt_decode_partial_kernel<G, 1>), grid, dim3(kDecodeThreads), 0, stream, a);
+        hipLaunchKernelGGL((lt_decode_kernel<G, 1>), grid, dim3(kDecodeThreads), 0, stream, a);
     else
-        hipLaunchKernelGGL((lt_decode_partial_kernel<G, 0>), grid, dim3(kDecodeThreads), 0, stream, a);
+        hipLaunchKernelGGL((lt_decode_kernel<G, 0>), grid, dim3(kDecodeThreads), 0, stream, a);
     return hipGetLastError();
 }
 
@@ -308,24 +416,24 @@ hipError_t append(const AppendArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t decode_partial(const DecodeArgs &a, hipStream_t stream)
+hipError_t decode(const DecodeArgs &a, hipStream_t stream)
 {
     switch (a.n_q_heads / a.n_kv_heads) {
-    case 1: return launch_partial<1>(a, stream);
-    case 2: return launch_partial<2>(a, stream);
-    case 3: return launch_partial<3>(a, stream);
-    case 4: return launch_partial<4>(a, stream);
-    case 5: return launch_partial<5>(a, stream);
-    case 6: return launch_partial<6>(a, stream);
-    case 7: return launch_partial<7>(a, stream);
-    case 8: return launch_partial<8>(a, stream);
+    case 1: return launch_decode<1>(a, stream);
+    case 2: return launch_decode<2>(a, stream);
+    case 3: return launch_decode<3>(a, stream);
+    case 4: return launch_decode<4>(a, stream);
+    case 5: return launch_decode<5>(a, stream);
+    case 6: return launch_decode<6>(a, stream);
+    case 7: return launch_decode<7>(a, stream);
+    case 8: return launch_decode<8>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }
 
-hipError_t decode_merge(const DecodeArgs &a, hipStream_t stream)
+hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream)
 {
-    hipLaunchKernelGGL(lt_decode_merge_kernel, dim3(a.n_q_heads, a.batch), dim3(kHeadDim), 0, stream, a);
+    hipLaunchKernelGGL(lt_zero_tickets_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, tickets, n);
     return hipGetLastError();
 }
 

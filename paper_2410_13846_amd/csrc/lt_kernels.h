@@ -12,6 +12,7 @@ constexpr int kHeadDim = 128;          // bf16 elements per key / value / query 
 constexpr int kMaxGroup = 8;           // query heads per KV head
 constexpr int kDecodeThreads = 256;    // 4 wavefronts per decode workgroup
 constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
+constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head) is split into
 constexpr int kScoreTileKeys = 64;     // keys staged in LDS per step of the scoring kernel
 
 struct AppendArgs {
@@ -25,7 +26,10 @@ struct AppendArgs {
 hipError_t append(const AppendArgs &a, hipStream_t stream);
 
 struct DecodeArgs {
-    const uint16_t *k_cache, *v_cache;
+    uint16_t *k_cache, *v_cache;
+    const uint16_t *k_new, *v_new;     // [B][Hkv][128] token of this step to append on the fly, or nullptr
+    int32_t new_slot;                  // cache entry the new token belongs to (used when k_new != nullptr)
+    unsigned int *tickets;             // [B][Hkv], zero between launches
     const uint16_t *q;                 // [B][Hq][128]
     float *part_acc;                   // [B][Hq][S][128]  un-normalised partial outputs
     float *part_ml;                    // [B][Hq][S][2]    running max (log2 units) and sum
@@ -38,8 +42,8 @@ struct DecodeArgs {
     float scale_log2e;                 // softmax_scale * log2(e)
     int32_t lazy_tag;                  // selects the kernel instantiation (name) only
 };
-hipError_t decode_partial(const DecodeArgs &a, hipStream_t stream);
-hipError_t decode_merge(const DecodeArgs &a, hipStream_t stream);
+hipError_t decode(const DecodeArgs &a, hipStream_t stream);
+hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream);
 
 struct ScoreArgs {
     const uint16_t *q_last;            // [B][Hq][w][128]

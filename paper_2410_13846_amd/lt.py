@@ -14,11 +14,11 @@ from . import build as _build
 
 OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_STATE, ERR_HIP, ERR_NOMEM = range(7)
 RECENT_PER_QUERY, RECENT_FIXED = 0, 1
-KERNEL_DECODE_FULL, KERNEL_DECODE_LAZY, KERNEL_MERGE, KERNEL_APPEND = range(4)
+KERNEL_DECODE_FULL, KERNEL_DECODE_LAZY, KERNEL_APPEND = range(3)
 
 EXPORTS = [
     "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
-    "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn",
+    "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
     "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
 ]
 
@@ -79,6 +79,8 @@ def load() -> ctypes.CDLL:
     lib.lt_append_kv.restype = ctypes.c_int
     lib.lt_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.lt_decode_attn.restype = ctypes.c_int
+    lib.lt_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
+    lib.lt_decode_step.restype = ctypes.c_int
     lib.lt_set_split.argtypes = [vp, i32, i32]
     lib.lt_set_split.restype = ctypes.c_int
     lib.lt_profile_enable.argtypes = [vp, i32]
@@ -250,6 +252,24 @@ class Context:
         st = load().lt_decode_attn(self._h, int(layer), qp, _dev_ptr(out, torch.float32, "out"),
                                    _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
         _check(st, "lt_decode_attn")
+        return (out, lse) if (want_lse or lse is not None) else out
+
+    def decode_step(self, layer: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
+                    out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None, want_lse: bool = False, stream=None):
+        """Fused append of one token + attention.  k_new / v_new: bf16 [B,Hkv,1,128] or [B,Hkv,128]."""
+        qp = _dev_ptr(q, torch.bfloat16, "q")
+        kp, vp = _dev_ptr(k_new, torch.bfloat16, "k_new"), _dev_ptr(v_new, torch.bfloat16, "v_new")
+        if tuple(q.shape) != (self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim):
+            raise LtError(ERR_SHAPE, "lt_decode_step (q must be [B,Hq,128])")
+        if k_new.numel() != self.cfg.batch * self.cfg.n_kv_heads * self.cfg.head_dim or v_new.numel() != k_new.numel():
+            raise LtError(ERR_SHAPE, "lt_decode_step (k_new / v_new must hold one token: [B,Hkv,128])")
+        if out is None:
+            out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=torch.float32, device=q.device)
+        if lse is None and want_lse:
+            lse = torch.empty((self.cfg.batch, self.cfg.n_q_heads), dtype=torch.float32, device=q.device)
+        st = load().lt_decode_step(self._h, int(layer), qp, kp, vp, _dev_ptr(out, torch.float32, "out"),
+                                   _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
+        _check(st, "lt_decode_step")
         return (out, lse) if (want_lse or lse is not None) else out
 
     def set_split(self, keys_full: int = 0, keys_lazy: int = 0):

@@ -13,8 +13,8 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def run_case(B, Hq, Hkv, n_prefill, steps, w_sink, w_recent, seed, split=None, max_extra=0):
-    say("decode case", dict(B=B, Hq=Hq, Hkv=Hkv, n=n_prefill, steps=steps, ws=w_sink, wr=w_recent, seed=seed, split=split))
+def run_case(B, Hq, Hkv, n_prefill, steps, w_sink, w_recent, seed, split=None, max_extra=0, fused=False):
+    say("decode case", dict(B=B, Hq=Hq, Hkv=Hkv, n=n_prefill, steps=steps, ws=w_sink, wr=w_recent, seed=seed, split=split, fused=fused))
     cfg = lt.make_config(2, B, Hq, Hkv, 128, w_sink, w_recent, n_prefill + steps + max_extra)
     mask = [0, 1]
     ctx = lt.Context(cfg, mask, DEV)
@@ -33,8 +33,11 @@ def run_case(B, Hq, Hkv, n_prefill, steps, w_sink, w_recent, seed, split=None, m
             q = randn_bf16((B, Hq, 128), seed + 1000 * (step + 1) + layer, scale=1.5)
             k = randn_bf16((B, Hkv, 1, 128), seed + 1000 * (step + 1) + 30 + layer)
             v = randn_bf16((B, Hkv, 1, 128), seed + 1000 * (step + 1) + 40 + layer)
-            ctx.append_kv(layer, k, v)
-            out, lse = ctx.decode_attn(layer, q, want_lse=True)
+            if fused:                                   # one launch: append on the fly + attend
+                out, lse = ctx.decode_step(layer, q, k, v, want_lse=True)
+            else:
+                ctx.append_kv(layer, k, v)
+                out, lse = ctx.decode_attn(layer, q, want_lse=True)
             hist.append(layer, bits(k), bits(v))
             ref, ref_lse = hist.decode(layer, bits(q))
             err = np.abs(f64(out) - ref).max()
@@ -49,24 +52,32 @@ def run_case(B, Hq, Hkv, n_prefill, steps, w_sink, w_recent, seed, split=None, m
     return worst
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("n_prefill", [0, 1, 15, 16, 17, 63, 64, 65, 300, 1027, 2500])
-def test_prefill_lengths_span_tiles_and_ragged_tails(n_prefill):
-    run_case(B=2, Hq=8, Hkv=2, n_prefill=n_prefill, steps=3, w_sink=4, w_recent=60, seed=100 + n_prefill)
+def test_prefill_lengths_span_tiles_and_ragged_tails(n_prefill, fused):
+    run_case(B=2, Hq=8, Hkv=2, n_prefill=n_prefill, steps=3, w_sink=4, w_recent=60, seed=100 + n_prefill, fused=fused)
 
 
 @pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 6, 7, 8])
 def test_every_query_group_size(group):
-    run_case(B=1, Hq=2 * group, Hkv=2, n_prefill=333, steps=2, w_sink=4, w_recent=124, seed=200 + group)
+    run_case(B=1, Hq=2 * group, Hkv=2, n_prefill=333, steps=2, w_sink=4, w_recent=124, seed=200 + group, fused=group % 2 == 0)
 
 
+@pytest.mark.parametrize("fused", [False, True])
 @pytest.mark.parametrize("ws,wr", [(0, 7), (4, 0), (1, 1), (4, 1020), (6, 252), (2, 508), (0, 2044), (300, 5)])
-def test_window_shapes_including_the_paper_grid(ws, wr):
-    run_case(B=1, Hq=8, Hkv=2, n_prefill=2300, steps=3, w_sink=ws, w_recent=wr, seed=300 + ws + wr)
+def test_window_shapes_including_the_paper_grid(ws, wr, fused):
+    run_case(B=1, Hq=8, Hkv=2, n_prefill=2300, steps=3, w_sink=ws, w_recent=wr, seed=300 + ws + wr, fused=fused)
 
 
-def test_ring_wraps_many_times_with_single_token_appends():
+@pytest.mark.parametrize("fused", [False, True])
+def test_ring_wraps_many_times_with_single_token_appends(fused):
     # window of 4 + 12 entries, 70 decode steps from an empty cache: the ring wraps five times
-    run_case(B=2, Hq=4, Hkv=1, n_prefill=0, steps=70, w_sink=4, w_recent=12, seed=400)
+    run_case(B=2, Hq=4, Hkv=1, n_prefill=0, steps=70, w_sink=4, w_recent=12, seed=400, fused=fused)
+
+
+def test_many_splits_merge_in_one_launch():
+    # 20000 keys in 256-key ranges: 79 workgroups per (sequence, KV head) hand their results to the last one
+    run_case(B=2, Hq=8, Hkv=2, n_prefill=20000, steps=4, w_sink=4, w_recent=1020, seed=450, split=(256, 64), fused=True)
 
 
 @pytest.mark.parametrize("split", [(256, 64), (512, 128), (2048, 2048)])
@@ -117,11 +128,15 @@ def test_ring_slots_hold_exactly_the_kept_tokens():
     say("ring slots")
     for layer in range(2):
         ctx.append_kv(layer, ks[0], vs[0])
+    q = randn_bf16((B, 8, 128), 629)
     for s in range(steps):
         ks.append(randn_bf16((B, Hkv, 1, 128), 630 + s))
         vs.append(randn_bf16((B, Hkv, 1, 128), 730 + s))
         for layer in range(2):
-            ctx.append_kv(layer, ks[-1], vs[-1])
+            if s % 2:
+                ctx.append_kv(layer, ks[-1], vs[-1])
+            else:                                       # the fused step must leave the same bytes in the cache
+                ctx.decode_step(layer, q, ks[-1], vs[-1])
     K, V = torch.cat(ks, 2), torch.cat(vs, 2)
     T = n + steps
     kf, vf = ctx.layer_tensors(0)
@@ -157,6 +172,12 @@ def test_error_paths_on_the_device():
     assert e.value.status == lt.ERR_SHAPE
     out = ctx.decode_attn(0, q)
     assert torch.isfinite(out).all()
+    ctx.decode_step(0, q, k[:, :, :1].contiguous(), k[:, :, :1].contiguous())
+    ctx.decode_step(0, q, k[:, :, :1].contiguous(), k[:, :, :1].contiguous())
+    with pytest.raises(lt.LtError) as e:                # 10 tokens stored, max_tokens = 10
+        ctx.decode_step(0, q, k[:, :, :1].contiguous(), k[:, :, :1].contiguous())
+    assert e.value.status == lt.ERR_CAPACITY
+    assert ctx.layer_len(0) == (10, 10)
     ctx.reset()
     assert ctx.layer_len(1) == (0, 0)
     ctx.close()
