@@ -41,6 +41,9 @@ def parse_args():
     ap.add_argument("--no-speedup", action="store_true", help="skip the all-full comparison run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the second pass that times kernels with HIP events")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (outside the timed region) so that hardware-counter "
+                         "runs have a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
     return ap.parse_args()
 
 
@@ -196,6 +199,14 @@ def main():
     K, Wm = args.steps, args.warmup
     log("workload %s: L=%d B=%d Hq=%d Hkv=%d n=%d window=%d+%d lazy=%d" % (
         wl.name, wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.context, wl.w_sink, wl.w_recent, wl.n_lazy))
+
+    if args.calibrate_copy:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)                                 # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---- identification: score every layer, select ------------------------------------------------
     t0 = time.perf_counter()

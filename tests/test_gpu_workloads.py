@@ -1,0 +1,169 @@
+"""GPU parity at the benchmark configurations' real shapes, in the launch configuration bench.py
+times (same batch, heads, context, window, default split choice, fused decode step).
+
+The tiny configuration is compared tensor by tensor.  The large ones keep the real per-layer
+shapes but fewer layers (a layer's launch does not depend on how many layers exist), and compare
+sampled (layer, sequence) slices that the oracle can compute one by one, plus properties that
+hold for every output."""
+import numpy as np
+import pytest
+import torch
+
+import lt_workloads as W
+import oracle
+from gpu_util import TOL_LSE, TOL_OUT, TOL_RATIO, bits, f64, say
+from paper_2410_13846_amd import lt
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def make_cfg(wl, extra_tokens=0):
+    return lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink, wl.w_recent,
+                          wl.context + wl.decode_steps + extra_tokens)
+
+
+def test_tiny_hybrid_whole_tensors():
+    """2 layers (0 full, 1 streaming), batch 1, 32/8 heads, prompt 4096, 4 + 1020 window, 16 decode steps,
+    lazy ratio over the last 64 prompt queries: every output element against the oracle."""
+    wl = W.WORKLOADS["tiny"].scaled(bias="planted")
+    cfg = make_cfg(wl)
+    ratios, kv = [], []
+    for layer in range(wl.n_layers):
+        say("tiny: scoring layer", layer)
+        k, v = W.prefill_kv(wl, layer, DEV)
+        q_last = W.last_queries(wl, layer, DEV)
+        mean, seq, rho = lt.lazy_ratio(cfg, q_last, k, wl.context, wl.w_last, want_rho=True)
+        ref_rho, ref_seq, ref_r = oracle.lazy_ratio(bits(q_last), bits(k), wl.w_sink, wl.w_recent)
+        assert np.abs(f64(rho) - ref_rho).max() <= TOL_RATIO
+        assert np.abs(f64(seq) - ref_seq).max() <= TOL_RATIO
+        assert abs(float(mean.cpu()[0]) - ref_r) <= TOL_RATIO
+        ratios.append(float(mean.cpu()[0]))
+        kv.append((k, v))
+    is_lazy, order = lt.select_lazy(ratios, wl.n_lazy)
+    ref_lazy, _ = oracle.select_lazy(np.asarray(ratios, np.float32).astype(np.float64), wl.n_lazy)
+    np.testing.assert_array_equal(is_lazy, ref_lazy)
+    assert list(np.nonzero(is_lazy)[0]) == W.planted_lazy_layers(wl)
+
+    ctx = lt.Context(cfg, is_lazy, DEV)
+    hist = oracle.History(wl.n_layers, is_lazy, wl.w_sink, wl.w_recent)
+    for layer, (k, v) in enumerate(kv):
+        ctx.append_kv(layer, k, v)
+        hist.append(layer, bits(k), bits(v))
+    worst = 0.0
+    for step in range(wl.decode_steps):
+        for layer in range(wl.n_layers):
+            q, k, v = W.decode_qkv(wl, layer, step, DEV)
+            say("tiny: step", step, "layer", layer)
+            out, lse = ctx.decode_step(layer, q, k, v, want_lse=True)
+            hist.append(layer, bits(k), bits(v))
+            ref, ref_lse = hist.decode(layer, bits(q))
+            worst = max(worst, np.abs(f64(out) - ref).max())
+            assert np.abs(f64(lse) - ref_lse).max() <= TOL_LSE
+    assert worst <= TOL_OUT
+    assert ctx.layer_len(0) == (wl.context + wl.decode_steps, wl.context + wl.decode_steps)
+    assert ctx.layer_len(1) == (wl.context + wl.decode_steps, wl.w_sink + wl.w_recent)
+    ctx.close()
+
+
+def history_of(wl, layer, b, steps_done):
+    """Whole K/V history of one sequence of one layer, regenerated from the seeds: uint16 [1,Hkv,T,d]."""
+    k, v = W.prefill_kv(wl, layer, DEV)
+    ks, vs = [bits(k[b:b + 1])], [bits(v[b:b + 1])]
+    del k, v
+    for step in range(steps_done):
+        _, kn, vn = W.decode_qkv(wl, layer, step, DEV)
+        ks.append(bits(kn[b:b + 1]))
+        vs.append(bits(vn[b:b + 1]))
+    return np.concatenate(ks, axis=2), np.concatenate(vs, axis=2)
+
+
+def run_sampled(wl, layers, is_lazy, samples, steps, score_samples=()):
+    """Fill the stack for `layers` (indices into the workload's recipe), decode `steps` tokens with the
+    fused step, and check the sampled (position in `layers`, sequence) pairs at the last step."""
+    sub = wl.scaled(n_layers=len(layers), decode_steps=steps)
+    cfg = make_cfg(sub)
+    ctx = lt.Context(cfg, is_lazy, DEV)
+    for i, layer in enumerate(layers):
+        say(wl.name, "prefill layer", layer)
+        k, v = W.prefill_kv(wl, layer, DEV)
+        if (i, 0) in score_samples or any(s[0] == i for s in score_samples):
+            q_last = W.last_queries(wl, layer, DEV)
+            mean, seq, rho = lt.lazy_ratio(cfg, q_last, k, wl.context, wl.w_last, want_rho=True)
+            rho_h = f64(rho)
+            assert np.isfinite(rho_h).all() and rho_h.min() >= 0.0 and rho_h.max() <= 1.0 + 1e-6
+            assert abs(float(mean.cpu()[0]) - float(seq.double().mean().cpu())) <= 1e-6
+            for (si, b, g) in [s for s in score_samples if s[0] == i]:
+                G = wl.group
+                qs = bits(q_last[b:b + 1, g * G:(g + 1) * G])
+                ksub = bits(k[b:b + 1, g:g + 1])
+                ref_rho, _, _ = oracle.lazy_ratio(qs, ksub, wl.w_sink, wl.w_recent)
+                err = np.abs(rho_h[b, g * G:(g + 1) * G] - ref_rho[0]).max()
+                say(wl.name, "ratio sample layer", layer, "b", b, "kv head", g, "err", err)
+                assert err <= TOL_RATIO
+            del q_last
+        ctx.append_kv(i, k, v)
+        del k, v
+    outs = {}
+    for step in range(steps):
+        for i, layer in enumerate(layers):
+            q, k, v = W.decode_qkv(wl, layer, step, DEV)
+            out, lse = ctx.decode_step(i, q, k, v, want_lse=True)
+            if step == steps - 1:
+                outs[i] = (q, out, lse)
+    torch.cuda.synchronize()
+    for i, (q, out, lse) in outs.items():
+        assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+        assert out.abs().max().item() <= 8.0                  # a convex combination of N(0,1) bf16 values
+    for (i, b) in samples:
+        layer = layers[i]
+        K, V = history_of(wl, layer, b, steps)
+        q, out, lse = outs[i]
+        mode = oracle.MODE_LAZY if is_lazy[i] else oracle.MODE_FULL
+        ref, ref_lse = oracle.decode_attn(bits(q[b:b + 1]), K, V, mode, wl.w_sink, wl.w_recent)
+        err = np.abs(f64(out[b:b + 1]) - ref).max()
+        err_lse = np.abs(f64(lse[b:b + 1]) - ref_lse).max()
+        say(wl.name, "decode sample layer", layer, "lazy" if is_lazy[i] else "full", "b", b, "T", K.shape[2], "err", err)
+        assert err <= TOL_OUT and err_lse <= TOL_LSE
+    total, stored = ctx.layer_len(0)
+    assert total == wl.context + steps
+    ctx.close()
+
+
+def test_llama3_8b_32k_shapes_sampled():
+    """Batch 8, 32/8 heads, context 32768, 4 + 2044 window: two planted-lazy and two full layers."""
+    wl = W.WORKLOADS["llama3_8b_32k"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layers = [l for l in range(wl.n_layers) if l not in lazy_layers]
+    layers = [full_layers[0], lazy_layers[0], full_layers[-1], lazy_layers[-1]]
+    run_sampled(wl, layers, [0, 1, 0, 1], samples=[(0, 0), (1, 3), (2, 7), (3, 5)], steps=3,
+                score_samples=[(0, 2, 1), (1, 6, 7)])
+
+
+def test_mistral_7b_16k_shapes_sampled():
+    """Batch 32, context 16384: one full and one lazy layer of the sweep."""
+    wl = W.WORKLOADS["mistral_7b_16k"]
+    run_sampled(wl, [3, 17], [0, 1], samples=[(0, 31), (1, 12)], steps=2, score_samples=[(1, 20, 4)])
+
+
+def test_qwq_32b_shapes_sampled():
+    """40 query heads over 8 KV heads (groups of 5), batch 4, history grown to several thousand tokens."""
+    wl = W.WORKLOADS["qwq_32b_gen"].scaled(context=6000)
+    run_sampled(wl, [0, 40], [0, 1], samples=[(0, 1), (1, 3)], steps=4, score_samples=[(0, 2, 3)])
+
+
+def test_llama31_8b_128k_shapes_sampled():
+    """Context 131072, 4 + 4092 window, batch 1: decode over 128K keys and scoring at 128K."""
+    wl = W.WORKLOADS["llama31_8b_128k_b1"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layers = [l for l in range(wl.n_layers) if l not in lazy_layers]
+    run_sampled(wl, [full_layers[0], lazy_layers[0]], [0, 1], samples=[(0, 0), (1, 0)], steps=2,
+                score_samples=[(1, 0, 5)])
+
+
+def test_llama31_8b_128k_batch_16_one_full_layer():
+    """The batch-16 128K shape: one full layer holds 8.6 GB of K and V; offsets exceed 2^31 elements."""
+    wl = W.WORKLOADS["llama31_8b_128k_b16"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layer = [l for l in range(wl.n_layers) if l not in lazy_layers][0]
+    run_sampled(wl, [full_layer], [0], samples=[(0, 15), (0, 8)], steps=1)
