@@ -92,21 +92,17 @@ struct lt_ctx {
 
 namespace {
 
-// Keys per workgroup.  The decode kernel keeps kResidentBlocks workgroups on the chip at once
-// (3 per compute unit at its register budget); a launch whose workgroup count is just above a
-// multiple of that leaves the chip idle in a tail, so the split count per key stream is chosen
-// to fill whole rounds.  `streams` = B * Hkv independent key streams.
+// Keys per workgroup.  Measured on MI355X, the decode kernel streams fastest with ONE workgroup
+// (four wavefronts, 16 KB of loads in flight each) per compute unit reading one long contiguous
+// range: 256 workgroups reach 6.6 TB/s where 512 or 768 reach 6.1-6.2 TB/s.  So each of the
+// `streams` = B * Hkv key streams is cut into 256 / streams ranges; more streams than compute
+// units means one range per stream.  Short ranges are not cut below `lo` keys.
 int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t splits_cap)
 {
-    constexpr int64_t kResidentBlocks = 256 * 3;
-    const int64_t lo = lazy ? 128 : 256;                            // not so small that partial results rival the KV bytes
-    int64_t splits = std::max<int64_t>(kResidentBlocks / streams, 1);
+    constexpr int64_t kComputeUnits = 256;
+    const int64_t lo = lazy ? 128 : 256;
+    const int64_t splits = std::max<int64_t>(kComputeUnits / streams, 1);
     int64_t keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
-    if (keys > 4096) {                                              // long streams: several full rounds
-        const int64_t rounds = ceil_div(keys, 4096);
-        splits *= rounds;
-        keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
-    }
     keys = std::max(keys, lo);
     keys = std::max(keys, ceil_div(ceil_div(stored, splits_cap), ltk::kKeyGranule) * ltk::kKeyGranule);
     return (int)keys;
@@ -161,7 +157,7 @@ size_t lt_workspace_bytes(const lt_config *cfg)
     if (!config_ok(cfg) || config_shape(cfg) != LT_OK) return 0;
     const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)max_splits(cfg);
     return align_up(rows * ltk::kHeadDim * sizeof(float)) + align_up(rows * 2 * sizeof(float)) +
-           align_up((size_t)cfg->batch * cfg->n_kv_heads * sizeof(unsigned int));
+           align_up((size_t)cfg->batch * cfg->n_kv_heads * ltk::kTicketStride * sizeof(unsigned int));
 }
 
 lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab, size_t kv_bytes, void *workspace,
@@ -408,7 +404,7 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     a.lazy_tag = l.lazy ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ctx->tickets_ready) {
-        if (ltk::zero_tickets(ctx->tickets, c.batch * c.n_kv_heads, s) != hipSuccess) return LT_ERR_HIP;
+        if (ltk::zero_tickets(ctx->tickets, c.batch * c.n_kv_heads * ltk::kTicketStride, s) != hipSuccess) return LT_ERR_HIP;
         ctx->tickets_ready = true;
     }
     {

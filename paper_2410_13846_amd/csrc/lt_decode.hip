@@ -264,18 +264,37 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
         for (int e = 0; e < 8; ++e) st.acc[h][e] = 0.f;
     }
 
-    // Wavefront w takes tiles w, w+4, ...; two tile buffers alternate so the loads of the next
-    // tile are in flight while the current one is consumed.  Every fetch is unconditional (keys
-    // past the range are clamped to its last key and never consumed): with a fixed number of
-    // loads between a fetch and its use the wait counts are exact, and a tile is consumed while
-    // the following one is still arriving.
+    // Wavefront w takes every fourth tile; two tile buffers alternate so the loads of the next
+    // tile are in flight while the current one is consumed.  Every fetch is unconditional (past
+    // its last tile a wavefront re-fetches tiles it never consumes): with a fixed number of loads
+    // between a fetch and its use the wait counts are exact, and a tile is consumed while the
+    // following one is still arriving.
+    // Workgroups run in lockstep, and their ranges start at multiples of the same strides, so
+    // without care they all hit the same few memory channels at the same moment (measured: 185
+    // vs 162 us per launch depending on the cache capacity alone).  The order of keys does not
+    // matter to the result, so each workgroup starts at its own pseudo-random tile of its range
+    // and wraps around.
+    const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    const int phase = (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)n_tiles);
+    const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
+    int next_tile = wave + phase;
+    while (next_tile >= n_tiles) next_tile -= n_tiles;
+    auto advance = [&]() {
+        const int cur = next_tile;
+        next_tile += kWaves;
+        while (next_tile >= n_tiles) next_tile -= n_tiles;
+        return begin_key + 16 * cur;
+    };
     Tile t0, t1;
-    fetch(t0, begin_key + 16 * wave);
-    for (int t = wave; t < n_tiles; t += 2 * kWaves) {
-        fetch(t1, begin_key + 16 * (t + kWaves));
-        consume(t0, begin_key + 16 * t, st, qf);
-        fetch(t0, begin_key + 16 * (t + 2 * kWaves));
-        if (t + kWaves < n_tiles) consume(t1, begin_key + 16 * (t + kWaves), st, qf);
+    int key0 = advance();
+    fetch(t0, key0);
+    for (int k = 0; k < my_tiles; k += 2) {
+        const int key1 = advance();
+        fetch(t1, key1);
+        consume(t0, key0, st, qf);
+        key0 = advance();
+        fetch(t0, key0);
+        if (k + 1 < my_tiles) consume(t1, key1, st, qf);
     }
 
     // Merge the four rows of the wavefront.
@@ -342,7 +361,7 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
     // then the ticket is taken, and the merge loads are issued only after the last ticket.
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
-    unsigned int *ticket = a.tickets + (int64_t)b * a.n_kv_heads + g;
+    unsigned int *ticket = a.tickets + ((int64_t)b * a.n_kv_heads + g) * kTicketStride;
     if (threadIdx.x == 0) {
         const unsigned int t_mine = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         sh_is_last = (t_mine == (unsigned int)(a.n_splits - 1)) ? 1 : 0;

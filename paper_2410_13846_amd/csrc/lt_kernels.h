@@ -13,6 +13,7 @@ constexpr int kMaxGroup = 8;           // query heads per KV head
 constexpr int kDecodeThreads = 256;    // 4 wavefronts per decode workgroup
 constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
 constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head) is split into
+constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels
 constexpr int kScoreTileKeys = 64;     // keys staged in LDS per step of the scoring kernel
 
 struct AppendArgs {
@@ -29,7 +30,7 @@ struct DecodeArgs {
     uint16_t *k_cache, *v_cache;
     const uint16_t *k_new, *v_new;     // [B][Hkv][128] token of this step to append on the fly, or nullptr
     int32_t new_slot;                  // cache entry the new token belongs to (used when k_new != nullptr)
-    unsigned int *tickets;             // [B][Hkv], zero between launches
+    unsigned int *tickets;             // [B][Hkv] tickets kTicketStride apart, zero between launches
     const uint16_t *q;                 // [B][Hq][128]
     float *part_acc;                   // [B][Hq][S][128]  un-normalised partial outputs
     float *part_ml;                    // [B][Hq][S][2]    running max (log2 units) and sum
