@@ -41,6 +41,7 @@ def parse_args():
     ap.add_argument("--no-speedup", action="store_true", help="skip the all-full comparison run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the second pass that times kernels with HIP events")
+    ap.add_argument("--scoring-only", action="store_true", help="run and report only the lazy-ratio scoring of every layer")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (outside the timed region) so that hardware-counter "
                          "runs have a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -225,6 +226,10 @@ def main():
         "k_gbs": score_bytes / med_ms / 1e6, "hbm_frac": score_bytes / med_ms / 1e6 / HBM_PEAK_GBS, "select_us": select_us,
         "w_last": wl.w_last, "ratio_min": min(ratios), "ratio_max": max(ratios),
     }
+
+    if args.scoring_only:
+        print(json.dumps({"metric": "lazy-ratio scoring, per layer", "config": {"workload": wl.name}, "scoring": scoring}))
+        return 0
 
     # ---- decode -----------------------------------------------------------------------------------------
     profile_pass = not args.no_profile_pass

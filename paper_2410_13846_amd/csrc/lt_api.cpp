@@ -258,7 +258,7 @@ size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_
     if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n <= 0 || w_last <= 0 || w_last > 64) return 0;
     const int64_t chunks = ceil_div(n, score_keys_per_block(cfg, n));
     const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * chunks) * 3 * sizeof(float);
-    return align_up(part) + align_up((size_t)cfg->batch * sizeof(float));
+    return align_up(part) + align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
 }
 
 lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
@@ -295,7 +295,7 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
     a.scale_log2e = effective_scale(cfg) * kLog2e;
     a.part = static_cast<float *>(workspace);
     const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * a.n_chunks) * 3 * sizeof(float);
-    a.seq_scratch = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(part));
+    a.head_scratch = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(part));
     a.rho = rho_dev;
     a.ratio_seq = ratio_seq_dev;
     a.ratio_mean = ratio_mean_dev;

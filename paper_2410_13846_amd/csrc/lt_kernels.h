@@ -55,8 +55,8 @@ struct ScoreArgs {
     int32_t w_sink, w_recent, fixed_mode;
     int32_t keys_per_block, n_chunks;
     float scale_log2e;
-    float *part;                       // [B][Hq][w][2*n_chunks][3]: max (log2 units), causal sum, kept sum
-    float *seq_scratch;                // [B]
+    float *part;                       // [B][Hq][n_chunks][2][3][w]: max (log2 units), causal sum, kept sum
+    float *head_scratch;               // [B][Hq] sum of rho over the queries of a head
     float *rho, *ratio_seq, *ratio_mean;
 };
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);

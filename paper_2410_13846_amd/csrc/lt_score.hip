@@ -131,7 +131,7 @@ __device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Staging<G>::kPi
 // G: query heads per KV head (wavefronts per workgroup).
 // NT: 32-query column tiles per head: 1 (w <= 32) or 2 (w <= 64).
 template <int G, int NT>
-__global__ __launch_bounds__(64 * G) void lt_lazy_ratio_partial_kernel(ScoreArgs a)
+__global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreArgs a)
 {
     __shared__ __attribute__((aligned(16))) uint16_t sh_k[2][kScoreTileKeys * kRowElems];
 
@@ -165,104 +165,152 @@ __global__ __launch_bounds__(64 * G) void lt_lazy_ratio_partial_kernel(ScoreArgs
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { st[nt].m = -INFINITY; st[nt].sum_causal = 0.f; st[nt].sum_kept = 0.f; }
 
-    u32x4_t pre[kPieces];
-    if (n_tiles > 0) {
-        fetch_tile<G>(pre, kb, a.k_stride_t, begin_key, a.n);
-        commit_tile<G>(pre, sh_k[0]);
-    }
-    __syncthreads();
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        const int buf = tile & 1;
-        const bool more = tile + 1 < n_tiles;
-        if (more) fetch_tile<G>(pre, kb, a.k_stride_t, begin_key + (int64_t)(tile + 1) * kScoreTileKeys, a.n);
+    // S^T for one 32-key sub-tile: 8 k-steps of 16 dims, NT column tiles of 32 queries.
+    auto contract = [&](floatx16_t (&c)[NT], const uint16_t *tile, int kt) {
 #pragma unroll
-        for (int kt = 0; kt < kScoreTileKeys / 32; ++kt) {
-            const int64_t j0 = begin_key + (int64_t)tile * kScoreTileKeys + 32 * kt;
-            if (j0 >= end_key) break;
-            floatx16_t c[NT];
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
+            for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
+        for (int s = 0; s < 8; ++s) {
+            const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&tile[(32 * kt + col) * kRowElems + 16 * s + 8 * half]);
+            const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, u);
 #pragma unroll
-            for (int s = 0; s < 8; ++s) {
-                const uint4 u = *reinterpret_cast<const uint4 *>(&sh_k[buf][(32 * kt + col) * kRowElems + 16 * s + 8 * half]);
-                const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, u);
+            for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
+        }
+    };
+    // Fold one sub-tile's logits into the running max and the two sums of every query column.
+    auto fold = [&](const floatx16_t (&c)[NT], int64_t j0) {
+        const TileClass cls = classify(j0, a.n, a.w_last, a.w_sink, a.w_recent, a.fixed_mode);
+        if (cls.fast) {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
-            }
-            const TileClass cls = classify(j0, a.n, a.w_last, a.w_sink, a.w_recent, a.fixed_mode);
-            if (cls.fast) {
+            for (int nt = 0; nt < NT; ++nt) update_fast(c[nt], st[nt], a.scale_log2e, cls.kept);
+        } else {
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) update_fast(c[nt], st[nt], a.scale_log2e, cls.kept);
-            } else {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const int64_t p = a.n - a.w_last + nt * 32 + col;   // query position of this lane's column
-                    update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, p, a.n, a.w_sink, a.w_recent, a.fixed_mode);
-                }
+            for (int nt = 0; nt < NT; ++nt) {
+                const int64_t p = a.n - a.w_last + nt * 32 + col;       // query position of this lane's column
+                update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, p, a.n, a.w_sink, a.w_recent, a.fixed_mode);
             }
         }
-        if (more) commit_tile<G>(pre, sh_k[buf ^ 1]);
-        __syncthreads();
+    };
+
+    // Two wavefronts per SIMD (from two workgroups) overlap one's matrix-core work with the
+    // other's exponentials.  The K tiles are prefetched two tiles ahead in two register sets, so
+    // a global load has two tiles of compute (about 2.5 us) to arrive before it is parked in LDS.
+    auto compute = [&](const uint16_t *tile, int64_t j0) {
+#pragma unroll
+        for (int kt = 0; kt < kScoreTileKeys / 32; ++kt) {
+            if (j0 + 32 * kt >= end_key) break;
+            floatx16_t c[NT];
+            contract(c, tile, kt);
+            fold(c, j0 + 32 * kt);
+        }
+    };
+    auto tile_key = [&](int tile) { return begin_key + (int64_t)tile * kScoreTileKeys; };
+
+    u32x4_t pre_even[kPieces], pre_odd[kPieces];
+    if (n_tiles > 0) {
+        fetch_tile<G>(pre_even, kb, a.k_stride_t, tile_key(0), a.n);
+        commit_tile<G>(pre_even, sh_k[0]);
+    }
+    __syncthreads();
+    if (n_tiles > 1) fetch_tile<G>(pre_odd, kb, a.k_stride_t, tile_key(1), a.n);
+    for (int tile = 0; tile < n_tiles; tile += 2) {
+        if (tile + 2 < n_tiles) fetch_tile<G>(pre_even, kb, a.k_stride_t, tile_key(tile + 2), a.n);
+        compute(sh_k[0], tile_key(tile));
+        if (tile + 1 < n_tiles) {
+            commit_tile<G>(pre_odd, sh_k[1]);
+            __syncthreads();
+            if (tile + 3 < n_tiles) fetch_tile<G>(pre_odd, kb, a.k_stride_t, tile_key(tile + 3), a.n);
+            compute(sh_k[1], tile_key(tile + 1));
+            if (tile + 2 < n_tiles) {
+                commit_tile<G>(pre_even, sh_k[0]);
+                __syncthreads();
+            }
+        }
     }
 
+    // partial layout [B][Hq][chunk][half][field][w]: each store below is contiguous over the query columns
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
         const int t = nt * 32 + col;
         if (t < a.w_last) {
-            float *dst = a.part + (((((int64_t)b * a.n_q_heads + h) * a.w_last + t) * (2 * a.n_chunks)) + 2 * chunk + half) * 3;
+            float *dst = a.part + ((((int64_t)b * a.n_q_heads + h) * a.n_chunks + chunk) * 2 + half) * 3 * a.w_last + t;
             dst[0] = st[nt].m;
-            dst[1] = st[nt].sum_causal;
-            dst[2] = st[nt].sum_kept;
+            dst[a.w_last] = st[nt].sum_causal;
+            dst[2 * a.w_last] = st[nt].sum_kept;
         }
     }
 }
 
-// rho per (sequence, head, query) and the per-sequence mean.  One workgroup per sequence,
-// fixed-order reductions so the result does not depend on scheduling.
-__global__ __launch_bounds__(256) void lt_lazy_ratio_finish_kernel(ScoreArgs a)
+// rho per (sequence, head, query): one workgroup per (sequence, head), one thread per query,
+// merging the chunk partials by their running maxima; the head's sum of rho goes to scratch.
+// Fixed-order reductions: the result does not depend on scheduling.
+__global__ __launch_bounds__(64) void lt_lazy_ratio_finish_kernel(ScoreArgs a)
 {
-    __shared__ float sh_sum[256];
-    const int b = blockIdx.x;
-    const int per_seq = a.n_q_heads * a.w_last;
+    __shared__ float sh_sum[64];
+    const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
     const int n_part = 2 * a.n_chunks;
-    float local = 0.f;
-    for (int idx = threadIdx.x; idx < per_seq; idx += 256) {
-        const float *src = a.part + ((int64_t)b * per_seq + idx) * n_part * 3;
-        float mx = -INFINITY;
-        for (int c = 0; c < n_part; ++c) mx = fmaxf(mx, src[3 * c]);
-        float causal = 0.f, kept = 0.f;
-        for (int c = 0; c < n_part; ++c) {
-            const float m = src[3 * c];
-            const float wgt = (m == -INFINITY) ? 0.f : fast_exp2(m - mx);
-            causal += wgt * src[3 * c + 1];
-            kept += wgt * src[3 * c + 2];
+    float rho = 0.f;
+    if (t < a.w_last) {
+        const float *src = a.part + ((int64_t)b * a.n_q_heads + h) * n_part * 3 * a.w_last + t;
+        float mx = -INFINITY, causal = 0.f, kept = 0.f;
+        for (int c0 = 0; c0 < n_part; c0 += 8) {              // eight partials per round trip
+            float m[8], f[8], k[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float *pc = src + (int64_t)min(c0 + u, n_part - 1) * 3 * a.w_last;
+                m[u] = pc[0];
+                f[u] = pc[a.w_last];
+                k[u] = pc[2 * a.w_last];
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                if (c0 + u < n_part && m[u] != -INFINITY) {
+                    const float m_new = fmaxf(mx, m[u]);
+                    const float keep = fast_exp2(mx - m_new), add = fast_exp2(m[u] - m_new);
+                    causal = causal * keep + add * f[u];
+                    kept = kept * keep + add * k[u];
+                    mx = m_new;
+                }
+            }
         }
-        const float rho = kept / causal;
-        if (a.rho != nullptr) a.rho[(int64_t)b * per_seq + idx] = rho;
-        local += rho;
+        rho = kept / causal;
+        if (a.rho != nullptr) a.rho[((int64_t)b * a.n_q_heads + h) * a.w_last + t] = rho;
     }
-    sh_sum[threadIdx.x] = local;
+    sh_sum[t] = rho;
     __syncthreads();
-    for (int step = 128; step > 0; step >>= 1) {
-        if ((int)threadIdx.x < step) sh_sum[threadIdx.x] += sh_sum[threadIdx.x + step];
+    for (int step = 32; step > 0; step >>= 1) {
+        if (t < step) sh_sum[t] += sh_sum[t + step];
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        const float r = sh_sum[0] / (float)per_seq;
-        a.seq_scratch[b] = r;
-        if (a.ratio_seq != nullptr) a.ratio_seq[b] = r;
-    }
+    if (t == 0) a.head_scratch[(int64_t)b * a.n_q_heads + h] = sh_sum[0];
 }
 
-__global__ void lt_lazy_ratio_mean_kernel(ScoreArgs a)
+// Per-sequence mean over heads and queries, then the batch mean (one workgroup, fixed order).
+__global__ __launch_bounds__(64) void lt_lazy_ratio_mean_kernel(ScoreArgs a)
 {
-    if (threadIdx.x != 0 || blockIdx.x != 0) return;
+    __shared__ float sh_seq[64];
     float total = 0.f;
-    for (int b = 0; b < a.batch; ++b) total += a.seq_scratch[b];
-    a.ratio_mean[0] = total / (float)a.batch;
+    for (int b0 = 0; b0 < a.batch; b0 += 64) {
+        const int b = b0 + threadIdx.x;
+        float r = 0.f;
+        if (b < a.batch) {
+            float sum = 0.f;
+            for (int h = 0; h < a.n_q_heads; ++h) sum += a.head_scratch[(int64_t)b * a.n_q_heads + h];
+            r = sum / (float)(a.n_q_heads * a.w_last);
+            if (a.ratio_seq != nullptr) a.ratio_seq[b] = r;
+        }
+        sh_seq[threadIdx.x] = r;
+        __syncthreads();
+        if (threadIdx.x == 0)
+            for (int i = 0; i < 64 && b0 + i < a.batch; ++i) total += sh_seq[i];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) a.ratio_mean[0] = total / (float)a.batch;
 }
+
+}  // namespace
 
 template <int G>
 hipError_t launch_partial(const ScoreArgs &a, hipStream_t stream)
@@ -274,8 +322,6 @@ hipError_t launch_partial(const ScoreArgs &a, hipStream_t stream)
         hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 2>), grid, dim3(64 * G), 0, stream, a);
     return hipGetLastError();
 }
-
-}  // namespace
 
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream)
 {
@@ -292,7 +338,7 @@ hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream)
     default: e = hipErrorInvalidValue; break;
     }
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(lt_lazy_ratio_finish_kernel, dim3(a.batch), dim3(256), 0, stream, a);
+    hipLaunchKernelGGL(lt_lazy_ratio_finish_kernel, dim3(a.n_q_heads, a.batch), dim3(64), 0, stream, a);
     e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(lt_lazy_ratio_mean_kernel, dim3(1), dim3(64), 0, stream, a);
