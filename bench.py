@@ -42,6 +42,13 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the second pass that times kernels with HIP events")
     ap.add_argument("--scoring-only", action="store_true", help="run and report only the lazy-ratio scoring of every layer")
+    ap.add_argument("--online", action="store_true",
+                    help="set the stack up the paper's way: prefill layer by layer, score each layer from its cache, push "
+                         "it into the priority queue and reduce the popped layer's cache at once (peak P+1 full caches)")
+    ap.add_argument("--growth", action="store_true",
+                    help="long-generation curve: fixed lazy mask, decode from the prompt length up to the workload's "
+                         "final length, timing --steps decode steps at each doubling of the history (the tokens in "
+                         "between are bulk-appended); reports tokens/s against generated length")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (outside the timed region) so that hardware-counter "
                          "runs have a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -55,19 +62,46 @@ def log(*a):
 class Stack:
     """A hybrid stack with its decode inputs pre-generated on the device."""
 
-    def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0):
+    def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0, online=False):
         import torch
 
-        self.lt, self.wl, self.is_lazy, self.dev = lt, wl, list(map(int, is_lazy)), dev
+        self.lt, self.wl, self.dev = lt, wl, dev
         self.cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink,
                                   wl.w_recent, wl.context + total_steps)
-        self.ctx = lt.Context(self.cfg, self.is_lazy, dev)
+        if online:
+            # prefill -> score in place -> push -> reduce the popped layer, one layer at a time
+            self.ctx = lt.Context(self.cfg, device=dev, n_full_online=wl.n_layers - wl.n_lazy)
+            queue = lt.SelectQueue(wl.n_layers - wl.n_lazy)
+            ws = torch.empty(max(lt.lazy_ratio_workspace_bytes(self.cfg, wl.context, wl.w_last), 256), dtype=torch.uint8, device=dev)
+            self.ratios, self.score_ms, mask = [], [], [0] * wl.n_layers
+            for layer in range(wl.n_layers):
+                k, v = W.prefill_kv(wl, layer, dev)
+                q_last = W.last_queries(wl, layer, dev)
+                self.ctx.append_kv(layer, k, v)
+                del k, v
+                k_cache, _ = self.ctx.layer_tensors(layer)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                mean, _, _ = lt.lazy_ratio(self.cfg, q_last, k_cache, wl.context, wl.w_last, workspace=ws)
+                e1.record()
+                e1.synchronize()
+                self.score_ms.append(e0.elapsed_time(e1))
+                self.ratios.append(float(mean.cpu()[0]))
+                popped = queue.push(self.ratios[-1], layer)
+                if popped >= 0:
+                    self.ctx.truncate_layer(popped)
+                    mask[popped] = 1
+            queue.close()
+            self.is_lazy = mask
+        else:
+            self.is_lazy = list(map(int, is_lazy))
+            self.ctx = lt.Context(self.cfg, self.is_lazy, dev)
+            for layer in range(wl.n_layers):
+                k, v = W.prefill_kv(wl, layer, dev)
+                self.ctx.append_kv(layer, k, v)
+                del k, v
         if keys_full or keys_lazy:
             self.ctx.set_split(keys_full, keys_lazy)
-        for layer in range(wl.n_layers):
-            k, v = W.prefill_kv(wl, layer, dev)
-            self.ctx.append_kv(layer, k, v)
-            del k, v
         self.q, self.k, self.v = [], [], []
         for layer in range(wl.n_layers):
             q, k, v = W.decode_qkv_block(wl, layer, 0, total_steps, dev)
@@ -177,6 +211,71 @@ def cpu_baseline(W, wl, stack, is_lazy):
     }
 
 
+def growth_curve(args, lt, W, wl, dev):
+    """tokens/s against history length for a fixed (pre-selected) lazy mask, LightTransfer-Train style."""
+    import numpy as np
+    import torch
+
+    final = wl.context + wl.decode_steps
+    is_lazy = [1 if l in W.planted_lazy_layers(wl) else 0 for l in range(wl.n_layers)]
+    cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink, wl.w_recent, final)
+    ctx = lt.Context(cfg, is_lazy, dev)
+    lib, h = lt.load(), ctx._h
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    K = args.steps
+    q = W.randn_bf16((K, wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), W.seed_for(wl, 0, stream=21), dev)
+    kn = W.randn_bf16((K, wl.n_layers, wl.batch, wl.n_kv_heads, wl.head_dim), W.seed_for(wl, 0, stream=22), dev)
+    vn = W.randn_bf16((K, wl.n_layers, wl.batch, wl.n_kv_heads, wl.head_dim), W.seed_for(wl, 0, stream=23), dev)
+    out = torch.empty((wl.n_layers, wl.batch, wl.n_q_heads, wl.head_dim), dtype=torch.float32, device=dev)
+    qs, ks = q[0, 0].numel() * 2, kn[0, 0].numel() * 2
+    filler = W.randn_bf16((wl.batch, wl.n_kv_heads, 4096, wl.head_dim), W.seed_for(wl, 0, stream=24), dev)
+
+    def grow_to(total):
+        for layer in range(wl.n_layers):
+            have = ctx.layer_len(layer)[0]
+            while have < total:
+                n = min(4096, total - have)
+                ctx.append_kv(layer, filler[:, :, :n].contiguous() if n < 4096 else filler, filler[:, :, :n].contiguous() if n < 4096 else filler)
+                have += n
+
+    def decode(n_steps):
+        for s in range(n_steps):
+            for layer in range(wl.n_layers):
+                off_q, off_k = (s * wl.n_layers + layer) * qs, (s * wl.n_layers + layer) * ks
+                st = lib.lt_decode_step(h, layer, q.data_ptr() + off_q, kn.data_ptr() + off_k, vn.data_ptr() + off_k,
+                                        out[layer].data_ptr(), None, stream)
+                if st != 0:
+                    raise lt.LtError(st, "lt_decode_step")
+
+    points, T = [], wl.context
+    targets = []
+    while T < final:
+        targets.append(T)
+        T *= 2
+    targets.append(final - K)
+    for T in targets:
+        grow_to(T)
+        torch.cuda.synchronize()
+        if not points:
+            decode(min(K, 4))                          # warm-up launches; they also lengthen the history a little
+            torch.cuda.synchronize()
+        T0 = ctx.layer_len(0)[0]
+        t0 = time.perf_counter()
+        decode(K)
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+        T_mid = T0 + (K + 1) / 2
+        nbytes = W.kv_bytes_per_step(wl, is_lazy, int(T_mid))
+        points.append({"tokens_in_history": int(T_mid), "ms_per_step": dt / K * 1e3, "tokens_per_s": wl.batch * K / dt,
+                       "kv_gbs": nbytes / (dt / K) / 1e9, "ceiling_tokens_per_s_at_8TBs": wl.batch / (nbytes / 8e12)})
+        log("T=%6d: %.3f ms/step, %.0f tokens/s, %.0f GB/s" % (T_mid, dt / K * 1e3, wl.batch * K / dt, nbytes / (dt / K) / 1e9))
+    ctx.close()
+    return {"metric": "decode tokens/s against history length, fixed lazy mask", "unit": "tokens/s", "n_gpus": 1,
+            "steps": K, "data": "synthetic", "config": {"workload": wl.name, "layers": wl.n_layers, "lazy_layers": int(sum(is_lazy)),
+            "batch": wl.batch, "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads, "w_sink": wl.w_sink, "w_recent": wl.w_recent},
+            "curve": points}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -209,12 +308,26 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
+    if args.growth:
+        print(json.dumps(growth_curve(args, lt, W, wl, dev)))
+        return 0
+
     # ---- identification: score every layer, select ------------------------------------------------
+    profile_pass = not args.no_profile_pass
+    total_steps = Wm + K + (K if profile_pass else 0)
     t0 = time.perf_counter()
-    ratios, score_ms = score_layers(lt, W, wl, dev)
-    t_sel = time.perf_counter()
-    is_lazy, _ = lt.select_lazy(ratios, wl.n_lazy)
-    select_us = (time.perf_counter() - t_sel) * 1e6
+    stack = None
+    if args.online:
+        stack = Stack(lt, W, wl, None, total_steps, dev, args.keys_full, args.keys_lazy, online=True)
+        ratios, score_ms, is_lazy, select_us = stack.ratios, stack.score_ms, np.asarray(stack.is_lazy, np.uint8), 0.0
+        closed_form, _ = lt.select_lazy(ratios, wl.n_lazy)
+        if list(closed_form) != list(is_lazy):
+            raise RuntimeError("the queue procedure and the closed form disagree")
+    else:
+        ratios, score_ms = score_layers(lt, W, wl, dev)
+        t_sel = time.perf_counter()
+        is_lazy, _ = lt.select_lazy(ratios, wl.n_lazy)
+        select_us = (time.perf_counter() - t_sel) * 1e6
     log("scoring + selection: %.1f s wall, lazy layers %s" % (time.perf_counter() - t0, list(np.nonzero(is_lazy)[0])))
     if wl.bias == "planted" and list(np.nonzero(is_lazy)[0]) != W.planted_lazy_layers(wl):
         raise RuntimeError("selection did not recover the planted lazy layers")
@@ -224,7 +337,7 @@ def main():
     scoring = {
         "ms_per_layer": med_ms, "tflops": score_flops / med_ms / 1e9, "mfma_frac": score_flops / med_ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
         "k_gbs": score_bytes / med_ms / 1e6, "hbm_frac": score_bytes / med_ms / 1e6 / HBM_PEAK_GBS, "select_us": select_us,
-        "w_last": wl.w_last, "ratio_min": min(ratios), "ratio_max": max(ratios),
+        "w_last": wl.w_last, "ratio_min": min(ratios), "ratio_max": max(ratios), "online_queue": bool(args.online),
     }
 
     if args.scoring_only:
@@ -232,9 +345,8 @@ def main():
         return 0
 
     # ---- decode -----------------------------------------------------------------------------------------
-    profile_pass = not args.no_profile_pass
-    total_steps = Wm + K + (K if profile_pass else 0)
-    stack = Stack(lt, W, wl, is_lazy, total_steps, dev, args.keys_full, args.keys_lazy)
+    if stack is None:
+        stack = Stack(lt, W, wl, is_lazy, total_steps, dev, args.keys_full, args.keys_lazy)
     log("stack ready: KV slab %.2f GB" % (stack.ctx.kv_slab.numel() / 1e9))
     stack.run(Wm)
     T_first = stack.tokens_now() + 1

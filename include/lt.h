@@ -138,6 +138,40 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
 lt_status lt_select_lazy(const float *ratios_host, int32_t n_layers, int32_t n_lazy, uint8_t *is_lazy_out,
                          int32_t *order_out);
 
+/* ---- online identification during prefill (Section "LightTransfer-Test", Figure 3) ---------- */
+
+/* The paper's procedure: after each layer's prefill its (ratio, layer) is pushed into a
+ * max-priority queue of capacity P; when the queue overflows, the layer with the highest ratio
+ * is popped, becomes lazy, and its cache is reduced at once, which frees memory for the next
+ * layer's cache.  Peak memory is P + 1 full caches instead of L. */
+typedef struct lt_queue lt_queue; /* opaque, host memory owned by the library */
+
+/* A queue that keeps `capacity` = P entries.  *out receives it. */
+lt_status lt_queue_create(int32_t capacity, lt_queue **out);
+void lt_queue_destroy(lt_queue *q); /* NULL is allowed */
+
+/* Push one layer's ratio (pure host code).  *popped_layer receives the layer that left the queue
+ * -- the highest ratio held, ties to the lower layer index, possibly the one just pushed -- or
+ * -1 if the queue did not overflow.  NaN ratios are rejected. */
+lt_status lt_select_push(lt_queue *q, float ratio, int32_t layer, int32_t *popped_layer);
+
+/* Bytes of KV slab for the online procedure with n_full = P layers kept full:
+ * min(P + 1, L) full-size slots and L - P ring slots.  Returns 0 on invalid arguments. */
+size_t lt_kv_bytes_online(const lt_config *cfg, int32_t n_full);
+
+/* Like lt_create, but no lazy mask is known yet: every layer starts as a full layer without
+ * storage and takes a free full-size slot at its first lt_append_kv (LT_ERR_CAPACITY if all
+ * min(P + 1, L) slots are in use).  lt_reset returns every layer to that state. */
+lt_status lt_create_online(const lt_config *cfg, int32_t n_full, void *kv_slab, size_t kv_bytes, void *workspace,
+                           size_t ws_bytes, lt_ctx **out);
+
+/* Turn a full layer of an online context into a lazy one: its first w_sink and last w_recent
+ * tokens are copied (enqueued on `stream`) into a free ring slot, each to the slot lt_append_kv
+ * would have used, and its full-size slot becomes available to appends enqueued afterwards on the
+ * same stream.  The token count is unchanged.  LT_ERR_STATE if the context was made by lt_create
+ * or the layer is already lazy; LT_ERR_CAPACITY if all L - P ring slots are in use. */
+lt_status lt_truncate_layer(lt_ctx *ctx, int32_t layer, void *stream);
+
 /* ---- decoding ----------------------------------------------------------------------------- */
 
 /* Append n_new tokens (the same count for every sequence) to a layer.

@@ -56,6 +56,15 @@ size_t block_bytes(const lt_config *c, bool lazy)
     return align_up((size_t)c->batch * c->n_kv_heads * (size_t)layer_capacity(c, lazy) * ltk::kHeadDim * sizeof(uint16_t));
 }
 
+int64_t max_splits(const lt_config *c);
+
+}  // namespace
+
+struct lt_ctx;
+static void bind_workspace(lt_ctx *ctx, void *workspace);
+
+namespace {
+
 int64_t max_splits(const lt_config *c)
 {
     const int64_t full = ceil_div(c->max_tokens, kMinKeysFull);
@@ -68,6 +77,7 @@ struct Layer {
     int64_t capacity = 0;
     int64_t total = 0;
     bool lazy = false;
+    int32_t slot = -1;                          // online mode: index of the full / ring slot in use, -1 = none yet
 };
 
 struct EventPair {
@@ -88,9 +98,47 @@ struct lt_ctx {
     bool profiling = false;
     std::vector<EventPair> events;             // pool, created on first enable
     size_t events_used = 0;
+    // online mode (lt_create_online): layers take storage on demand from two pools of slots
+    bool online = false;
+    uint8_t *full_pool = nullptr, *ring_pool = nullptr;
+    std::vector<uint8_t> full_used, ring_used;
 };
 
+// Max-priority queue of (ratio, layer) with a fixed capacity; small, so a plain vector.
+struct lt_queue {
+    int32_t capacity = 0;
+    std::vector<std::pair<float, int32_t>> entries;
+};
+
+static void bind_workspace(lt_ctx *ctx, void *workspace)
+{
+    const lt_config *cfg = &ctx->cfg;
+    ctx->splits_cap = max_splits(cfg);
+    const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)ctx->splits_cap;
+    uint8_t *ws = static_cast<uint8_t *>(workspace);
+    ctx->part_acc = static_cast<float *>(workspace);
+    ctx->part_ml = reinterpret_cast<float *>(ws + align_up(rows * ltk::kHeadDim * sizeof(float)));
+    ctx->tickets = reinterpret_cast<unsigned int *>(ws + align_up(rows * ltk::kHeadDim * sizeof(float)) +
+                                                    align_up(rows * 2 * sizeof(float)));
+}
+
 namespace {
+
+// Online mode: give a layer without storage a free full-size slot.
+lt_status assign_full_slot(lt_ctx *ctx, Layer &l)
+{
+    for (size_t i = 0; i < ctx->full_used.size(); ++i) {
+        if (ctx->full_used[i]) continue;
+        ctx->full_used[i] = 1;
+        const size_t bytes = block_bytes(&ctx->cfg, false);
+        uint8_t *base = ctx->full_pool + i * 2 * bytes;
+        l.k = reinterpret_cast<uint16_t *>(base);
+        l.v = reinterpret_cast<uint16_t *>(base + bytes);
+        l.slot = (int32_t)i;
+        return LT_OK;
+    }
+    return LT_ERR_CAPACITY;
+}
 
 // Keys per workgroup.  Measured on MI355X, the decode kernel streams fastest with ONE workgroup
 // (four wavefronts, 16 KB of loads in flight each) per compute unit reading one long contiguous
@@ -191,13 +239,48 @@ lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab,
         l.v = reinterpret_cast<uint16_t *>(cursor + bytes);
         cursor += 2 * bytes;
     }
-    ctx->splits_cap = max_splits(cfg);
-    const size_t rows = (size_t)cfg->batch * cfg->n_q_heads * (size_t)ctx->splits_cap;
-    ctx->part_acc = static_cast<float *>(workspace);
-    uint8_t *ws = static_cast<uint8_t *>(workspace);
-    ctx->part_ml = reinterpret_cast<float *>(ws + align_up(rows * ltk::kHeadDim * sizeof(float)));
-    ctx->tickets = reinterpret_cast<unsigned int *>(ws + align_up(rows * ltk::kHeadDim * sizeof(float)) +
-                                                    align_up(rows * 2 * sizeof(float)));
+    bind_workspace(ctx, workspace);
+    *out = ctx;
+    return LT_OK;
+}
+
+size_t lt_kv_bytes_online(const lt_config *cfg, int32_t n_full)
+{
+    if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n_full < 0 || n_full > cfg->n_layers) return 0;
+    const int32_t full_slots = std::min(n_full + 1, cfg->n_layers);
+    return (size_t)full_slots * 2 * block_bytes(cfg, false) + (size_t)(cfg->n_layers - n_full) * 2 * block_bytes(cfg, true);
+}
+
+lt_status lt_create_online(const lt_config *cfg, int32_t n_full, void *kv_slab, size_t kv_bytes, void *workspace,
+                           size_t ws_bytes, lt_ctx **out)
+{
+    if (out == nullptr) return LT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!config_ok(cfg) || kv_slab == nullptr || workspace == nullptr || n_full < 0) return LT_ERR_INVALID_ARG;
+    const lt_status shape = config_shape(cfg);
+    if (shape != LT_OK) return shape;
+    if (n_full > cfg->n_layers) return LT_ERR_INVALID_ARG;
+    if (((uintptr_t)kv_slab % kAlign) != 0 || ((uintptr_t)workspace % kAlign) != 0) return LT_ERR_INVALID_ARG;
+    if (kv_bytes < lt_kv_bytes_online(cfg, n_full) || ws_bytes < lt_workspace_bytes(cfg)) return LT_ERR_CAPACITY;
+
+    lt_ctx *ctx = new (std::nothrow) lt_ctx();
+    if (ctx == nullptr) return LT_ERR_NOMEM;
+    ctx->cfg = *cfg;
+    ctx->cfg.softmax_scale = effective_scale(cfg);
+    ctx->online = true;
+    const int32_t full_slots = std::min(n_full + 1, cfg->n_layers);
+    try {
+        ctx->layers.resize(cfg->n_layers);
+        ctx->full_used.assign(full_slots, 0);
+        ctx->ring_used.assign(cfg->n_layers - n_full, 0);
+    } catch (const std::bad_alloc &) {
+        delete ctx;
+        return LT_ERR_NOMEM;
+    }
+    ctx->full_pool = static_cast<uint8_t *>(kv_slab);
+    ctx->ring_pool = ctx->full_pool + (size_t)full_slots * 2 * block_bytes(cfg, false);
+    for (Layer &l : ctx->layers) l.capacity = cfg->max_tokens;          // every layer starts out full, without storage
+    bind_workspace(ctx, workspace);
     *out = ctx;
     return LT_OK;
 }
@@ -215,7 +298,17 @@ void lt_destroy(lt_ctx *ctx)
 lt_status lt_reset(lt_ctx *ctx)
 {
     if (ctx == nullptr) return LT_ERR_INVALID_ARG;
-    for (Layer &l : ctx->layers) l.total = 0;
+    for (Layer &l : ctx->layers) {
+        l.total = 0;
+        if (ctx->online) {                      // back to "full, no storage yet"
+            l.k = l.v = nullptr;
+            l.slot = -1;
+            l.lazy = false;
+            l.capacity = ctx->cfg.max_tokens;
+        }
+    }
+    std::fill(ctx->full_used.begin(), ctx->full_used.end(), 0);
+    std::fill(ctx->ring_used.begin(), ctx->ring_used.end(), 0);
     return LT_OK;
 }
 
@@ -333,6 +426,10 @@ lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void
     Layer &l = ctx->layers[layer];
     if (n_new > kMaxTokens || l.total + n_new > kMaxTokens) return LT_ERR_CAPACITY;
     if (!l.lazy && l.total + n_new > l.capacity) return LT_ERR_CAPACITY;
+    if (ctx->online && l.slot < 0) {
+        const lt_status st = assign_full_slot(ctx, l);
+        if (st != LT_OK) return st;             // every full-size slot is taken: truncate a layer first
+    }
     if (l.capacity > 0) {                       // a lazy layer with an empty window stores nothing
         ltk::AppendArgs a{};
         a.k_new = static_cast<const uint16_t *>(k_new);
@@ -425,6 +522,88 @@ lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *
 {
     if (k_new == nullptr || v_new == nullptr) return LT_ERR_INVALID_ARG;
     return launch_decode(ctx, layer, q, k_new, v_new, out, lse_out, stream);
+}
+
+// ---- online identification during prefill ------------------------------------------------------
+
+lt_status lt_queue_create(int32_t capacity, lt_queue **out)
+{
+    if (out == nullptr) return LT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (capacity < 0) return LT_ERR_INVALID_ARG;
+    lt_queue *q = new (std::nothrow) lt_queue();
+    if (q == nullptr) return LT_ERR_NOMEM;
+    q->capacity = capacity;
+    try {
+        q->entries.reserve((size_t)capacity + 1);
+    } catch (const std::bad_alloc &) {
+        delete q;
+        return LT_ERR_NOMEM;
+    }
+    *out = q;
+    return LT_OK;
+}
+
+void lt_queue_destroy(lt_queue *q) { delete q; }
+
+lt_status lt_select_push(lt_queue *q, float ratio, int32_t layer, int32_t *popped_layer)
+{
+    if (q == nullptr || popped_layer == nullptr || layer < 0 || std::isnan(ratio)) return LT_ERR_INVALID_ARG;
+    *popped_layer = -1;
+    q->entries.emplace_back(ratio, layer);      // capacity + 1 was reserved
+    if ((int64_t)q->entries.size() <= q->capacity) return LT_OK;
+    size_t top = 0;                             // highest ratio, ties to the lower layer index
+    for (size_t i = 1; i < q->entries.size(); ++i) {
+        const auto &e = q->entries[i], &t = q->entries[top];
+        if (e.first > t.first || (e.first == t.first && e.second < t.second)) top = i;
+    }
+    *popped_layer = q->entries[top].second;
+    q->entries[top] = q->entries.back();
+    q->entries.pop_back();
+    return LT_OK;
+}
+
+lt_status lt_truncate_layer(lt_ctx *ctx, int32_t layer, void *stream)
+{
+    if (ctx == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
+    if (!ctx->online) return LT_ERR_STATE;
+    Layer &l = ctx->layers[layer];
+    if (l.lazy) return LT_ERR_STATE;
+    const lt_config &c = ctx->cfg;
+    const int64_t window = window_of(&c);
+    size_t ring = ctx->ring_used.size();
+    for (size_t i = 0; i < ctx->ring_used.size(); ++i)
+        if (!ctx->ring_used[i]) { ring = i; break; }
+    if (ring == ctx->ring_used.size()) return LT_ERR_CAPACITY;      // more lazy layers than the context was sized for
+    const size_t ring_bytes = block_bytes(&c, true);
+    uint16_t *k_ring = reinterpret_cast<uint16_t *>(ctx->ring_pool + ring * 2 * ring_bytes);
+    uint16_t *v_ring = reinterpret_cast<uint16_t *>(ctx->ring_pool + ring * 2 * ring_bytes + ring_bytes);
+    if (l.slot >= 0 && l.total > 0 && window > 0) {
+        ltk::TruncateArgs a{};
+        a.k_full = l.k;
+        a.v_full = l.v;
+        a.k_ring = k_ring;
+        a.v_ring = v_ring;
+        a.stride_h_full = l.capacity * ltk::kHeadDim;
+        a.stride_b_full = a.stride_h_full * c.n_kv_heads;
+        a.stride_h_ring = window * ltk::kHeadDim;
+        a.stride_b_ring = a.stride_h_ring * c.n_kv_heads;
+        a.total = l.total;
+        a.batch = c.batch;
+        a.n_kv_heads = c.n_kv_heads;
+        a.w_sink = c.w_sink;
+        a.w_recent = c.w_recent;
+        ScopedEvents ev(ctx, static_cast<hipStream_t>(stream), LT_KERNEL_APPEND);
+        if (ltk::truncate(a, static_cast<hipStream_t>(stream)) != hipSuccess) return LT_ERR_HIP;
+    }
+    if (l.slot >= 0) ctx->full_used[l.slot] = 0;     // reusable by work enqueued later on the same stream
+    ctx->ring_used[ring] = 1;
+    l.k = k_ring;
+    l.v = v_ring;
+    l.slot = (int32_t)ring;
+    l.lazy = true;
+    l.capacity = window;
+    return LT_OK;
 }
 
 // ---- tuning and measurement --------------------------------------------------------------------

@@ -87,6 +87,30 @@ __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
 }
 
 // ---------------------------------------------------------------------------------------------
+// truncate: a layer that turns lazy keeps the first w_sink and the last w_recent of its `total`
+// tokens; they move from its full-size block into a ring block (disjoint memory), each token to
+// the slot the append rule would have given it.  One thread moves 16 bytes of K and of V.
+// ---------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void lt_truncate_kernel(TruncateArgs a)
+{
+    const int64_t n_sink = a.total < a.w_sink ? a.total : a.w_sink;
+    const int64_t first_recent = (a.total - a.w_recent) > a.w_sink ? (a.total - a.w_recent) : a.w_sink;
+    const int64_t n_recent = a.total > first_recent ? a.total - first_recent : 0;
+    const int64_t per_stream = (n_sink + n_recent) * 16;
+    const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (idx >= per_stream) return;
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int64_t j = idx >> 4;
+    const int c = (int)(idx & 15);
+    const int64_t p = j < n_sink ? j : first_recent + (j - n_sink);          // absolute position
+    const int64_t slot = p < a.w_sink ? p : a.w_sink + (p - a.w_sink) % a.w_recent;
+    const int64_t src = (int64_t)b * a.stride_b_full + (int64_t)g * a.stride_h_full + p * kHeadDim + c * 8;
+    const int64_t dst = (int64_t)b * a.stride_b_ring + (int64_t)g * a.stride_h_ring + slot * kHeadDim + c * 8;
+    store16(a.k_ring + dst, load16(a.k_full + src));
+    store16(a.v_ring + dst, load16(a.v_full + src));
+}
+
+// ---------------------------------------------------------------------------------------------
 // split decode attention.
 //
 // Lane layout inside a wavefront: lane = 16*sub + chunk.  One 16-byte load per lane covers four
@@ -432,6 +456,14 @@ hipError_t append(const AppendArgs &a, hipStream_t stream)
     const int64_t per_stream = a.n_new * 16;
     const dim3 grid((unsigned)((per_stream + 255) / 256), a.n_kv_heads, a.batch);
     hipLaunchKernelGGL(lt_append_kv_kernel, grid, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+hipError_t truncate(const TruncateArgs &a, hipStream_t stream)
+{
+    const int64_t kept = (a.total < a.w_sink ? a.total : a.w_sink) + (a.total < a.w_recent ? a.total : a.w_recent);
+    const dim3 grid((unsigned)((kept * 16 + 255) / 256), a.n_kv_heads, a.batch);    // an upper bound on the kept tokens
+    hipLaunchKernelGGL(lt_truncate_kernel, grid, dim3(256), 0, stream, a);
     return hipGetLastError();
 }
 

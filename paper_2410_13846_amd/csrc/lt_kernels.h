@@ -26,6 +26,15 @@ struct AppendArgs {
 };
 hipError_t append(const AppendArgs &a, hipStream_t stream);
 
+struct TruncateArgs {
+    const uint16_t *k_full, *v_full;   // full-layer blocks [B][Hkv][cap_full][128]
+    uint16_t *k_ring, *v_ring;         // ring blocks       [B][Hkv][w_sink + w_recent][128]
+    int64_t stride_b_full, stride_h_full, stride_b_ring, stride_h_ring;
+    int64_t total;                     // tokens the layer holds
+    int32_t batch, n_kv_heads, w_sink, w_recent;
+};
+hipError_t truncate(const TruncateArgs &a, hipStream_t stream);
+
 struct DecodeArgs {
     uint16_t *k_cache, *v_cache;
     const uint16_t *k_new, *v_new;     // [B][Hkv][128] token of this step to append on the fly, or nullptr

@@ -20,6 +20,7 @@ EXPORTS = [
     "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
     "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
     "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
+    "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
 ]
 
 
@@ -87,6 +88,18 @@ def load() -> ctypes.CDLL:
     lib.lt_profile_enable.restype = ctypes.c_int
     lib.lt_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
     lib.lt_profile_read.restype = ctypes.c_int
+    lib.lt_queue_create.argtypes = [i32, ctypes.POINTER(vp)]
+    lib.lt_queue_create.restype = ctypes.c_int
+    lib.lt_queue_destroy.argtypes = [vp]
+    lib.lt_queue_destroy.restype = None
+    lib.lt_select_push.argtypes = [vp, ctypes.c_float, i32, ctypes.POINTER(i32)]
+    lib.lt_select_push.restype = ctypes.c_int
+    lib.lt_kv_bytes_online.argtypes = [cfgp, i32]
+    lib.lt_kv_bytes_online.restype = sz
+    lib.lt_create_online.argtypes = [cfgp, i32, vp, sz, vp, sz, ctypes.POINTER(vp)]
+    lib.lt_create_online.restype = ctypes.c_int
+    lib.lt_truncate_layer.argtypes = [vp, i32, vp]
+    lib.lt_truncate_layer.restype = ctypes.c_int
     lib.lt_status_str.argtypes = [ctypes.c_int]
     lib.lt_status_str.restype = ctypes.c_char_p
     _lib = lib
@@ -172,26 +185,72 @@ def lazy_ratio(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_las
     return mean, seq, rho
 
 
-class Context:
-    """Owns the torch tensors used as KV slab and workspace, and the library's host-side context."""
+class SelectQueue:
+    """The max-priority queue of the online procedure (host only)."""
 
-    def __init__(self, cfg: Config, is_lazy, device="cuda:0"):
+    def __init__(self, capacity: int):
+        handle = ctypes.c_void_p()
+        _check(load().lt_queue_create(int(capacity), ctypes.byref(handle)), "lt_queue_create")
+        self._h = handle
+
+    def push(self, ratio: float, layer: int) -> int:
+        """Returns the layer that left the queue, or -1."""
+        popped = ctypes.c_int32(-1)
+        _check(load().lt_select_push(self._h, float(ratio), int(layer), ctypes.byref(popped)), "lt_select_push")
+        return popped.value
+
+    def close(self):
+        if getattr(self, "_h", None):
+            load().lt_queue_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def kv_bytes_online(cfg: Config, n_full: int) -> int:
+    return int(load().lt_kv_bytes_online(ctypes.byref(cfg), int(n_full)))
+
+
+class Context:
+    """Owns the torch tensors used as KV slab and workspace, and the library's host-side context.
+
+    With a lazy mask: lt_create.  With `n_full_online` instead: lt_create_online (layers take storage on
+    demand and turn lazy through truncate_layer)."""
+
+    def __init__(self, cfg: Config, is_lazy=None, device="cuda:0", n_full_online: Optional[int] = None):
         lib = load()
         self.cfg = cfg
-        self.is_lazy = _mask_array(is_lazy)
-        if self.is_lazy.shape[0] != cfg.n_layers:
-            raise ValueError("is_lazy needs one entry per layer")
-        kvb, wsb = kv_bytes(cfg, self.is_lazy), workspace_bytes(cfg)
+        online = n_full_online is not None
+        if online:
+            kvb = kv_bytes_online(cfg, n_full_online)
+        else:
+            self.is_lazy = _mask_array(is_lazy)
+            if self.is_lazy.shape[0] != cfg.n_layers:
+                raise ValueError("is_lazy needs one entry per layer")
+            kvb = kv_bytes(cfg, self.is_lazy)
+        wsb = workspace_bytes(cfg)
         if kvb == 0 or wsb == 0:
             raise LtError(ERR_INVALID_ARG, "lt_kv_bytes / lt_workspace_bytes")
         self.device = torch.device(device)
         self.kv_slab = torch.empty(kvb, dtype=torch.uint8, device=self.device)
         self.workspace = torch.empty(wsb, dtype=torch.uint8, device=self.device)
         handle = ctypes.c_void_p()
-        st = lib.lt_create(ctypes.byref(cfg), self.is_lazy.ctypes.data, self.kv_slab.data_ptr(), kvb,
-                           self.workspace.data_ptr(), wsb, ctypes.byref(handle))
-        _check(st, "lt_create")
+        if online:
+            st = lib.lt_create_online(ctypes.byref(cfg), int(n_full_online), self.kv_slab.data_ptr(), kvb,
+                                      self.workspace.data_ptr(), wsb, ctypes.byref(handle))
+            _check(st, "lt_create_online")
+        else:
+            st = lib.lt_create(ctypes.byref(cfg), self.is_lazy.ctypes.data, self.kv_slab.data_ptr(), kvb,
+                               self.workspace.data_ptr(), wsb, ctypes.byref(handle))
+            _check(st, "lt_create")
         self._h = handle
+
+    def truncate_layer(self, layer: int, stream=None):
+        _check(load().lt_truncate_layer(self._h, int(layer), _stream_ptr(stream)), "lt_truncate_layer")
 
     def close(self):
         if getattr(self, "_h", None):

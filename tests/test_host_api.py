@@ -161,3 +161,76 @@ def test_select_lazy_rejects_bad_input():
     with pytest.raises(lt.LtError):
         lt.select_lazy(np.array([0.5, 0.1], np.float32), 3)
     assert lt.status_str(lt.ERR_CAPACITY) == "capacity exceeded"
+
+
+# ---- online identification (priority queue + slot pools), host side only -----------------------
+
+def test_select_push_reproduces_the_queue_procedure():
+    rng = np.random.default_rng(11)
+    for L in (1, 2, 7, 32, 64):
+        for trial in range(10):
+            r = rng.random(L).astype(np.float32)
+            if trial % 2:
+                r = (np.round(r * 4) / 4).astype(np.float32)        # ties
+            for n_lazy in sorted({0, 1, L // 2, L - 1, L}):
+                q = lt.SelectQueue(L - n_lazy)
+                popped_at = np.full(L, -1, dtype=np.int32)
+                for layer in range(L):
+                    out = q.push(r[layer], layer)
+                    if out >= 0:
+                        assert popped_at[out] < 0
+                        popped_at[out] = layer
+                q.close()
+                ref_lazy, ref_pop = oracle.select_lazy_queue(r.astype(np.float64), n_lazy)
+                np.testing.assert_array_equal(popped_at, ref_pop)
+                np.testing.assert_array_equal((popped_at >= 0).astype(np.uint8), ref_lazy)
+                closed_form, _ = lt.select_lazy(r, n_lazy)
+                np.testing.assert_array_equal(closed_form, ref_lazy)
+
+
+def test_select_push_rejects_bad_input():
+    q = lt.SelectQueue(2)
+    with pytest.raises(lt.LtError) as e:
+        q.push(float("nan"), 0)
+    assert e.value.status == lt.ERR_INVALID_ARG
+    with pytest.raises(lt.LtError):
+        q.push(0.5, -1)
+    q.close()
+    with pytest.raises(lt.LtError):
+        lt.SelectQueue(-1)
+
+
+def test_online_context_sizes_and_slot_accounting():
+    lib, c = lt.load(), cfg()                     # 4 layers, full = 1000 tokens, ring = 64 tokens
+    per_token = 2 * 2 * 128 * 2
+    full, ring = 2 * per_token * 1000, 2 * per_token * 64
+    assert lt.kv_bytes_online(c, 2) == 3 * full + 2 * ring        # P + 1 full slots, L - P rings
+    assert lt.kv_bytes_online(c, 4) == 4 * full                   # nothing turns lazy
+    assert lt.kv_bytes_online(c, 0) == 1 * full + 4 * ring
+    assert lt.kv_bytes_online(c, 5) == 0
+    handle = ctypes.c_void_p()
+    need = lt.kv_bytes_online(c, 2)
+    assert lib.lt_create_online(ctypes.byref(c), 2, FAKE_DEV, need - 1, FAKE_DEV + (1 << 34), lt.workspace_bytes(c),
+                                ctypes.byref(handle)) == lt.ERR_CAPACITY
+    assert lib.lt_create_online(ctypes.byref(c), 2, FAKE_DEV, need, FAKE_DEV + (1 << 34), lt.workspace_bytes(c),
+                                ctypes.byref(handle)) == lt.OK
+    # no layer has storage yet; decode is out of order, truncating an empty full layer only flips its kind
+    k, v = ctypes.c_void_p(1), ctypes.c_void_p(1)
+    cap, lazy = ctypes.c_int64(), ctypes.c_int32()
+    assert lib.lt_layer_view(handle, 0, ctypes.byref(k), ctypes.byref(v), None, None, ctypes.byref(cap), ctypes.byref(lazy)) == lt.OK
+    assert (k.value, v.value, cap.value, lazy.value) == (None, None, 1000, 0)
+    assert lib.lt_decode_attn(handle, 0, FAKE_DEV, FAKE_DEV, None, None) == lt.ERR_STATE
+    assert lib.lt_truncate_layer(handle, 0, None) == lt.OK
+    assert lib.lt_layer_view(handle, 0, ctypes.byref(k), None, None, None, ctypes.byref(cap), ctypes.byref(lazy)) == lt.OK
+    assert (k.value, cap.value, lazy.value) == (FAKE_DEV + 3 * full, 64, 1)
+    assert lib.lt_truncate_layer(handle, 0, None) == lt.ERR_STATE          # already lazy
+    assert lib.lt_truncate_layer(handle, 1, None) == lt.OK
+    assert lib.lt_truncate_layer(handle, 2, None) == lt.ERR_CAPACITY       # only L - P = 2 rings
+    assert lib.lt_reset(handle) == lt.OK
+    assert lib.lt_layer_view(handle, 0, ctypes.byref(k), None, None, None, ctypes.byref(cap), ctypes.byref(lazy)) == lt.OK
+    assert (k.value, cap.value, lazy.value) == (None, 1000, 0)
+    lib.lt_destroy(handle)
+    # a context with a fixed mask cannot be truncated
+    h = make_ctx(c, [0, 1, 0, 1])
+    assert lib.lt_truncate_layer(h, 0, None) == lt.ERR_STATE
+    lib.lt_destroy(h)
