@@ -31,16 +31,6 @@ __device__ __forceinline__ float dpp_move(float x)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
 }
 
-// Sum over the 16 lanes of a DPP row; every lane of the row receives the total.
-__device__ __forceinline__ float row16_allsum(float x)
-{
-    x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
-    x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
-    x += dpp_move<0x141>(x);  // row_half_mirror
-    x += dpp_move<0x140>(x);  // row_mirror
-    return x;
-}
-
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;   // 16 bytes as one register quad
 
 // Every pointer the kernels see is device memory: say so, or a pointer chosen at run time
@@ -129,19 +119,28 @@ struct Tile {
 // fused into the decode: its K/V are read from the caller's k_new / v_new instead of the cache.
 // Every path issues the same eight loads in the same order, so the wait counts of the software
 // pipeline stay exact; only the addresses differ, and only in the one tile that holds new_slot.
+//
+// key0 < 0 marks a fetch past the wavefront's last tile, issued only to keep the load count of
+// the pipeline fixed: it reads `hot` (the query vector, already in cache) so that nothing after
+// the loop has to wait a full memory latency for data nobody uses.
 __device__ __forceinline__ void load_tile(Tile &t, const uint16_t *kb, const uint16_t *vb, int key0, int sub, int chunk,
-                                          int last_key, int new_slot, const uint16_t *k_new, const uint16_t *v_new)
+                                          int last_key, int new_slot, const uint16_t *k_new, const uint16_t *v_new,
+                                          const uint16_t *hot)
 {
     const uint16_t *kp[4], *vp[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         int key = key0 + 4 * i + sub;
         key = key < last_key ? key : last_key;                      // clamp: masked later
+        key = key > 0 ? key : 0;
         const int64_t off = (int64_t)key * kHeadDim + chunk * 8;
         kp[i] = kb + off;
         vp[i] = vb + off;
     }
-    if (new_slot >= key0 && new_slot < key0 + 16) {                 // wave-uniform, true for one tile of one workgroup
+    if (key0 < 0) {                                                 // wave-uniform
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { kp[i] = hot + chunk * 8; vp[i] = hot + chunk * 8; }
+    } else if (new_slot >= key0 && new_slot < key0 + 16) {                 // wave-uniform, true for one tile of one workgroup
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             int key = key0 + 4 * i + sub;
@@ -174,6 +173,11 @@ __device__ __forceinline__ void store_new_token(const Tile &t, uint16_t *kb, uin
     }
 }
 
+// Online-softmax state of one 16-lane row.  m (running max, log2 units) is the same in all 16
+// lanes of the row.  After the q.k reduction each quad of the row (lanes 4i..4i+3) holds the
+// logits of ONE of the row's four keys of a tile (key 4i + sub), for all G heads; l accumulates in
+// that layout, so the row's sum is the sum over one lane of each quad.  acc is the row's
+// un-normalised output for the lane's eight dims.
 template <int G>
 struct RowState {
     float m[G];
@@ -181,35 +185,100 @@ struct RowState {
     float acc[G][8];
 };
 
+// Sum of x over the lanes {l, 15-l} (row_mirror) or {l, 7-l} (row_half_mirror) of a DPP row.
+__device__ __forceinline__ float add_mirror(float keep, float send) { return keep + dpp_move<0x140>(send); }
+__device__ __forceinline__ float add_half_mirror(float keep, float send) { return keep + dpp_move<0x141>(send); }
+
+// Cross-row exchange (gfx950): with a' and b' the values after the call,
+//   swap_rows16: a' = {a.row0, b.row0, a.row2, b.row2},  b' = {a.row1, b.row1, a.row3, b.row3}
+//   swap_rows32: a' = {a.row0, a.row1, b.row0, b.row1},  b' = {a.row2, a.row3, b.row2, b.row3}
+// (rows are the four 16-lane groups of the wavefront).
+// Written as inline assembly: with this toolchain the corresponding builtins compile to code
+// that treats their two results as one value.  Both operands are rewritten in place; the
+// s_nop keep the wait states these instructions need around other vector instructions, which
+// the compiler does not track inside an asm statement.
+__device__ __forceinline__ void swap_rows16(float &a, float &b)
+{
+    asm volatile("s_nop 1\n\tv_permlane16_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ void swap_rows32(float &a, float &b)
+{
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+
+// Maximum of x over the four rows, in every row.
+__device__ __forceinline__ float max_rows(float x)
+{
+    float a = x, b = x;
+    swap_rows16(a, b);                      // a: rows {0,0,2,2}, b: rows {1,1,3,3} of x
+    const float m = fmaxf(a, b);
+    a = m;
+    b = m;
+    swap_rows32(a, b);                      // a: rows {0,1,0,1}, b: rows {2,3,2,3} of m
+    return fmaxf(a, b);
+}
+
+// Sums x0..x3 over the four rows; row r of the result holds the total of x_r.
+__device__ __forceinline__ float sum_rows4(float x0, float x1, float x2, float x3)
+{
+    swap_rows16(x0, x1);                    // x0 + x1: rows 0,2 hold x0 over row pairs, rows 1,3 hold x1
+    swap_rows16(x2, x3);
+    float a = x0 + x1, b = x2 + x3;
+    swap_rows32(a, b);                      // a + b: rows 0,1 come from the first pair, rows 2,3 from the second
+    return a + b;
+}
+
+template <int LANE>
+__device__ __forceinline__ float row_broadcast(float x)      // value of lane LANE of the row, in every lane of the row
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + LANE, 0xf, 0xf, false));
+}
+
 template <int G>
 __device__ __forceinline__ void process_tile(const Tile &t, const uint32_t (&qf)[G][4], RowState<G> &st, int key0, int sub,
-                                             int end_key, float scale_log2e)
+                                             int chunk, int end_key, float scale_log2e)
 {
-    float s[4][G];
+    // Partial dot products: lane (sub, chunk) covers dims 8*chunk..8*chunk+7 of keys key0 + 4*i + sub.
+    float part[4][G];
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        const bool valid = key0 + 4 * i + sub < end_key;
+    for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int h = 0; h < G; ++h) {
             float x = dot2_bf16(t.k[i][0], qf[h][0], 0.f);
             x = dot2_bf16(t.k[i][1], qf[h][1], x);
             x = dot2_bf16(t.k[i][2], qf[h][2], x);
-            x = dot2_bf16(t.k[i][3], qf[h][3], x);
-            x = row16_allsum(x) * scale_log2e;
-            s[i][h] = valid ? x : -INFINITY;
+            part[i][h] = dot2_bf16(t.k[i][3], qf[h][3], x);
         }
-    }
-    bool grow = false;
-    float tmax[G];
+    // Reduce over the 16 lanes of the row and scatter at the same time: each step pairs every lane
+    // with one in the other half (then the other quad), keeps the keys of its own half and hands
+    // the others over, so the number of values halves; a last all-reduce inside the quad leaves
+    // quad i with the complete logits of key i.  44 instructions instead of 64 for a full
+    // all-reduce, and the exponentials that follow are computed 4 times instead of 16.
+    const bool upper_half = (chunk & 8) != 0, upper_quad = (chunk & 4) != 0;
+    float s[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        tmax[h] = fmaxf(fmaxf(s[0][h], s[1][h]), fmaxf(s[2][h], s[3][h]));
-        grow |= tmax[h] > st.m[h];
+        const float a0 = add_mirror(upper_half ? part[2][h] : part[0][h], upper_half ? part[0][h] : part[2][h]);
+        const float a1 = add_mirror(upper_half ? part[3][h] : part[1][h], upper_half ? part[1][h] : part[3][h]);
+        float x = add_half_mirror(upper_quad ? a1 : a0, upper_quad ? a0 : a1);
+        x += dpp_move<0xB1>(x);   // quad_perm [1,0,3,2]
+        x += dpp_move<0x4E>(x);   // quad_perm [2,3,0,1]
+        s[h] = x * scale_log2e;
+    }
+    const int my_key = key0 + (chunk & 12) + sub;                   // quad i = chunk / 4 holds key 4*i + sub
+    const bool valid = my_key < end_key;
+    bool grow = false;
+#pragma unroll
+    for (int h = 0; h < G; ++h) {
+        s[h] = valid ? s[h] : -INFINITY;
+        grow |= s[h] > st.m[h];
     }
     if (__any(grow)) {                                              // rare after the first tiles
 #pragma unroll
         for (int h = 0; h < G; ++h) {
-            const float m_new = fmaxf(st.m[h], tmax[h]);
+            float tmax = fmaxf(s[h], dpp_move<0x141>(s[h]));        // max over the row's four keys
+            tmax = fmaxf(tmax, dpp_move<0x140>(tmax));
+            const float m_new = fmaxf(st.m[h], tmax);
             const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(st.m[h] - m_new);
             st.m[h] = m_new;
             st.l[h] *= alpha;
@@ -217,33 +286,37 @@ __device__ __forceinline__ void process_tile(const Tile &t, const uint32_t (&qf)
             for (int e = 0; e < 8; ++e) st.acc[h][e] *= alpha;
         }
     }
-    float p[4][G];
+    float p[G];
 #pragma unroll
     for (int h = 0; h < G; ++h) {
         const float m_safe = (st.m[h] == -INFINITY) ? 0.f : st.m[h];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            p[i][h] = fast_exp2(s[i][h] - m_safe);
-            st.l[h] += p[i][h];
-        }
+        p[h] = fast_exp2(s[h] - m_safe);
+        st.l[h] += p[h];
     }
+    // P.V: the probability of key 4*i + sub sits in quad i; broadcast it over the row for load i.
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float vf[8];
 #pragma unroll
         for (int e = 0; e < 4; ++e) { vf[2 * e] = bf16_lo(t.v[i][e]); vf[2 * e + 1] = bf16_hi(t.v[i][e]); }
 #pragma unroll
-        for (int h = 0; h < G; ++h)
+        for (int h = 0; h < G; ++h) {
+            const float pb = i == 0 ? row_broadcast<0>(p[h]) : i == 1 ? row_broadcast<4>(p[h])
+                           : i == 2 ? row_broadcast<8>(p[h]) : row_broadcast<12>(p[h]);
 #pragma unroll
-            for (int e = 0; e < 8; ++e) st.acc[h][e] = fmaf(p[i][h], vf[e], st.acc[h][e]);
+            for (int e = 0; e < 8; ++e) st.acc[h][e] = fmaf(pb, vf[e], st.acc[h][e]);
+        }
     }
 }
 
-// LAZY_TAG only gives full and lazy layers distinct kernel names in profiles.
-template <int G, int LAZY_TAG>
-__global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
+// LAZY_TAG only gives full and lazy layers distinct kernel names in profiles.  kWaves wavefronts
+// per workgroup: four when a workgroup has a long range to stream (memory-bound: more wavefronts
+// per compute unit only lower the bandwidth), eight when the range is short and the launch is
+// bound by how fast one wavefront gets through its tiles.
+template <int G, int LAZY_TAG, int kWaves>
+__global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
 {
-    constexpr int kWaves = kDecodeThreads / 64;
+    constexpr int kThreads = 64 * kWaves;
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
     __shared__ float sh_acc[kWaves][G][kHeadDim];
@@ -266,10 +339,11 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
     const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
-    auto fetch = [&](Tile &t, int key0) { load_tile(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new); };
+    const uint16_t *hot = a.q + ((int64_t)b * a.n_q_heads + g * G) * kHeadDim;
+    auto fetch = [&](Tile &t, int key0) { load_tile(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new, hot); };
     auto consume = [&](const Tile &t, int key0, RowState<G> &st, const uint32_t (&qf)[G][4]) {
         store_new_token(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot);
-        process_tile<G>(t, qf, st, key0, sub, end_key, a.scale_log2e);
+        process_tile<G>(t, qf, st, key0, sub, chunk, end_key, a.scale_log2e);
     };
 
     uint32_t qf[G][4];
@@ -301,13 +375,13 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
     const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
     const int phase = (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)n_tiles);
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
-    int next_tile = wave + phase;
+    int next_tile = wave + phase, fetched = 0;
     while (next_tile >= n_tiles) next_tile -= n_tiles;
-    auto advance = [&]() {
+    auto advance = [&]() {                                          // first key of the next tile to fetch, -1 past the last
         const int cur = next_tile;
         next_tile += kWaves;
         while (next_tile >= n_tiles) next_tile -= n_tiles;
-        return begin_key + 16 * cur;
+        return fetched++ < my_tiles ? begin_key + 16 * cur : -1;
     };
     Tile t0, t1;
     int key0 = advance();
@@ -321,39 +395,45 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
         if (k + 1 < my_tiles) consume(t1, key1, st, qf);
     }
 
-    // Merge the four rows of the wavefront.
+    // Merge the four rows of the wavefront with the cross-row swap instructions of gfx950 (vector
+    // ALU, no LDS round trips).  First the rows agree on a common maximum per head and rescale;
+    // then sum_rows4 adds four different values over the four rows at once and leaves the total
+    // of value number r in row r, so every lane ends up owning two of its eight dims.
 #pragma unroll
     for (int h = 0; h < G; ++h) {
-        float mx = fmaxf(st.m[h], __shfl_xor(st.m[h], 16));
-        mx = fmaxf(mx, __shfl_xor(mx, 32));
+        const float mx = max_rows(st.m[h]);
         const float wgt = (st.m[h] == -INFINITY) ? 0.f : fast_exp2(st.m[h] - mx);
-        float l = st.l[h] * wgt;
-        l += __shfl_xor(l, 16);
-        l += __shfl_xor(l, 32);
+        float l = st.l[h];
+        l += dpp_move<0x141>(l);                                   // one lane of each quad: the row's sum
+        l += dpp_move<0x140>(l);
+        st.l[h] = l * wgt;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            float x = st.acc[h][e] * wgt;
-            x += __shfl_xor(x, 16);
-            x += __shfl_xor(x, 32);
-            st.acc[h][e] = x;
-        }
+        for (int e = 0; e < 8; ++e) st.acc[h][e] *= wgt;
         st.m[h] = mx;
-        st.l[h] = l;
     }
-    if (sub == 0) {
 #pragma unroll
-        for (int h = 0; h < G; ++h) {
-            if (chunk == 0) { sh_m[wave][h] = st.m[h]; sh_l[wave][h] = st.l[h]; }
+    for (int h = 0; h < G; ++h) {
+        const float lo = sum_rows4(st.acc[h][0], st.acc[h][1], st.acc[h][2], st.acc[h][3]);   // row r: dim 8*chunk + r
+        const float hi = sum_rows4(st.acc[h][4], st.acc[h][5], st.acc[h][6], st.acc[h][7]);   // row r: dim 8*chunk + 4 + r
+        sh_acc[wave][h][chunk * 8 + sub] = lo;
+        sh_acc[wave][h][chunk * 8 + 4 + sub] = hi;
+    }
 #pragma unroll
-            for (int e = 0; e < 8; ++e) sh_acc[wave][h][chunk * 8 + e] = st.acc[h][e];
-        }
+    for (int h0 = 0; h0 < G; h0 += 4) {                            // the sums of heads h0..h0+3 land in rows 0..3
+        const float l4 = sum_rows4(st.l[h0], h0 + 1 < G ? st.l[h0 + 1] : 0.f, h0 + 2 < G ? st.l[h0 + 2] : 0.f,
+                                   h0 + 3 < G ? st.l[h0 + 3] : 0.f);
+        if (chunk == 0 && h0 + sub < G) sh_l[wave][h0 + sub] = l4;
+    }
+    if (lane == 0) {
+#pragma unroll
+        for (int h = 0; h < G; ++h) sh_m[wave][h] = st.m[h];
     }
     __syncthreads();
 
     // Merge the wavefronts.  With a single split this is the final result; otherwise store the
     // split's partial result (un-normalised accumulator, running max in log2 units, sum).
     const bool single = a.n_splits == 1;
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kDecodeThreads) {
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kThreads) {
         const int h = idx / kHeadDim, dim = idx % kHeadDim;
         float mx = sh_m[0][h];
 #pragma unroll
@@ -393,17 +473,30 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
     __syncthreads();
     if (!sh_is_last) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
-    // Phase 1: every (head, split) pair's running max and sum into LDS, one load round trip.
-    for (int idx = threadIdx.x; idx < G * a.n_splits; idx += kDecodeThreads) {
+    // Every (head, split) pair's running max and sum go to LDS; the first eight partial
+    // accumulators of each output element are requested in the same round trip.
+    float first[(G * kHeadDim + kThreads - 1) / kThreads][8];
+#pragma unroll
+    for (int r = 0; r < (G * kHeadDim + kThreads - 1) / kThreads; ++r) {
+        const int idx = threadIdx.x + r * kThreads;
+        const int h = (idx < G * kHeadDim ? idx : 0) / kHeadDim, dim = idx % kHeadDim;
+        const float *acc = a.part_acc + ((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits * kHeadDim + dim;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) first[r][u] = observe(acc + (int64_t)min(u, a.n_splits - 1) * kHeadDim);
+    }
+    for (int idx = threadIdx.x; idx < G * a.n_splits; idx += kThreads) {
         const int h = idx / a.n_splits, c = idx % a.n_splits;
         const float *ml = a.part_ml + (((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + c) * 2;
         sh_merge_m[h][c] = observe(ml);
         sh_merge_l[h][c] = observe(ml + 1);
     }
     __syncthreads();
-    // Phase 2: one thread per (head, dim); the partial accumulators are fetched eight splits at
-    // a time so the loads overlap instead of paying one memory latency per split.
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kDecodeThreads) {
+    // One thread per (head, dim); further partial accumulators are fetched eight splits at a time
+    // so the loads overlap instead of paying one memory latency per split.
+#pragma unroll
+    for (int r = 0; r < (G * kHeadDim + kThreads - 1) / kThreads; ++r) {
+        const int idx = threadIdx.x + r * kThreads;
+        if (idx >= G * kHeadDim) break;
         const int h = idx / kHeadDim, dim = idx % kHeadDim;
         const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
         const float *acc = a.part_acc + head * a.n_splits * kHeadDim + dim;
@@ -413,10 +506,8 @@ __global__ __launch_bounds__(kDecodeThreads) void lt_decode_kernel(DecodeArgs a)
         for (int c0 = 0; c0 < a.n_splits; c0 += 8) {
             float v[8];
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const int c = min(c0 + u, a.n_splits - 1);
-                v[u] = observe(acc + (int64_t)c * kHeadDim);
-            }
+            for (int u = 0; u < 8; ++u)
+                v[u] = c0 == 0 ? first[r][u] : observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 if (c0 + u < a.n_splits) {
@@ -442,10 +533,14 @@ template <int G>
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
-    if (a.lazy_tag)
-        hipLaunchKernelGGL((lt_decode_kernel<G, 1>), grid, dim3(kDecodeThreads), 0, stream, a);
-    else
-        hipLaunchKernelGGL((lt_decode_kernel<G, 0>), grid, dim3(kDecodeThreads), 0, stream, a);
+    const bool wide = a.keys_per_block <= kWideBlockKeys;          // short ranges: eight wavefronts per workgroup
+    if (a.lazy_tag) {
+        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, 1, 8>), grid, dim3(512), 0, stream, a);
+        else hipLaunchKernelGGL((lt_decode_kernel<G, 1, 4>), grid, dim3(256), 0, stream, a);
+    } else {
+        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, 0, 8>), grid, dim3(512), 0, stream, a);
+        else hipLaunchKernelGGL((lt_decode_kernel<G, 0, 4>), grid, dim3(256), 0, stream, a);
+    }
     return hipGetLastError();
 }
 

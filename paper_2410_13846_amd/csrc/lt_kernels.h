@@ -10,7 +10,7 @@ namespace ltk {
 
 constexpr int kHeadDim = 128;          // bf16 elements per key / value / query vector
 constexpr int kMaxGroup = 8;           // query heads per KV head
-constexpr int kDecodeThreads = 256;    // 4 wavefronts per decode workgroup
+constexpr int kWideBlockKeys = 2048;    // decode workgroups with at most this many keys run eight wavefronts, else four
 constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
 constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head) is split into
 constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels
