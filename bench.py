@@ -380,8 +380,8 @@ def main():
         avg_ms = total_ms / max(launches, 1)
         achieved = launch_bytes / avg_ms / 1e6
         roofline = {
-            "bound": "hbm", "kernel": "lt_decode_kernel<4,0> (full layers)" if kernel == lt.KERNEL_DECODE_FULL
-            else "lt_decode_kernel<4,1> (lazy layers)",
+            "bound": "hbm", "kernel": "lt_decode_kernel<%d, 0, *> (full layers)" % wl.group if kernel == lt.KERNEL_DECODE_FULL
+            else "lt_decode_kernel<%d, 1, *> (lazy layers)" % wl.group,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": read_traffic(wl.name), "launches": launches, "avg_launch_us": avg_ms * 1e3,
             "bytes_per_launch": launch_bytes, "ms_per_step_with_events": elapsed_p / K * 1e3, "kernels": per_kernel,
