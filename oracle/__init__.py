@@ -55,6 +55,12 @@ def _load():
             fn.argtypes = [u16p, u16p, c_int, c_int, c_int, c_int, c_i64, c_int,
                            c_i64, c_i64, c_f64, c_int, f64p, f64p, f64p]
             fn.restype = c_int
+        lib.lto_lazy_ratio_from_lse.argtypes = [u16p, u16p, f64p, c_int, c_int, c_int, c_int, c_i64, c_int,
+                                                c_i64, c_i64, c_f64, c_int, f64p, f64p, f64p]
+        lib.lto_lazy_ratio_from_lse.restype = c_int
+        lib.lto_prefill_attn.argtypes = [u16p, u16p, u16p, c_int, c_int, c_int, c_int, c_i64,
+                                         c_int, c_i64, c_i64, c_f64, f64p, f64p, f64p]
+        lib.lto_prefill_attn.restype = c_int
         lib.lto_select_lazy.argtypes = [f64p, c_int, c_int, u8p, i32p]
         lib.lto_select_lazy.restype = c_int
         lib.lto_select_lazy_queue.argtypes = [f64p, c_int, c_int, u8p, i32p]
@@ -156,6 +162,52 @@ def lazy_ratio(q_last, K, w_sink, w_recent, scale=None, recent_mode=RECENT_PER_Q
 def lazy_ratio_lse(q_last, K, w_sink, w_recent, scale=None, recent_mode=RECENT_PER_QUERY):
     """Table 1 form.  Returns (log_rho [B,Hq,w], r_seq [B], r)."""
     return _ratio_call(_load().lto_lazy_ratio_lse, q_last, K, w_sink, w_recent, scale, recent_mode)
+
+
+def lazy_ratio_from_lse(q_last, K, lse_rows, w_sink, w_recent, scale=None, recent_mode=RECENT_PER_QUERY):
+    """Table 1 with the prefill's log-sum-exp supplied: lse_rows [B,Hq,w] (natural log) of the causal rows
+    n-w..n-1.  Returns (log_rho [B,Hq,w], r_seq [B], r)."""
+    q_last = _u16(q_last)
+    B, Hq, w, d = q_last.shape
+    K = _u16(K)
+    _, Hkv, n, _ = K.shape
+    K = _u16(K, (B, Hkv, n, d))
+    lse_rows = np.ascontiguousarray(lse_rows, dtype=np.float64)
+    if lse_rows.shape != (B, Hq, w):
+        raise ValueError(f"lse_rows has shape {lse_rows.shape}, expected {(B, Hq, w)}")
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    per = np.empty((B, Hq, w), dtype=np.float64)
+    r_seq = np.empty((B,), dtype=np.float64)
+    r = np.empty((1,), dtype=np.float64)
+    st = _load().lto_lazy_ratio_from_lse(_ptr(q_last, ctypes.c_uint16), _ptr(K, ctypes.c_uint16),
+                                         _ptr(lse_rows, ctypes.c_double), B, Hq, Hkv, d, n, w,
+                                         int(w_sink), int(w_recent), float(scale), int(recent_mode),
+                                         _ptr(per, ctypes.c_double), _ptr(r_seq, ctypes.c_double), _ptr(r, ctypes.c_double))
+    _check(st, "lazy_ratio_from_lse")
+    return per, r_seq, float(r[0])
+
+
+def prefill_attn(Q, K, V, mode, w_sink=0, w_recent=0, scale=None, return_absw=False):
+    """Prefill attention over a whole prompt.  Q [B,Hq,n,d], K/V [B,Hkv,n,d] as uint16 bf16 bits.
+    Returns (out [B,Hq,n,d], lse [B,Hq,n]) as float64, plus absw [B,Hq,n,d] = sum_j p_j |V_j| when asked."""
+    Q = _u16(Q)
+    B, Hq, n, d = Q.shape
+    K = _u16(K)
+    Hkv = K.shape[1]
+    K = _u16(K, (B, Hkv, n, d))
+    V = _u16(V, (B, Hkv, n, d))
+    if scale is None:
+        scale = 1.0 / np.sqrt(d)
+    out = np.empty((B, Hq, n, d), dtype=np.float64)
+    lse = np.empty((B, Hq, n), dtype=np.float64)
+    absw = np.empty((B, Hq, n, d), dtype=np.float64) if return_absw else None
+    st = _load().lto_prefill_attn(_ptr(Q, ctypes.c_uint16), _ptr(K, ctypes.c_uint16), _ptr(V, ctypes.c_uint16),
+                                  B, Hq, Hkv, d, n, int(mode), int(w_sink), int(w_recent), float(scale),
+                                  _ptr(out, ctypes.c_double), _ptr(lse, ctypes.c_double),
+                                  _ptr(absw, ctypes.c_double) if return_absw else None)
+    _check(st, "prefill_attn")
+    return (out, lse, absw) if return_absw else (out, lse)
 
 
 def select_lazy(ratios, n_lazy):

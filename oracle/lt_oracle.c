@@ -3,8 +3,8 @@
  *
  * A plain, slow, fp64 CPU statement of what the LightTransfer hot path computes:
  * decode attention in a hybrid layer stack (full attention / streaming attention
- * over sink + recent tokens), the lazy ratio of a layer, and the choice of lazy
- * layers.  It exists only so that tests, the smoke check and the benchmark's CPU
+ * over sink + recent tokens), the lazy ratio of a layer, the choice of lazy layers,
+ * and the prefill attention whose log-sum-exp the lazy ratio can reuse.  It exists only so that tests, the smoke check and the benchmark's CPU
  * baseline can compare the GPU library against the paper's definitions.  Nothing
  * in the product path may call it, and it shares no code with the GPU path.
  *
@@ -18,7 +18,10 @@
  * history, one dominant key, the identity |s1 - s1~|_1 = 1 - rho and the bound of
  * the paper's streaming-attention lemma, agreement of the probability-sum and the
  * log-sum-exp forms of the lazy ratio, brute force against an explicit N x N masked
- * softmax built from library routines, and queue simulation == sort for selection.
+ * softmax built from library routines, and queue simulation == sort for selection;
+ * prefill rows against the decode function on the truncated history and against the
+ * library form of the whole masked softmax, the ratio from a supplied log-sum-exp
+ * against the two self-contained forms.
  * No function here is "parity unpinned".
  */
 #include <math.h>
@@ -282,6 +285,134 @@ int lto_lazy_ratio_lse(const uint16_t *q_last, const uint16_t *K,
         if (log_rho) memcpy(log_rho, lr_all, (size_t)B * Hq * w * sizeof(double));
     }
     free(lr_all);
+    return status;
+}
+
+/*
+ * Lazy ratio from a log-sum-exp that the prefill attention already produced (Table 1:
+ * the LSE of the window logits minus the prefill kernel's LSE of the whole causal row).
+ * Only the initial and recent keys of each query are touched.
+ *
+ *   lse_rows [B, Hq, w]   natural-log LSE of the causal rows n-w .. n-1 (scale included)
+ *
+ * Other arguments and outputs as lto_lazy_ratio_lse.
+ */
+int lto_lazy_ratio_from_lse(const uint16_t *q_last, const uint16_t *K, const double *lse_rows,
+                            int B, int Hq, int Hkv, int d, int64_t n, int w,
+                            int64_t w_sink, int64_t w_recent, double scale, int recent_mode,
+                            double *log_rho, double *r_seq, double *r)
+{
+    if (!q_last || !K || !lse_rows || !r) return LTO_ERR_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || n <= 0 || w <= 0 || w > n) return LTO_ERR_ARG;
+    if (Hq % Hkv != 0 || w_sink < 0 || w_recent < 0) return LTO_ERR_ARG;
+    if (recent_mode != LTO_RECENT_PER_QUERY && recent_mode != LTO_RECENT_FIXED) return LTO_ERR_ARG;
+    const int G = Hq / Hkv;
+    double *lr_all = (double *)malloc((size_t)B * Hq * w * sizeof(double));
+    if (!lr_all) return LTO_ERR_NOMEM;
+
+    for (int bh = 0; bh < B * Hq; ++bh) {
+        const int b = bh / Hq, h = bh % Hq, g = h / G;
+        const uint16_t *Kb = K + ((size_t)b * Hkv + g) * (size_t)n * d;
+        for (int t = 0; t < w; ++t) {
+            const int64_t p = n - w + t;
+            const uint16_t *qv = q_last + (((size_t)b * Hq + h) * w + t) * d;
+            /* logits of the kept keys only, then their log-sum-exp */
+            double m = -INFINITY, Z = 0.0;
+            for (int pass = 0; pass < 2; ++pass) {
+                for (int64_t j = 0; j <= p; ++j) {
+                    const int keep = (recent_mode == LTO_RECENT_PER_QUERY)
+                                         ? in_streaming_set(j, p, w_sink, w_recent)
+                                         : in_fixed_set(j, p, n, w_sink, w_recent);
+                    if (!keep) continue;
+                    const double sj = scale * dot_qk(qv, Kb + (size_t)j * d, d);
+                    if (pass == 0) { if (sj > m) m = sj; }
+                    else Z += exp(sj - m);
+                }
+            }
+            const double lse_window = (m == -INFINITY) ? -INFINITY : m + log(Z);
+            lr_all[((size_t)b * Hq + h) * w + t] = lse_window - lse_rows[((size_t)b * Hq + h) * w + t];
+        }
+    }
+    double total = 0.0;
+    for (int b = 0; b < B; ++b) {
+        double acc = 0.0;
+        for (int i = 0; i < Hq * w; ++i) acc += exp(lr_all[(size_t)b * Hq * w + i]);
+        acc /= (double)Hq * (double)w;
+        if (r_seq) r_seq[b] = acc;
+        total += acc;
+    }
+    *r = total / (double)B;
+    if (log_rho) memcpy(log_rho, lr_all, (size_t)B * Hq * w * sizeof(double));
+    free(lr_all);
+    return LTO_OK;
+}
+
+/*
+ * Prefill attention of one layer over a whole prompt (Preliminary, "Prefilling":
+ * every position attends to itself and the positions before it; Appendix "Theoretical
+ * Analysis": softmax(Q K^T + M) V with M the causal mask, or the sink mask for a layer
+ * that runs streaming attention from the start, as LightTransfer-Train's lazy layers do).
+ *
+ *   Q      [B, Hq, n, d]    K, V  [B, Hkv, n, d]
+ *   mode   LTO_MODE_FULL: row p attends 0..p;  LTO_MODE_LAZY: first w_sink and last w_recent of 0..p
+ *   out    [B, Hq, n, d]    softmax-weighted mean of V per row
+ *   lse    [B, Hq, n]       log of each row's softmax denominator (may be NULL)
+ *   absw   [B, Hq, n, d]    sum_j p_j |V_j| per row and channel (may be NULL): the scale of the
+ *                           rounding error of an implementation that rounds the weights
+ */
+int lto_prefill_attn(const uint16_t *Q, const uint16_t *K, const uint16_t *V,
+                     int B, int Hq, int Hkv, int d, int64_t n,
+                     int mode, int64_t w_sink, int64_t w_recent, double scale,
+                     double *out, double *lse, double *absw)
+{
+    if (!Q || !K || !V || !out) return LTO_ERR_ARG;
+    if (B <= 0 || Hq <= 0 || Hkv <= 0 || d <= 0 || n <= 0) return LTO_ERR_ARG;
+    if (Hq % Hkv != 0) return LTO_ERR_ARG;
+    if (mode != LTO_MODE_FULL && mode != LTO_MODE_LAZY) return LTO_ERR_ARG;
+    if (w_sink < 0 || w_recent < 0) return LTO_ERR_ARG;
+    if (mode == LTO_MODE_LAZY && w_sink + w_recent == 0) return LTO_ERR_ARG;
+    const int G = Hq / Hkv;
+    int status = LTO_OK;
+
+#pragma omp parallel for schedule(dynamic)
+    for (int bh = 0; bh < B * Hq; ++bh) {
+        const int b = bh / Hq, h = bh % Hq, g = h / G;
+        const uint16_t *Kb = K + ((size_t)b * Hkv + g) * (size_t)n * d;
+        const uint16_t *Vb = V + ((size_t)b * Hkv + g) * (size_t)n * d;
+        double *w = (double *)malloc((size_t)n * sizeof(double));
+        if (!w) {
+#pragma omp critical
+            status = LTO_ERR_NOMEM;
+            continue;
+        }
+        for (int64_t p = 0; p < n; ++p) {
+            const uint16_t *qv = Q + (((size_t)b * Hq + h) * (size_t)n + p) * d;
+            double *o = out + (((size_t)b * Hq + h) * (size_t)n + p) * d;
+            double *a = absw ? absw + (((size_t)b * Hq + h) * (size_t)n + p) * d : NULL;
+            /* row p of Q K^T + M, then its softmax */
+            double m = -INFINITY;
+            for (int64_t j = 0; j <= p; ++j) {
+                const int keep = (mode == LTO_MODE_FULL) ? 1 : in_streaming_set(j, p, w_sink, w_recent);
+                w[j] = keep ? scale * dot_qk(qv, Kb + (size_t)j * d, d) : -INFINITY;
+                if (w[j] > m) m = w[j];
+            }
+            double Z = 0.0;
+            for (int64_t j = 0; j <= p; ++j) { w[j] = exp(w[j] - m); Z += w[j]; }
+            for (int c = 0; c < d; ++c) { o[c] = 0.0; if (a) a[c] = 0.0; }
+            for (int64_t j = 0; j <= p; ++j) {
+                const double pj = w[j] / Z;
+                if (pj == 0.0) continue;
+                const uint16_t *vj = Vb + (size_t)j * d;
+                for (int c = 0; c < d; ++c) {
+                    const double v = bf16_bits_to_double(vj[c]);
+                    o[c] += pj * v;
+                    if (a) a[c] += pj * fabs(v);
+                }
+            }
+            if (lse) lse[((size_t)b * Hq + h) * (size_t)n + p] = m + log(Z);
+        }
+        free(w);
+    }
     return status;
 }
 
