@@ -7,7 +7,7 @@ import subprocess
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "liblt_hip.so")
-SOURCES = ["lt_api.cpp", "lt_decode.hip", "lt_score.hip"]
+SOURCES = ["lt_api.cpp", "lt_decode.hip", "lt_score.hip", "lt_prefill.hip"]
 HEADERS = ["lt_kernels.h", os.path.join("..", "..", "include", "lt.h")]
 
 HIPCC_FLAGS = [

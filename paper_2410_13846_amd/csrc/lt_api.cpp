@@ -385,6 +385,9 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
     a.fixed_mode = mode == LT_RECENT_FIXED ? 1 : 0;
     a.keys_per_block = score_keys_per_block(cfg, n);
     a.n_chunks = (int32_t)ceil_div(n, a.keys_per_block);
+    a.range_a_end = n;
+    a.range_b_begin = n;
+    a.n_chunks_a = a.n_chunks;
     a.scale_log2e = effective_scale(cfg) * kLog2e;
     a.part = static_cast<float *>(workspace);
     const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * a.n_chunks) * 3 * sizeof(float);
@@ -393,6 +396,131 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
     a.ratio_seq = ratio_seq_dev;
     a.ratio_mean = ratio_mean_dev;
     return ltk::lazy_ratio(a, static_cast<hipStream_t>(stream)) == hipSuccess ? LT_OK : LT_ERR_HIP;
+}
+
+// Key ranges the window-only form touches: the tiles holding the first w_sink keys and the tiles from
+// the earliest recent key of any scored query to the end of the prompt (disjoint, tile-aligned).
+struct WindowPlan {
+    int64_t a_end, b_begin;
+    int32_t keys_per_block, chunks_a, chunks_b;
+};
+
+static WindowPlan window_plan(const lt_config *cfg, int64_t n, int32_t w_last, lt_ratio_mode mode)
+{
+    const int64_t tile = ltk::kScoreTileKeys;
+    WindowPlan p{};
+    p.a_end = std::min<int64_t>(n, ceil_div(cfg->w_sink, tile) * tile);
+    int64_t first_recent = mode == LT_RECENT_FIXED ? n - cfg->w_recent : n - w_last - (int64_t)cfg->w_recent + 1;
+    first_recent = std::min<int64_t>(std::max<int64_t>(first_recent, 0), n);
+    p.b_begin = std::max<int64_t>(p.a_end, first_recent / tile * tile);
+    p.keys_per_block = score_keys_per_block(cfg, p.a_end + (n - p.b_begin));
+    p.chunks_a = (int32_t)ceil_div(p.a_end, p.keys_per_block);
+    p.chunks_b = (int32_t)ceil_div(n - p.b_begin, p.keys_per_block);
+    return p;
+}
+
+size_t lt_lazy_ratio_lse_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last)
+{
+    if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n <= 0 || w_last <= 0 || w_last > 64 || w_last > n) return 0;
+    const WindowPlan p = window_plan(cfg, n, w_last, LT_RECENT_PER_QUERY), f = window_plan(cfg, n, w_last, LT_RECENT_FIXED);
+    const int64_t chunks = std::max(p.chunks_a + p.chunks_b, f.chunks_a + f.chunks_b);       // either reading fits
+    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * chunks) * 3 * sizeof(float);
+    return align_up(part) + align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
+}
+
+lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
+                            int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, const float *lse_rows,
+                            int64_t lse_stride_b, int64_t lse_stride_h, void *workspace, size_t ws_bytes, float *rho_dev,
+                            float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
+{
+    if (!config_ok(cfg) || q_last == nullptr || k == nullptr || lse_rows == nullptr || workspace == nullptr ||
+        ratio_mean_dev == nullptr)
+        return LT_ERR_INVALID_ARG;
+    if (mode != LT_RECENT_PER_QUERY && mode != LT_RECENT_FIXED) return LT_ERR_INVALID_ARG;
+    if (n <= 0 || w_last <= 0 || k_stride_b < 0 || k_stride_h < 0 || k_stride_t <= 0 || lse_stride_b < 0 || lse_stride_h < 0)
+        return LT_ERR_INVALID_ARG;
+    const lt_status shape = config_shape(cfg);
+    if (shape != LT_OK) return shape;
+    if (w_last > n || w_last > 64 || n > kMaxTokens) return LT_ERR_SHAPE;
+    if (k_stride_t < ltk::kHeadDim || (k_stride_b % 8) != 0 || (k_stride_h % 8) != 0 || (k_stride_t % 8) != 0) return LT_ERR_SHAPE;
+    if (((uintptr_t)q_last % 16) != 0 || ((uintptr_t)k % 16) != 0 || ((uintptr_t)lse_rows % 4) != 0 ||
+        ((uintptr_t)workspace % kAlign) != 0)
+        return LT_ERR_INVALID_ARG;
+    if (ws_bytes < lt_lazy_ratio_lse_workspace_bytes(cfg, n, w_last)) return LT_ERR_CAPACITY;
+
+    const WindowPlan p = window_plan(cfg, n, w_last, mode);
+    ltk::ScoreArgs a{};
+    a.q_last = static_cast<const uint16_t *>(q_last);
+    a.k = static_cast<const uint16_t *>(k);
+    a.k_stride_b = k_stride_b;
+    a.k_stride_h = k_stride_h;
+    a.k_stride_t = k_stride_t;
+    a.n = n;
+    a.w_last = w_last;
+    a.batch = cfg->batch;
+    a.n_q_heads = cfg->n_q_heads;
+    a.n_kv_heads = cfg->n_kv_heads;
+    a.w_sink = cfg->w_sink;
+    a.w_recent = cfg->w_recent;
+    a.fixed_mode = mode == LT_RECENT_FIXED ? 1 : 0;
+    a.keys_per_block = p.keys_per_block;
+    a.n_chunks = p.chunks_a + p.chunks_b;
+    a.range_a_end = p.a_end;
+    a.range_b_begin = p.b_begin;
+    a.n_chunks_a = p.chunks_a;
+    a.lse_rows = lse_rows;
+    a.lse_stride_b = lse_stride_b;
+    a.lse_stride_h = lse_stride_h;
+    a.scale_log2e = effective_scale(cfg) * kLog2e;
+    a.part = static_cast<float *>(workspace);
+    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * a.n_chunks) * 3 * sizeof(float);
+    a.head_scratch = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(part));
+    a.rho = rho_dev;
+    a.ratio_seq = ratio_seq_dev;
+    a.ratio_mean = ratio_mean_dev;
+    return ltk::lazy_ratio(a, static_cast<hipStream_t>(stream)) == hipSuccess ? LT_OK : LT_ERR_HIP;
+}
+
+// ---- prefill attention -------------------------------------------------------------------------
+
+lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, const void *v, int64_t kv_stride_b,
+                          int64_t kv_stride_h, int64_t kv_stride_t, int64_t n, lt_mask_mode mask, lt_out_dtype out_dtype,
+                          void *out, float *lse_out, void *stream)
+{
+    if (!config_ok(cfg) || q == nullptr || k == nullptr || v == nullptr || out == nullptr) return LT_ERR_INVALID_ARG;
+    if (mask != LT_MASK_CAUSAL && mask != LT_MASK_STREAMING) return LT_ERR_INVALID_ARG;
+    if (out_dtype != LT_OUT_BF16 && out_dtype != LT_OUT_F32) return LT_ERR_INVALID_ARG;
+    if (n <= 0 || kv_stride_b < 0 || kv_stride_h < 0 || kv_stride_t <= 0) return LT_ERR_INVALID_ARG;
+    const lt_status shape = config_shape(cfg);
+    if (shape != LT_OK) return shape;
+    if (n > kMaxTokens) return LT_ERR_SHAPE;
+    if (mask == LT_MASK_STREAMING && cfg->w_sink + cfg->w_recent < 1) return LT_ERR_SHAPE;
+    if (kv_stride_t < ltk::kHeadDim || (kv_stride_b % 8) != 0 || (kv_stride_h % 8) != 0 || (kv_stride_t % 8) != 0) return LT_ERR_SHAPE;
+    if (((uintptr_t)q % 16) != 0 || ((uintptr_t)k % 16) != 0 || ((uintptr_t)v % 16) != 0 || ((uintptr_t)out % 16) != 0 ||
+        ((uintptr_t)lse_out % 4) != 0)
+        return LT_ERR_INVALID_ARG;
+    const int64_t blocks = ceil_div(n, 32) * cfg->n_kv_heads * cfg->batch;     // upper bound of the grid
+    if (blocks + 8 > (int64_t)0x7fffffff) return LT_ERR_SHAPE;
+
+    ltk::PrefillArgs a{};
+    a.q = static_cast<const uint16_t *>(q);
+    a.k = static_cast<const uint16_t *>(k);
+    a.v = static_cast<const uint16_t *>(v);
+    a.kv_stride_b = kv_stride_b;
+    a.kv_stride_h = kv_stride_h;
+    a.kv_stride_t = kv_stride_t;
+    a.out = out;
+    a.lse = lse_out;
+    a.n = n;
+    a.batch = cfg->batch;
+    a.n_q_heads = cfg->n_q_heads;
+    a.n_kv_heads = cfg->n_kv_heads;
+    a.streaming = mask == LT_MASK_STREAMING ? 1 : 0;
+    a.w_sink = cfg->w_sink;
+    a.w_recent = cfg->w_recent;
+    a.out_f32 = out_dtype == LT_OUT_F32 ? 1 : 0;
+    a.scale_log2e = effective_scale(cfg) * kLog2e;
+    return ltk::prefill_attn(a, static_cast<hipStream_t>(stream)) == hipSuccess ? LT_OK : LT_ERR_HIP;
 }
 
 lt_status lt_select_lazy(const float *ratios_host, int32_t n_layers, int32_t n_lazy, uint8_t *is_lazy_out, int32_t *order_out)

@@ -63,11 +63,31 @@ struct ScoreArgs {
     int32_t w_last, batch, n_q_heads, n_kv_heads;
     int32_t w_sink, w_recent, fixed_mode;
     int32_t keys_per_block, n_chunks;
+    // key ranges the chunks cover: chunks [0, n_chunks_a) tile [0, range_a_end), the others
+    // [range_b_begin, n).  The dense form has one range (range_a_end = n, n_chunks_a = n_chunks).
+    int64_t range_a_end, range_b_begin;
+    int32_t n_chunks_a;
+    const float *lse_rows;             // natural-log LSE of the causal rows n-w..n-1, or nullptr: computed here
+    int64_t lse_stride_b, lse_stride_h;
     float scale_log2e;
     float *part;                       // [B][Hq][n_chunks][2][3][w]: max (log2 units), causal sum, kept sum
     float *head_scratch;               // [B][Hq] sum of rho over the queries of a head
     float *rho, *ratio_seq, *ratio_mean;
 };
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);
+
+struct PrefillArgs {
+    const uint16_t *q;                 // [B][Hq][n][128]
+    const uint16_t *k, *v;             // [B][Hkv][n][128] through the strides below (elements)
+    int64_t kv_stride_b, kv_stride_h, kv_stride_t;
+    void *out;                         // [B][Hq][n][128] bf16, or fp32 when out_f32
+    float *lse;                        // [B][Hq][n] natural-log row denominators, or nullptr
+    int64_t n;
+    int32_t batch, n_q_heads, n_kv_heads;
+    int32_t streaming, w_sink, w_recent;
+    int32_t out_f32;
+    float scale_log2e;
+};
+hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream);
 
 }  // namespace ltk

@@ -1,0 +1,330 @@
+// Prefill attention for gfx950 (Section "Preliminary", prefilling stage; Appendix "Theoretical
+// Analysis": softmax(Q K^T + M) V with the causal mask, or the sink mask of streaming attention):
+// every prompt position attends to the positions up to itself, and the kernel also returns the
+// log-sum-exp of every row, which the lazy-ratio test of Table 1 reuses.
+//
+// One workgroup = one (sequence, KV head, block of query positions); its wavefronts are the G
+// query heads of the group (times QB consecutive sub-blocks of queries when G is small), each
+// with NT 32-query column tiles, and all of them share every K and V tile staged in LDS.  Both products
+// run on the matrix cores with v_mfma_f32_32x32x16_bf16 in transposed form:
+//   S^T = K Q^T   rows = keys, columns = queries: a lane holds 16 logits of ONE query, so the
+//                 running max and sum of a softmax row stay in two lanes (the two halves);
+//   O^T = V^T P^T rows = head dims, columns = queries: the probabilities a lane has just
+//                 computed are, packed to bf16, exactly the B operand of its own column, and
+//                 V^T comes out of the row-major V tile with the LDS transpose read
+//                 (ds_read_b64_tr_b16), which hands a lane four consecutive keys of one dim.
+// The softmax reference point of a row moves only when the row's maximum has grown by more than
+// 2^8 since it was set: any reference gives the same quotient, the probabilities stay below 2^8,
+// and the accumulator is rescaled a handful of times per row instead of once per tile.
+#include "lt_kernels.h"
+
+namespace ltk {
+namespace {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
+typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
+typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2_t;
+typedef short v4i16_t __attribute__((ext_vector_type(4)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+
+constexpr int kTileKeys = 64;                 // keys per LDS tile
+constexpr int kKRow = kHeadDim + 8;           // 272-byte K rows: 16-byte reads of 32 rows spread over the banks
+constexpr int kVRow = kHeadDim + 32;          // 320-byte V rows: the 4 rows x 64 bytes of a transpose read do not collide
+constexpr float kRescaleStep = 8.f;           // log2 units the row maximum may exceed the reference before it moves
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// v_permlane32_swap exchanges the upper half of its first operand with the lower half of the
+// second; the s_nop keep the wait states the instruction needs, which the compiler does not
+// track inside an asm statement.
+__device__ __forceinline__ void swap_halves(float &a, float &b)
+{
+    asm volatile("s_nop 1\n\tv_permlane32_swap_b32 %0, %1\n\ts_nop 1" : "+v"(a), "+v"(b));
+}
+__device__ __forceinline__ float max_halves(float x)
+{
+    float a = x, b = x;
+    swap_halves(a, b);                        // a = lower half of x in both halves, b = upper half
+    return fmaxf(a, b);
+}
+__device__ __forceinline__ float sum_halves(float x)
+{
+    float a = x, b = x;
+    swap_halves(a, b);
+    return a + b;
+}
+
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
+{
+    const float2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
+
+template <int kWaves>
+struct Stage {
+    static constexpr int kThreads = 64 * kWaves;
+    static constexpr int kTotal = kTileKeys * 16;                        // 16-byte pieces of one 64 x 128 tile
+    static constexpr int kPieces = (kTotal + kThreads - 1) / kThreads;
+};
+
+template <int W>
+__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int64_t j0, int64_t n)
+{
+#pragma unroll
+    for (int i = 0; i < Stage<W>::kPieces; ++i) {
+        int idx = threadIdx.x + i * Stage<W>::kThreads;
+        idx = idx < Stage<W>::kTotal ? idx : Stage<W>::kTotal - 1;       // surplus threads re-read the last piece
+        int64_t j = j0 + (idx >> 4);
+        j = j < n ? j : n - 1;                                           // keys past the prompt are masked as non-causal
+        pre[i] = *reinterpret_cast<const u32x4_t *>(base + j * stride_t + (idx & 15) * 8);
+    }
+}
+
+template <int W, int kRow>
+__device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kPieces], uint16_t *sh)
+{
+#pragma unroll
+    for (int i = 0; i < Stage<W>::kPieces; ++i) {
+        const int idx = threadIdx.x + i * Stage<W>::kThreads;
+        if (idx < Stage<W>::kTotal) *reinterpret_cast<u32x4_t *>(&sh[(idx >> 4) * kRow + (idx & 15) * 8]) = pre[i];
+    }
+}
+
+// G: query heads per KV head.  QB: query sub-blocks per workgroup.  NT: 32-query tiles per wavefront.
+template <int G, int QB, int NT>
+__global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArgs a)
+{
+    constexpr int W = G * QB;                          // wavefronts
+    constexpr int kWaveQueries = 32 * NT, kBlockQueries = kWaveQueries * QB;
+    __shared__ __attribute__((aligned(16))) uint16_t sh_k[2][kTileKeys * kKRow];
+    __shared__ __attribute__((aligned(16))) uint16_t sh_v[2][kTileKeys * kVRow];
+    constexpr int kPieces = Stage<W>::kPieces;
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int col = lane & 31, half = lane >> 5;
+
+    // Workgroups that run at the same time on one XCD (linear index mod 8) work on neighbouring
+    // query blocks of the same (sequence, KV head): they walk the same K/V tiles at the same pace
+    // and share them in that XCD's L2.  Within a pair the long (late) query blocks go first.
+    const int n_qb = (int)((a.n + kBlockQueries - 1) / kBlockQueries);
+    const int64_t total = (int64_t)n_qb * a.n_kv_heads * a.batch;
+    const int64_t per_xcd = (total + 7) / 8;
+    const int64_t vid = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
+    if (vid >= total) return;
+    const int pair = (int)(vid / n_qb), qb = n_qb - 1 - (int)(vid % n_qb);
+    const int b = pair / a.n_kv_heads, g = pair % a.n_kv_heads;
+    const int h = g * G + wave % G;
+    const int64_t q_block = (int64_t)qb * kBlockQueries;
+    const int64_t q0 = q_block + (wave / G) * kWaveQueries;         // first query of this wavefront
+
+    // key tiles the block needs: [0, n_a) and [t_b, t_last]
+    const int t_last = (int)(min(q_block + kBlockQueries, a.n) - 1) / kTileKeys;
+    int n_a = 0, t_b = 0;
+    if (a.streaming) {
+        n_a = min((a.w_sink + kTileKeys - 1) / kTileKeys, t_last + 1);
+        const int64_t first_recent = max(q_block - (int64_t)a.w_recent + 1, (int64_t)0);
+        t_b = max(n_a, (int)(first_recent / kTileKeys));
+    }
+    const int n_tiles = n_a + (t_last + 1 - t_b);
+    auto tile_key = [&](int i) { return (int64_t)(i < n_a ? i : t_b + (i - n_a)) * kTileKeys; };
+
+    const uint16_t *kb = a.k + (int64_t)b * a.kv_stride_b + (int64_t)g * a.kv_stride_h;
+    const uint16_t *vb = a.v + (int64_t)b * a.kv_stride_b + (int64_t)g * a.kv_stride_h;
+
+    // Q^T fragments (B operand of S^T = K Q^T): for its query column a lane holds dims 16 s + 8 half .. + 7
+    bf16x8_t qf[NT][8];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int64_t p = q0 + nt * 32 + col;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            u32x4_t u = {0u, 0u, 0u, 0u};
+            if (p < a.n)
+                u = *reinterpret_cast<const u32x4_t *>(a.q + (((int64_t)b * a.n_q_heads + h) * a.n + p) * kHeadDim + 16 * s + 8 * half);
+            qf[nt][s] = __builtin_bit_cast(bf16x8_t, u);
+        }
+    }
+
+    floatx16_t acc[4][NT];                     // O^T: [32-dim tile][32-query tile]
+#pragma unroll
+    for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[dt][nt][i] = 0.f;
+    float m_ref[NT], l_sum[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) { m_ref[nt] = -INFINITY; l_sum[nt] = 0.f; }
+
+    // transpose-read lane offset into a V tile (bytes): source lane (k, j) of a 16-lane block
+    // points at 4 dims of key row k; the block's result lane i then holds dim d0 + i of 4 keys
+    const int blk = lane >> 4, src = lane & 15;
+    const int v_lane_off = ((4 * (blk >> 1) + (src >> 2)) * kVRow + 16 * (blk & 1) + 4 * (src & 3)) * 2;
+
+    // one 32-key sub-tile: logits, softmax update, P V
+    auto subtile = [&](const uint16_t *tile_k, const uint16_t *tile_v, int kt, int64_t j0) {
+        // nothing of this sub-tile is visible to this wavefront's queries: later than all of them,
+        // or, for streaming attention, between the initial tokens and every query's window
+        if (j0 > q0 + kWaveQueries - 1) return;
+        if (a.streaming && j0 >= a.w_sink && j0 + 31 <= q0 - a.w_recent) return;
+        floatx16_t c[NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&tile_k[(32 * kt + col) * kKRow + 16 * s + 8 * half]);
+            const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, u);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
+        }
+
+        bf16x8_t pf[NT][2];                     // P^T fragments: [query tile][16-key step]
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const int64_t p_min = q0 + nt * 32, p_max = p_min + 31;
+            bool clear = j0 + 31 <= p_min;                                       // causal for every pair
+            if (a.streaming) clear = clear && ((j0 + 31 < a.w_sink) || (j0 > p_max - a.w_recent));
+            if (!clear) {
+                const int64_t p = p_min + col;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    const int64_t j = j0 + 8 * (i >> 2) + 4 * half + (i & 3);
+                    bool keep = j <= p;
+                    if (a.streaming) keep = keep && (j < a.w_sink || j > p - a.w_recent);
+                    c[nt][i] = keep ? c[nt][i] : -INFINITY;
+                }
+            }
+            float tmax = c[nt][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, c[nt][i]);
+            tmax = max_halves(tmax) * a.scale_log2e;
+            const bool grow = tmax > m_ref[nt] + kRescaleStep;
+            if (__any(grow)) {
+                const float alpha = grow ? fast_exp2(m_ref[nt] - tmax) : 1.f;      // 0 when the reference was -inf
+                m_ref[nt] = grow ? tmax : m_ref[nt];
+                l_sum[nt] *= alpha;
+#pragma unroll
+                for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) acc[dt][nt][i] *= alpha;
+            }
+            const float mu = m_ref[nt] == -INFINITY ? 0.f : m_ref[nt];
+            float pr[16], sum = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                pr[i] = fast_exp2(fmaf(c[nt][i], a.scale_log2e, -mu));
+                sum += pr[i];
+            }
+            l_sum[nt] += sum;
+#pragma unroll
+            for (int sp = 0; sp < 2; ++sp) {
+                const u32x4_t u = {pack_bf16(pr[8 * sp + 0], pr[8 * sp + 1]), pack_bf16(pr[8 * sp + 2], pr[8 * sp + 3]),
+                                   pack_bf16(pr[8 * sp + 4], pr[8 * sp + 5]), pack_bf16(pr[8 * sp + 6], pr[8 * sp + 7])};
+                pf[nt][sp] = __builtin_bit_cast(bf16x8_t, u);
+            }
+        }
+
+        // O^T += V^T P^T: k slots e = 0..3 of a lane are keys 16 sp + 4 half + e, slots 4..7 the same + 8,
+        // which is the order the logits sit in the accumulator registers 8 sp .. 8 sp + 7
+        const char *vbytes = reinterpret_cast<const char *>(tile_v) + v_lane_off;
+#pragma unroll
+        for (int sp = 0; sp < 2; ++sp) {
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt) {
+                const int off = ((32 * kt + 16 * sp) * kVRow + 32 * dt) * 2;
+                const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) v4i16_t *)(vbytes + off));
+                const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                    (__attribute__((address_space(3))) v4i16_t *)(vbytes + off + 8 * kVRow * 2));
+                const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
+                const u32x4_t u = {lo2[0], lo2[1], hi2[0], hi2[1]};
+                const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, u);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][sp], acc[dt][nt], 0, 0, 0);
+            }
+        }
+    };
+
+    u32x4_t pre_k[kPieces], pre_v[kPieces];
+    fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(0), a.n);
+    fetch_tile<W>(pre_v, vb, a.kv_stride_t, tile_key(0), a.n);
+    commit_tile<W, kKRow>(pre_k, sh_k[0]);
+    commit_tile<W, kVRow>(pre_v, sh_v[0]);
+    __syncthreads();
+    for (int t = 0; t < n_tiles; ++t) {
+        const int buf = t & 1;
+        if (t + 1 < n_tiles) {
+            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t + 1), a.n);
+            fetch_tile<W>(pre_v, vb, a.kv_stride_t, tile_key(t + 1), a.n);
+        }
+        const int64_t j0 = tile_key(t);
+        subtile(sh_k[buf], sh_v[buf], 0, j0);
+        subtile(sh_k[buf], sh_v[buf], 1, j0 + 32);
+        if (t + 1 < n_tiles) {
+            commit_tile<W, kKRow>(pre_k, sh_k[buf ^ 1]);
+            commit_tile<W, kVRow>(pre_v, sh_v[buf ^ 1]);
+        }
+        __syncthreads();
+    }
+
+    // normalise and store: a lane holds, for its query, dims 32 dt + 8 (i / 4) + 4 half + (i % 4)
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int64_t p = q0 + nt * 32 + col;
+        const float l_tot = sum_halves(l_sum[nt]);
+        if (p >= a.n) continue;
+        const float inv = 1.f / l_tot;
+        const int64_t row = ((int64_t)b * a.n_q_heads + h) * a.n + p;
+        if (a.lse != nullptr && half == 0) a.lse[row] = (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
+#pragma unroll
+        for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+            for (int gi = 0; gi < 4; ++gi) {
+                const int d0 = 32 * dt + 8 * gi + 4 * half;
+                const float o0 = acc[dt][nt][4 * gi + 0] * inv, o1 = acc[dt][nt][4 * gi + 1] * inv;
+                const float o2 = acc[dt][nt][4 * gi + 2] * inv, o3 = acc[dt][nt][4 * gi + 3] * inv;
+                if (a.out_f32) {
+                    const float4 o = make_float4(o0, o1, o2, o3);
+                    *reinterpret_cast<float4 *>(reinterpret_cast<float *>(a.out) + row * kHeadDim + d0) = o;
+                } else {
+                    const u32x2_t o = {pack_bf16(o0, o1), pack_bf16(o2, o3)};
+                    *reinterpret_cast<u32x2_t *>(reinterpret_cast<uint16_t *>(a.out) + row * kHeadDim + d0) = o;
+                }
+            }
+    }
+}
+
+}  // namespace
+
+template <int G, int QB, int NT>
+hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream)
+{
+    const int64_t block_queries = 32 * NT * QB;
+    const int64_t total = (a.n + block_queries - 1) / block_queries * a.n_kv_heads * a.batch;
+    const int64_t grid = (total + 7) / 8 * 8;
+    hipLaunchKernelGGL((lt_prefill_attn_kernel<G, QB, NT>), dim3((unsigned)grid), dim3(64 * G * QB), 0, stream, a);
+    return hipGetLastError();
+}
+
+// Up to four wavefronts per workgroup run alone on their SIMD with the whole register file and take
+// 64 queries each; larger groups share SIMDs and take 32.
+hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream)
+{
+    switch (a.n_q_heads / a.n_kv_heads) {
+    case 1: return launch_prefill<1, 4, 2>(a, stream);
+    case 2: return launch_prefill<2, 2, 2>(a, stream);
+    case 3: return launch_prefill<3, 1, 2>(a, stream);
+    case 4: return launch_prefill<4, 1, 2>(a, stream);
+    case 5: return launch_prefill<5, 1, 1>(a, stream);
+    case 6: return launch_prefill<6, 1, 1>(a, stream);
+    case 7: return launch_prefill<7, 1, 1>(a, stream);
+    case 8: return launch_prefill<8, 1, 1>(a, stream);
+    default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace ltk

@@ -141,8 +141,14 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
     const int col = lane & 31, half = lane >> 5;
     const int h = g * G + wave;
 
-    const int64_t begin_key = (int64_t)chunk * a.keys_per_block;
-    const int64_t end_key = min(a.n, begin_key + (int64_t)a.keys_per_block);
+    int64_t begin_key, end_key;
+    if (chunk < a.n_chunks_a) {
+        begin_key = (int64_t)chunk * a.keys_per_block;
+        end_key = min(a.range_a_end, begin_key + (int64_t)a.keys_per_block);
+    } else {
+        begin_key = a.range_b_begin + (int64_t)(chunk - a.n_chunks_a) * a.keys_per_block;
+        end_key = min(a.n, begin_key + (int64_t)a.keys_per_block);
+    }
     const int n_tiles = (int)((end_key - begin_key + kScoreTileKeys - 1) / kScoreTileKeys);
     const uint16_t *kb = a.k + (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
 
@@ -275,7 +281,14 @@ __global__ __launch_bounds__(64) void lt_lazy_ratio_finish_kernel(ScoreArgs a)
                 }
             }
         }
-        rho = kept / causal;
+        if (a.lse_rows != nullptr) {
+            // Table 1: the chunks covered only the initial and recent keys; the whole row's
+            // denominator comes from the prefill attention's log-sum-exp
+            const float lse = a.lse_rows[(int64_t)b * a.lse_stride_b + (int64_t)h * a.lse_stride_h + t];
+            rho = mx == -INFINITY ? 0.f : kept * fast_exp2(mx - lse * 1.44269504088896340736f);
+        } else {
+            rho = kept / causal;
+        }
         if (a.rho != nullptr) a.rho[((int64_t)b * a.n_q_heads + h) * a.w_last + t] = rho;
     }
     sh_sum[t] = rho;

@@ -15,12 +15,15 @@ from . import build as _build
 OK, ERR_INVALID_ARG, ERR_SHAPE, ERR_CAPACITY, ERR_STATE, ERR_HIP, ERR_NOMEM = range(7)
 RECENT_PER_QUERY, RECENT_FIXED = 0, 1
 KERNEL_DECODE_FULL, KERNEL_DECODE_LAZY, KERNEL_APPEND = range(3)
+MASK_CAUSAL, MASK_STREAMING = 0, 1
+OUT_BF16, OUT_F32 = 0, 1
 
 EXPORTS = [
     "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
     "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
     "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
+    "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn",
 ]
 
 
@@ -74,6 +77,12 @@ def load() -> ctypes.CDLL:
     lib.lt_lazy_ratio_workspace_bytes.restype = sz
     lib.lt_lazy_ratio.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, sz, vp, vp, vp, vp]
     lib.lt_lazy_ratio.restype = ctypes.c_int
+    lib.lt_lazy_ratio_lse_workspace_bytes.argtypes = [cfgp, i64, i32]
+    lib.lt_lazy_ratio_lse_workspace_bytes.restype = sz
+    lib.lt_lazy_ratio_lse.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, i64, i64, vp, sz, vp, vp, vp, vp]
+    lib.lt_lazy_ratio_lse.restype = ctypes.c_int
+    lib.lt_prefill_attn.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, vp, vp]
+    lib.lt_prefill_attn.restype = ctypes.c_int
     lib.lt_select_lazy.argtypes = [vp, i32, i32, vp, vp]
     lib.lt_select_lazy.restype = ctypes.c_int
     lib.lt_append_kv.argtypes = [vp, i32, vp, vp, i64, vp]
@@ -183,6 +192,58 @@ def lazy_ratio(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_las
                            rho.data_ptr() if rho is not None else None, seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
     _check(st, "lt_lazy_ratio")
     return mean, seq, rho
+
+
+def lazy_ratio_lse_workspace_bytes(cfg: Config, n: int, w_last: int) -> int:
+    return int(load().lt_lazy_ratio_lse_workspace_bytes(ctypes.byref(cfg), int(n), int(w_last)))
+
+
+def lazy_ratio_lse(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_last: int, lse_rows: torch.Tensor,
+                   mode: int = RECENT_PER_QUERY, workspace: Optional[torch.Tensor] = None, want_rho: bool = False, stream=None):
+    """Lazy ratio from the prefill's log-sum-exp.  lse_rows: fp32 view [B,Hq,w_last] (last dim contiguous) of the rows
+    n-w_last..n-1, e.g. ``lse[:, :, n - w_last:]`` of prefill_attn's output.  Returns what lazy_ratio returns."""
+    lib = load()
+    if q_last.dtype != torch.bfloat16 or k.dtype != torch.bfloat16 or not q_last.is_cuda or not k.is_cuda:
+        raise TypeError("q_last and k must be bf16 device tensors")
+    if not q_last.is_contiguous() or k.dim() != 4 or k.stride(3) != 1:
+        raise TypeError("q_last must be contiguous and k must have contiguous head_dim")
+    if lse_rows.dtype != torch.float32 or not lse_rows.is_cuda or lse_rows.dim() != 3 or lse_rows.stride(2) != 1 \
+            or tuple(lse_rows.shape) != (cfg.batch, cfg.n_q_heads, w_last):
+        raise TypeError("lse_rows must be an fp32 device view [B, Hq, w_last] with a contiguous last dim")
+    need = lazy_ratio_lse_workspace_bytes(cfg, n, w_last)
+    if workspace is None:
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_last.device)
+    dev = q_last.device
+    mean = torch.empty(1, dtype=torch.float32, device=dev)
+    seq = torch.empty(cfg.batch, dtype=torch.float32, device=dev)
+    rho = torch.empty((cfg.batch, cfg.n_q_heads, w_last), dtype=torch.float32, device=dev) if want_rho else None
+    st = lib.lt_lazy_ratio_lse(ctypes.byref(cfg), q_last.data_ptr(), k.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
+                               int(n), int(w_last), int(mode), lse_rows.data_ptr(), lse_rows.stride(0), lse_rows.stride(1),
+                               workspace.data_ptr(), workspace.numel(), rho.data_ptr() if rho is not None else None,
+                               seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
+    _check(st, "lt_lazy_ratio_lse")
+    return mean, seq, rho
+
+
+def prefill_attn(cfg: Config, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, n: int, mask: int = MASK_CAUSAL,
+                 out_dtype=torch.bfloat16, want_lse: bool = True, stream=None):
+    """q bf16 [B,Hq,n,128] contiguous; k, v bf16 [B,Hkv,>=n,128] with equal strides and contiguous dims.
+    Returns (out [B,Hq,n,128] in out_dtype, lse fp32 [B,Hq,n] or None)."""
+    lib = load()
+    for t in (q, k, v):
+        if t.dtype != torch.bfloat16 or not t.is_cuda:
+            raise TypeError("q, k, v must be bf16 device tensors")
+    if not q.is_contiguous() or k.dim() != 4 or k.stride(3) != 1 or k.stride() != v.stride():
+        raise TypeError("q must be contiguous; k and v need equal strides and contiguous head_dim")
+    if out_dtype not in (torch.bfloat16, torch.float32):
+        raise TypeError("out_dtype must be bfloat16 or float32")
+    out = torch.empty((cfg.batch, cfg.n_q_heads, int(n), cfg.head_dim), dtype=out_dtype, device=q.device)
+    lse = torch.empty((cfg.batch, cfg.n_q_heads, int(n)), dtype=torch.float32, device=q.device) if want_lse else None
+    st = lib.lt_prefill_attn(ctypes.byref(cfg), q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
+                             int(n), int(mask), OUT_F32 if out_dtype == torch.float32 else OUT_BF16, out.data_ptr(),
+                             lse.data_ptr() if lse is not None else None, _stream_ptr(stream))
+    _check(st, "lt_prefill_attn")
+    return out, lse
 
 
 class SelectQueue:

@@ -1,0 +1,140 @@
+"""GPU parity: lt_prefill_attn (MFMA prefill attention with log-sum-exp output) and lt_lazy_ratio_lse (the
+lazy ratio from that log-sum-exp, Table 1) against the CPU oracle, through the C ABI.
+
+Tolerance of the attention output.  Logits, the softmax denominator and the accumulation are fp32, but the
+probabilities enter the P V product rounded to bf16 (relative error <= 2^-8 each), so the error of an output
+element is bounded by 2^-8 * sum_j p_j |V_j| -- a quantity the oracle returns per element (absw) -- plus the
+fp32 terms; a bf16 output adds its own rounding, 2^-8 |out|.  The log-sum-exp is fp32 throughout."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL_LSE, TOL_RATIO, bits, f64, randn_bf16, say
+from paper_2410_13846_amd import lt
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+EPS_P = 2.0 ** -8
+TOL_PREFILL_LSE = 1e-4
+
+
+def out_tolerance(absw, ref, out_dtype):
+    tol = EPS_P * absw + 2e-5
+    if out_dtype == torch.bfloat16:
+        tol = tol + EPS_P * np.abs(ref)
+    return tol
+
+
+def check(B, Hq, Hkv, n, ws, wr, mask, seed, out_dtype=torch.float32, q_scale=1.0):
+    say("prefill case", dict(B=B, Hq=Hq, Hkv=Hkv, n=n, ws=ws, wr=wr, mask=mask, seed=seed, out=str(out_dtype)))
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, ws, wr, max(n, 1))
+    q = randn_bf16((B, Hq, n, 128), seed, scale=q_scale)
+    k = randn_bf16((B, Hkv, n, 128), seed + 1)
+    v = randn_bf16((B, Hkv, n, 128), seed + 2)
+    out, lse = lt.prefill_attn(cfg, q, k, v, n, mask, out_dtype=out_dtype)
+    torch.cuda.synchronize()
+    mode = oracle.MODE_LAZY if mask == lt.MASK_STREAMING else oracle.MODE_FULL
+    ref, ref_lse, absw = oracle.prefill_attn(bits(q), bits(k), bits(v), mode, ws, wr, return_absw=True)
+    err = np.abs(f64(out.float()) - ref)
+    tol = out_tolerance(absw, ref, out_dtype)
+    worst = (err / tol).max()
+    say("  max err", err.max(), "max err/tol", worst, "max lse err", np.abs(f64(lse) - ref_lse).max())
+    assert worst <= 1.0
+    assert np.abs(f64(lse) - ref_lse).max() <= TOL_PREFILL_LSE
+    return out, lse
+
+
+@pytest.mark.parametrize("n", [1, 2, 31, 32, 33, 64, 65, 127, 128, 200, 333, 1000])
+def test_causal_prompt_lengths_span_tiles_and_ragged_tails(n):
+    check(B=2, Hq=8, Hkv=2, n=n, ws=4, wr=60, mask=lt.MASK_CAUSAL, seed=5000 + n)
+
+
+@pytest.mark.parametrize("group", [1, 2, 3, 4, 5, 6, 7, 8])
+@pytest.mark.parametrize("mask", [lt.MASK_CAUSAL, lt.MASK_STREAMING])
+def test_every_query_group_size(group, mask):
+    check(B=1, Hq=group, Hkv=1, n=300, ws=4, wr=100, mask=mask, seed=5100 + group)
+
+
+@pytest.mark.parametrize("ws,wr", [(4, 20), (0, 33), (70, 100), (4, 1020), (3, 0), (0, 1), (64, 64), (4, 5000)])
+@pytest.mark.parametrize("n", [700, 1500])
+def test_streaming_windows(ws, wr, n):
+    check(B=1, Hq=4, Hkv=1, n=n, ws=ws, wr=wr, mask=lt.MASK_STREAMING, seed=5200 + ws + wr + n)
+
+
+@pytest.mark.parametrize("group", [2, 4, 5])
+def test_bf16_output(group):
+    check(B=1, Hq=2 * group, Hkv=2, n=450, ws=4, wr=60, mask=lt.MASK_CAUSAL, seed=5300 + group, out_dtype=torch.bfloat16)
+
+
+def test_large_logits_move_the_softmax_reference():
+    """Queries scaled so that row maxima keep growing by more than the rescale step."""
+    check(B=1, Hq=4, Hkv=1, n=600, ws=4, wr=60, mask=lt.MASK_CAUSAL, seed=5400, q_scale=6.0)
+    check(B=1, Hq=5, Hkv=1, n=600, ws=4, wr=60, mask=lt.MASK_STREAMING, seed=5401, q_scale=6.0)
+
+
+def test_keys_and_values_read_in_place_from_the_cache():
+    B, Hq, Hkv, n, cap = 2, 8, 2, 777, 1000
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, 4, 60, cap)
+    ctx = lt.Context(cfg, [0], DEV)
+    q = randn_bf16((B, Hq, n, 128), 5501)
+    k, v = randn_bf16((B, Hkv, n, 128), 5502), randn_bf16((B, Hkv, n, 128), 5503)
+    ctx.append_kv(0, k, v)
+    kc, vc = ctx.layer_tensors(0)
+    say("prefill in place: cache strides", kc.stride())
+    out, lse = lt.prefill_attn(cfg, q, kc, vc, n, out_dtype=torch.float32)
+    ref, ref_lse, absw = oracle.prefill_attn(bits(q), bits(k), bits(v), oracle.MODE_FULL, return_absw=True)
+    assert (np.abs(f64(out) - ref) <= out_tolerance(absw, ref, torch.float32)).all()
+    assert np.abs(f64(lse) - ref_lse).max() <= TOL_PREFILL_LSE
+    ctx.close()
+
+
+def test_prefill_errors():
+    cfg = lt.make_config(1, 1, 4, 1, 128, 0, 0, 64)
+    q, k = randn_bf16((1, 4, 64, 128), 1), randn_bf16((1, 1, 64, 128), 2)
+    with pytest.raises(lt.LtError):
+        lt.prefill_attn(cfg, q, k, k, 64, lt.MASK_STREAMING)          # empty window
+    with pytest.raises(lt.LtError):
+        lt.prefill_attn(cfg, q, k, k, 0)
+    with pytest.raises(lt.LtError):
+        lt.prefill_attn(cfg, q, k, k, 64, mask=7)
+
+
+# ---- lazy ratio from the prefill's log-sum-exp -------------------------------------------------------------
+
+def check_ratio_lse(B, Hq, Hkv, n, w, ws, wr, seed, mode=lt.RECENT_PER_QUERY, q_scale=2.0):
+    say("ratio-from-lse case", dict(B=B, Hq=Hq, Hkv=Hkv, n=n, w=w, ws=ws, wr=wr, mode=mode, seed=seed))
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, ws, wr, n)
+    q = randn_bf16((B, Hq, n, 128), seed, scale=q_scale)
+    k, v = randn_bf16((B, Hkv, n, 128), seed + 1), randn_bf16((B, Hkv, n, 128), seed + 2)
+    _, lse = lt.prefill_attn(cfg, q, k, v, n)
+    q_last = q[:, :, n - w:].contiguous()
+    mean, seq, rho = lt.lazy_ratio_lse(cfg, q_last, k, n, w, lse[:, :, n - w:], mode, want_rho=True)
+    # (1) against the oracle fed the same fp32 log-sum-exp values
+    log_rho, ref_seq, ref_r = oracle.lazy_ratio_from_lse(bits(q_last), bits(k), f64(lse[:, :, n - w:]), ws, wr, recent_mode=mode)
+    assert np.abs(f64(rho) - np.exp(log_rho)).max() <= TOL_RATIO
+    assert np.abs(f64(seq) - ref_seq).max() <= TOL_RATIO
+    assert abs(float(mean.cpu()[0]) - ref_r) <= TOL_RATIO
+    # (2) end to end against Eq. 1 computed by the oracle from scratch, and against the dense GPU form
+    ref_rho, _, ref_r1 = oracle.lazy_ratio(bits(q_last), bits(k), ws, wr, recent_mode=mode)
+    assert np.abs(f64(rho) - ref_rho).max() <= TOL_RATIO
+    assert abs(float(mean.cpu()[0]) - ref_r1) <= TOL_RATIO
+    mean_d, _, rho_d = lt.lazy_ratio(cfg, q_last, k, n, w, mode, want_rho=True)
+    assert np.abs(f64(rho) - f64(rho_d)).max() <= TOL_RATIO
+
+
+@pytest.mark.parametrize("n", [64, 65, 100, 257, 1000, 2600, 4133])
+def test_ratio_from_lse_prompt_lengths(n):
+    check_ratio_lse(B=2, Hq=8, Hkv=2, n=n, w=min(64, n), ws=4, wr=60, seed=6000 + n)
+
+
+@pytest.mark.parametrize("ws,wr", [(0, 252), (4, 1020), (6, 2044), (4, 0), (0, 1), (40, 70), (130, 300)])
+@pytest.mark.parametrize("mode", [lt.RECENT_PER_QUERY, lt.RECENT_FIXED])
+def test_ratio_from_lse_windows_and_both_readings(ws, wr, mode):
+    check_ratio_lse(B=1, Hq=4, Hkv=1, n=2600, w=64, ws=ws, wr=wr, seed=6100 + ws + wr, mode=mode)
+
+
+@pytest.mark.parametrize("w", [1, 8, 31, 33, 64])
+@pytest.mark.parametrize("group", [1, 5])
+def test_ratio_from_lse_scored_queries_and_groups(w, group):
+    check_ratio_lse(B=1, Hq=group, Hkv=1, n=900, w=w, ws=4, wr=124, seed=6200 + w + group)
