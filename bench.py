@@ -41,6 +41,8 @@ def parse_args():
     ap.add_argument("--no-speedup", action="store_true", help="skip the all-full comparison run")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the second pass that times kernels with HIP events")
+    ap.add_argument("--prefill", action="store_true",
+                    help="time lt_prefill_attn (causal and streaming masks) and lt_lazy_ratio_lse on layers of the workload")
     ap.add_argument("--scoring-only", action="store_true", help="run and report only the lazy-ratio scoring of every layer")
     ap.add_argument("--online", action="store_true",
                     help="set the stack up the paper's way: prefill layer by layer, score each layer from its cache, push "
@@ -276,6 +278,69 @@ def growth_curve(args, lt, W, wl, dev):
             "curve": points}
 
 
+def prefill_bench(args, lt, W, wl, dev):
+    """Prefill attention of single layers at the workload's prompt shape, the lazy ratio from its log-sum-exp, and the
+    dense lazy ratio beside it.  Times are HIP-event times on the launch stream (torch's current stream)."""
+    import numpy as np
+    import torch
+    cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink, wl.w_recent, wl.context)
+    n, w = wl.context, min(wl.w_last, wl.context)
+    layers = sorted(set(W.planted_lazy_layers(wl)[:1] + [l for l in range(wl.n_layers) if l not in W.planted_lazy_layers(wl)][:1]))
+    ws_lse = torch.empty(max(lt.lazy_ratio_lse_workspace_bytes(cfg, n, w), 256), dtype=torch.uint8, device=dev)
+    ws_dense = torch.empty(max(lt.lazy_ratio_workspace_bytes(cfg, n, w), 256), dtype=torch.uint8, device=dev)
+
+    def timed_ms(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    rows = []
+    for layer in layers:
+        q = W.prefill_queries(wl, layer, dev)
+        k, v = W.prefill_kv(wl, layer, dev)
+        q_last = q[:, :, n - w:].contiguous()
+        out, lse = lt.prefill_attn(cfg, q, k, v, n)
+        res = {}
+        def causal():
+            res["o"] = lt.prefill_attn(cfg, q, k, v, n)
+        def streaming():
+            res["s"] = lt.prefill_attn(cfg, q, k, v, n, lt.MASK_STREAMING)
+        def from_lse():
+            res["r"] = lt.lazy_ratio_lse(cfg, q_last, k, n, w, lse[:, :, n - w:], workspace=ws_lse)
+        def dense():
+            res["d"] = lt.lazy_ratio(cfg, q_last, k, n, w, workspace=ws_dense)
+        reps = max(1, min(args.steps, 4))
+        t_causal, t_stream = timed_ms(causal, reps), timed_ms(streaming, reps)
+        t_lse, t_dense = timed_ms(from_lse, 20), timed_ms(dense, 20)
+        r_lse, r_dense = float(res["r"][0].cpu()[0]), float(res["d"][0].cpu()[0])
+        pairs = n * (n + 1) / 2.0
+        window = wl.w_sink + wl.w_recent
+        pairs_stream = pairs if n <= window else window * (window + 1) / 2.0 + (n - window) * float(window)
+        flops = 4.0 * wl.batch * wl.n_q_heads * wl.head_dim * pairs
+        flops_stream = 4.0 * wl.batch * wl.n_q_heads * wl.head_dim * pairs_stream
+        row = {"layer": layer, "causal_ms": t_causal, "causal_tflops": flops / t_causal / 1e9,
+               "causal_mfma_frac": flops / t_causal / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+               "streaming_ms": t_stream, "streaming_tflops": flops_stream / t_stream / 1e9,
+               "ratio_from_lse_ms": t_lse, "ratio_dense_ms": t_dense, "ratio_from_lse": r_lse, "ratio_dense": r_dense,
+               "ratio_abs_diff": abs(r_lse - r_dense)}
+        log("layer %d: causal prefill %.2f ms (%.0f TFLOP/s), streaming %.2f ms (%.0f TFLOP/s), ratio from LSE %.3f ms vs dense %.3f ms, "
+            "r %.6f vs %.6f" % (layer, t_causal, row["causal_tflops"], t_stream, row["streaming_tflops"], t_lse, t_dense, r_lse, r_dense))
+        if abs(r_lse - r_dense) > 1e-4:
+            raise RuntimeError("the two forms of the lazy ratio disagree")
+        rows.append(row)
+        del q, k, v, out, lse, res
+        torch.cuda.empty_cache()
+    return {"metric": "prefill attention and lazy ratio from its log-sum-exp, per layer", "n_gpus": 1, "data": "synthetic",
+            "dtype": "bf16 operands, fp32 accumulate", "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.n_q_heads,
+            "kv_heads": wl.n_kv_heads, "context": n, "w_sink": wl.w_sink, "w_recent": wl.w_recent, "w_last": w}, "layers": rows}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -310,6 +375,9 @@ def main():
 
     if args.growth:
         print(json.dumps(growth_curve(args, lt, W, wl, dev)))
+        return 0
+    if args.prefill:
+        print(json.dumps(prefill_bench(args, lt, W, wl, dev)))
         return 0
 
     # ---- identification: score every layer, select ------------------------------------------------

@@ -166,6 +166,15 @@ def last_queries(wl: Workload, layer: int, device="cpu", w_last: Optional[int] =
     return _bias_queries(wl, layer, q)
 
 
+def prefill_queries(wl: Workload, layer: int, device="cpu") -> torch.Tensor:
+    """Queries of every prompt position: bf16 [B, Hq, n, d]; the last w_last rows are last_queries()."""
+    w = min(wl.w_last, wl.context)
+    q = randn_bf16((wl.batch, wl.n_q_heads, wl.context, wl.head_dim), seed_for(wl, layer, stream=4), device)
+    q = _bias_queries(wl, layer, q)
+    q[:, :, wl.context - w:] = last_queries(wl, layer, device, w)
+    return q
+
+
 def decode_qkv(wl: Workload, layer: int, step: int, device="cpu"):
     """Query, key and value of the token generated at `step`: q [B,Hq,d], k/v [B,Hkv,1,d], bf16."""
     q = randn_bf16((wl.batch, wl.n_q_heads, wl.head_dim), seed_for(wl, layer, step, stream=3), device)

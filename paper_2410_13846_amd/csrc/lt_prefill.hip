@@ -163,13 +163,11 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     const int blk = lane >> 4, src = lane & 15;
     const int v_lane_off = ((4 * (blk >> 1) + (src >> 2)) * kVRow + 16 * (blk & 1) + 4 * (src & 3)) * 2;
 
-    // one 32-key sub-tile: logits, softmax update, P V
-    auto subtile = [&](const uint16_t *tile_k, const uint16_t *tile_v, int kt, int64_t j0) {
-        // nothing of this sub-tile is visible to this wavefront's queries: later than all of them,
-        // or, for streaming attention, between the initial tokens and every query's window
-        if (j0 > q0 + kWaveQueries - 1) return;
-        if (a.streaming && j0 >= a.w_sink && j0 + 31 <= q0 - a.w_recent) return;
-        floatx16_t c[NT];
+    const int win_sink = a.streaming ? a.w_sink : 0x3fffffff;       // causal attention: every key counts as "initial"
+
+    // S^T of one 32-key sub-tile for this wavefront's queries, masked, and the sub-tile maximum of
+    // every query column in log2 units (both halves of a column agree on it)
+    auto logits = [&](floatx16_t (&c)[NT], float (&tmax)[NT], const uint16_t *tile_k, int kt, int64_t j0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -181,37 +179,37 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
         }
-
-        bf16x8_t pf[NT][2];                     // P^T fragments: [query tile][16-key step]
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int64_t p_min = q0 + nt * 32, p_max = p_min + 31;
-            bool clear = j0 + 31 <= p_min;                                       // causal for every pair
-            if (a.streaming) clear = clear && ((j0 + 31 < a.w_sink) || (j0 > p_max - a.w_recent));
+            // every (key, query) pair of the sub-tile is attended: causal, and inside the initial tokens or
+            // inside every query's recent window
+            const bool clear = (j0 + 31 <= p_min) && (!a.streaming || j0 + 31 < a.w_sink || j0 > p_max - a.w_recent);
             if (!clear) {
+                // positions relative to the sub-tile, clamped so that 32-bit compares decide
                 const int64_t p = p_min + col;
+                const int p_rel = (int)min(max(p - j0, (int64_t)-1), (int64_t)32);
+                const int sink_rel = (int)min(max((int64_t)win_sink - j0, (int64_t)0), (int64_t)32);
+                const int old_rel = (int)min(max(p - a.w_recent - j0, (int64_t)-1), (int64_t)32);   // last key before the window
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
-                    const int64_t j = j0 + 8 * (i >> 2) + 4 * half + (i & 3);
-                    bool keep = j <= p;
-                    if (a.streaming) keep = keep && (j < a.w_sink || j > p - a.w_recent);
+                    const int j_rel = 8 * (i >> 2) + 4 * half + (i & 3);
+                    const bool keep = (j_rel <= p_rel) & ((j_rel < sink_rel) | (j_rel > old_rel));
                     c[nt][i] = keep ? c[nt][i] : -INFINITY;
                 }
             }
-            float tmax = c[nt][0];
+            float t = c[nt][0];
 #pragma unroll
-            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, c[nt][i]);
-            tmax = max_halves(tmax) * a.scale_log2e;
-            const bool grow = tmax > m_ref[nt] + kRescaleStep;
-            if (__any(grow)) {
-                const float alpha = grow ? fast_exp2(m_ref[nt] - tmax) : 1.f;      // 0 when the reference was -inf
-                m_ref[nt] = grow ? tmax : m_ref[nt];
-                l_sum[nt] *= alpha;
+            for (int i = 1; i < 16; ++i) t = fmaxf(t, c[nt][i]);
+            tmax[nt] = max_halves(t) * a.scale_log2e;
+        }
+    };
+
+    // probabilities against the current reference, their sum, and O^T += V^T P^T
+    auto accumulate = [&](const floatx16_t (&c)[NT], const uint16_t *tile_v, int kt) {
+        bf16x8_t pf[NT][2];                      // P^T fragments: [query tile][16-key step]
 #pragma unroll
-                for (int dt = 0; dt < 4; ++dt)
-#pragma unroll
-                    for (int i = 0; i < 16; ++i) acc[dt][nt][i] *= alpha;
-            }
+        for (int nt = 0; nt < NT; ++nt) {
             const float mu = m_ref[nt] == -INFINITY ? 0.f : m_ref[nt];
             float pr[16], sum = 0.f;
 #pragma unroll
@@ -227,12 +225,11 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
                 pf[nt][sp] = __builtin_bit_cast(bf16x8_t, u);
             }
         }
-
-        // O^T += V^T P^T: k slots e = 0..3 of a lane are keys 16 sp + 4 half + e, slots 4..7 the same + 8,
-        // which is the order the logits sit in the accumulator registers 8 sp .. 8 sp + 7
+        // k slots e = 0..3 of a lane are keys 16 sp + 4 half + e, slots 4..7 the same + 8, which is
+        // the order the logits sit in the accumulator registers 8 sp .. 8 sp + 7
         const char *vbytes = reinterpret_cast<const char *>(tile_v) + v_lane_off;
 #pragma unroll
-        for (int sp = 0; sp < 2; ++sp) {
+        for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
                 const int off = ((32 * kt + 16 * sp) * kVRow + 32 * dt) * 2;
@@ -246,29 +243,90 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][sp], acc[dt][nt], 0, 0, 0);
             }
-        }
+    };
+
+    // nothing of the sub-tile is visible to this wavefront's queries: later than all of them, or,
+    // for streaming attention, between the initial tokens and every query's window
+    auto dead = [&](int64_t j0) {
+        return j0 > q0 + kWaveQueries - 1 || (a.streaming && j0 >= a.w_sink && j0 + 31 <= q0 - a.w_recent);
     };
 
     u32x4_t pre_k[kPieces], pre_v[kPieces];
-    fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(0), a.n);
-    fetch_tile<W>(pre_v, vb, a.kv_stride_t, tile_key(0), a.n);
-    commit_tile<W, kKRow>(pre_k, sh_k[0]);
-    commit_tile<W, kVRow>(pre_v, sh_v[0]);
-    __syncthreads();
-    for (int t = 0; t < n_tiles; ++t) {
-        const int buf = t & 1;
-        if (t + 1 < n_tiles) {
-            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t + 1), a.n);
-            fetch_tile<W>(pre_v, vb, a.kv_stride_t, tile_key(t + 1), a.n);
+    auto prefetch = [&](int t) {
+        if (t < n_tiles) {
+            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), a.n);
+            fetch_tile<W>(pre_v, vb, a.kv_stride_t, tile_key(t), a.n);
         }
-        const int64_t j0 = tile_key(t);
-        subtile(sh_k[buf], sh_v[buf], 0, j0);
-        subtile(sh_k[buf], sh_v[buf], 1, j0 + 32);
-        if (t + 1 < n_tiles) {
-            commit_tile<W, kKRow>(pre_k, sh_k[buf ^ 1]);
-            commit_tile<W, kVRow>(pre_v, sh_v[buf ^ 1]);
+    };
+    auto park = [&](int t) {                     // registers of tile t -> its LDS buffer, then everyone may read it
+        if (t < n_tiles) {
+            commit_tile<W, kKRow>(pre_k, sh_k[t & 1]);
+            commit_tile<W, kVRow>(pre_v, sh_v[t & 1]);
         }
         __syncthreads();
+    };
+
+    // One sub-tile with the reference of every row moved first where its maximum has outgrown it.
+    auto careful = [&](int t, int kt) {
+        const int64_t j0 = tile_key(t) + 32 * kt;
+        if (dead(j0)) return;
+        floatx16_t c[NT];
+        float tmax[NT];
+        logits(c, tmax, sh_k[t & 1], kt, j0);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            const bool grow = tmax[nt] > m_ref[nt] + kRescaleStep;
+            const float alpha = grow ? fast_exp2(m_ref[nt] - tmax[nt]) : 1.f;   // 0 when the reference was -inf
+            m_ref[nt] = grow ? tmax[nt] : m_ref[nt];
+            l_sum[nt] *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 4; ++dt)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[dt][nt][i] *= alpha;
+        }
+        accumulate(c, sh_v[t & 1], kt);
+    };
+    // The same without touching the references: returns false, having changed nothing, when some
+    // row's maximum has outgrown its reference.
+    auto quick = [&](int t, int kt) {
+        const int64_t j0 = tile_key(t) + 32 * kt;
+        if (dead(j0)) return true;
+        floatx16_t c[NT];
+        float tmax[NT];
+        logits(c, tmax, sh_k[t & 1], kt, j0);
+        bool grow = false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) grow = grow || tmax[nt] > m_ref[nt] + kRescaleStep;
+        if (__any(grow)) return false;
+        accumulate(c, sh_v[t & 1], kt);
+        return true;
+    };
+
+    prefetch(0);
+    park(0);
+    // The accumulator is multiplied only in the outer loop; the inner loop, which runs until some
+    // row's maximum outgrows its reference, touches it with matrix instructions alone, so it can
+    // stay in the accumulation registers for the whole stretch.
+    int t = 0, kt = 0;
+    while (t < n_tiles) {
+        if (kt == 0) {
+            prefetch(t + 1);
+            careful(t, 0);
+        }
+        careful(t, 1);
+        park(t + 1);
+        ++t;
+        kt = 0;
+        while (t < n_tiles) {
+            prefetch(t + 1);
+            if (!quick(t, 0)) break;
+            if (!quick(t, 1)) {
+                kt = 1;
+                break;
+            }
+            park(t + 1);
+            ++t;
+        }
     }
 
     // normalise and store: a lane holds, for its query, dims 32 dt + 8 (i / 4) + 4 half + (i % 4)
