@@ -154,7 +154,8 @@ lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void
  *         layer that runs streaming attention from the start does (LightTransfer-Train).
  *   q         device, bf16 [B][Hq][n][128]
  *   k, v      device, bf16; (sequence b, KV head g, position j) at element offset b*kv_stride_b +
- *             g*kv_stride_h + j*kv_stride_t of each; 128 dims contiguous, strides multiples of 8
+ *             g*kv_stride_h + j*kv_stride_t of each; 128 dims contiguous, strides multiples of 8,
+ *             128 <= kv_stride_t < 2^24
  *             (may point into the KV slab of a full layer after lt_append_kv of the prompt)
  *   out       device, [B][Hq][n][128], bf16 (LT_OUT_BF16) or fp32 (LT_OUT_F32)
  *   lse_out   device, fp32 [B][Hq][n]: natural log of each row's softmax denominator

@@ -495,7 +495,9 @@ lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, co
     if (shape != LT_OK) return shape;
     if (n > kMaxTokens) return LT_ERR_SHAPE;
     if (mask == LT_MASK_STREAMING && cfg->w_sink + cfg->w_recent < 1) return LT_ERR_SHAPE;
-    if (kv_stride_t < ltk::kHeadDim || (kv_stride_b % 8) != 0 || (kv_stride_h % 8) != 0 || (kv_stride_t % 8) != 0) return LT_ERR_SHAPE;
+    if (kv_stride_t < ltk::kHeadDim || kv_stride_t >= ((int64_t)1 << 24) || (kv_stride_b % 8) != 0 || (kv_stride_h % 8) != 0 ||
+        (kv_stride_t % 8) != 0)
+        return LT_ERR_SHAPE;
     if (((uintptr_t)q % 16) != 0 || ((uintptr_t)k % 16) != 0 || ((uintptr_t)v % 16) != 0 || ((uintptr_t)out % 16) != 0 ||
         ((uintptr_t)lse_out % 4) != 0)
         return LT_ERR_INVALID_ARG;

@@ -10,9 +10,10 @@
 //   S^T = K Q^T   rows = keys, columns = queries: a lane holds 16 logits of ONE query, so the
 //                 running max and sum of a softmax row stay in two lanes (the two halves);
 //   O^T = V^T P^T rows = head dims, columns = queries: the probabilities a lane has just
-//                 computed are, packed to bf16, exactly the B operand of its own column, and
-//                 V^T comes out of the row-major V tile with the LDS transpose read
-//                 (ds_read_b64_tr_b16), which hands a lane four consecutive keys of one dim.
+//                 computed are, packed to bf16, exactly the B operand of its own column; the V
+//                 tile is transposed in registers on its way into LDS, with the keys of each
+//                 group of 16 stored in the order the logits have in the accumulator registers,
+//                 so that a lane's eight keys of one dim are one 16-byte read.
 // The softmax reference point of a row moves only when the row's maximum has grown by more than
 // 2^8 since it was set: any reference gives the same quotient, the probabilities stay below 2^8,
 // and the accumulator is rescaled a handful of times per row instead of once per tile.
@@ -25,13 +26,12 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;
 typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2_t;
-typedef short v4i16_t __attribute__((ext_vector_type(4)));
 typedef float float2_t __attribute__((ext_vector_type(2)));
 typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 
 constexpr int kTileKeys = 64;                 // keys per LDS tile
 constexpr int kKRow = kHeadDim + 8;           // 272-byte K rows: 16-byte reads of 32 rows spread over the banks
-constexpr int kVRow = kHeadDim + 32;          // 320-byte V rows: the 4 rows x 64 bytes of a transpose read do not collide
+constexpr int kVtRow = kTileKeys + 8;         // V^T tile: 128 dim rows of 64 key slots, 144-byte rows (16-byte reads of 16 rows spread over the banks)
 constexpr float kRescaleStep = 8.f;           // log2 units the row maximum may exceed the reference before it moves
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
@@ -69,16 +69,19 @@ struct Stage {
     static constexpr int kPieces = (kTotal + kThreads - 1) / kThreads;
 };
 
+// Rows past the end of the prompt are read from its last key (they are masked as non-causal).
+// The row offset inside a tile is a 32-bit product: the API keeps the token stride below 2^24.
 template <int W>
 __device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int64_t j0, int64_t n)
 {
+    const uint16_t *tile = base + j0 * stride_t;                         // uniform
+    const int last = (int)min(n - 1 - j0, (int64_t)(kTileKeys - 1));
 #pragma unroll
     for (int i = 0; i < Stage<W>::kPieces; ++i) {
         int idx = threadIdx.x + i * Stage<W>::kThreads;
         idx = idx < Stage<W>::kTotal ? idx : Stage<W>::kTotal - 1;       // surplus threads re-read the last piece
-        int64_t j = j0 + (idx >> 4);
-        j = j < n ? j : n - 1;                                           // keys past the prompt are masked as non-causal
-        pre[i] = *reinterpret_cast<const u32x4_t *>(base + j * stride_t + (idx & 15) * 8);
+        const int row = min(idx >> 4, last);
+        pre[i] = *reinterpret_cast<const u32x4_t *>(tile + (row * (int)stride_t + (idx & 15) * 8));
     }
 }
 
@@ -92,6 +95,39 @@ __device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kPiec
     }
 }
 
+// V staging.  Work item (c, kg) = 8 dims x 4 consecutive keys: four 16-byte loads (one per key), an 8 x 4
+// transpose in registers, eight 8-byte LDS writes (one per dim).  The first 256 threads do it; lanes whose
+// dim chunks fall on the same banks take key groups 32 keys apart, so that a write of 32 lanes covers all banks.
+// Slot of key j (0..63) in a V^T row: 16 (j / 16) + {0, 8, 4, 12}[(j % 16) / 4] + j % 4, i.e. within 16 keys the
+// order 0-3, 8-11, 4-7, 12-15: slots 8 h .. 8 h + 7 then hold keys 4 h + {0..3} and 8 + 4 h + {0..3}.
+__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base, int64_t stride_t, int64_t j0, int64_t n)
+{
+    if (threadIdx.x >= 256) return;
+    const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2);
+    const uint16_t *tile = base + j0 * stride_t;
+    const int last = (int)min(n - 1 - j0, (int64_t)(kTileKeys - 1));
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+        const int row = min(4 * kg + r, last);
+        pre[r] = *reinterpret_cast<const u32x4_t *>(tile + (row * (int)stride_t + c * 8));
+    }
+}
+
+__device__ __forceinline__ void commit_v(const u32x4_t (&pre)[4], uint16_t *sh)
+{
+    if (threadIdx.x >= 256) return;
+    const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2);
+    const int slot = 16 * (kg >> 2) + ((0x0C040800 >> (8 * (kg & 3))) & 0xff);
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        // dims 2 w (low halves) and 2 w + 1 (high halves) of the four keys
+        const u32x2_t even = {__builtin_amdgcn_perm(pre[1][w], pre[0][w], 0x05040100u), __builtin_amdgcn_perm(pre[3][w], pre[2][w], 0x05040100u)};
+        const u32x2_t odd = {__builtin_amdgcn_perm(pre[1][w], pre[0][w], 0x07060302u), __builtin_amdgcn_perm(pre[3][w], pre[2][w], 0x07060302u)};
+        *reinterpret_cast<u32x2_t *>(&sh[(8 * c + 2 * w) * kVtRow + slot]) = even;
+        *reinterpret_cast<u32x2_t *>(&sh[(8 * c + 2 * w + 1) * kVtRow + slot]) = odd;
+    }
+}
+
 // G: query heads per KV head.  QB: query sub-blocks per workgroup.  NT: 32-query tiles per wavefront.
 template <int G, int QB, int NT>
 __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArgs a)
@@ -99,10 +135,12 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     constexpr int W = G * QB;                          // wavefronts
     constexpr int kWaveQueries = 32 * NT, kBlockQueries = kWaveQueries * QB;
     __shared__ __attribute__((aligned(16))) uint16_t sh_k[2][kTileKeys * kKRow];
-    __shared__ __attribute__((aligned(16))) uint16_t sh_v[2][kTileKeys * kVRow];
+    __shared__ __attribute__((aligned(16))) uint16_t sh_v[2][kHeadDim * kVtRow];
+    static_assert(W >= 4, "V staging needs 256 threads");
     constexpr int kPieces = Stage<W>::kPieces;
 
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // in a scalar register: what depends on it branches uniformly
     const int col = lane & 31, half = lane >> 5;
 
     // Workgroups that run at the same time on one XCD (linear index mod 8) work on neighbouring
@@ -157,11 +195,6 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     float m_ref[NT], l_sum[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { m_ref[nt] = -INFINITY; l_sum[nt] = 0.f; }
-
-    // transpose-read lane offset into a V tile (bytes): source lane (k, j) of a 16-lane block
-    // points at 4 dims of key row k; the block's result lane i then holds dim d0 + i of 4 keys
-    const int blk = lane >> 4, src = lane & 15;
-    const int v_lane_off = ((4 * (blk >> 1) + (src >> 2)) * kVRow + 16 * (blk & 1) + 4 * (src & 3)) * 2;
 
     const int win_sink = a.streaming ? a.w_sink : 0x3fffffff;       // causal attention: every key counts as "initial"
 
@@ -225,20 +258,13 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
                 pf[nt][sp] = __builtin_bit_cast(bf16x8_t, u);
             }
         }
-        // k slots e = 0..3 of a lane are keys 16 sp + 4 half + e, slots 4..7 the same + 8, which is
-        // the order the logits sit in the accumulator registers 8 sp .. 8 sp + 7
-        const char *vbytes = reinterpret_cast<const char *>(tile_v) + v_lane_off;
+        // k slots 0..7 of a lane are keys 16 sp + 4 half + {0..3} and 16 sp + 8 + 4 half + {0..3}: the order the
+        // logits sit in the accumulator registers 8 sp .. 8 sp + 7, and the order of the V^T slots
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                const int off = ((32 * kt + 16 * sp) * kVRow + 32 * dt) * 2;
-                const v4i16_t lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) v4i16_t *)(vbytes + off));
-                const v4i16_t hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) v4i16_t *)(vbytes + off + 8 * kVRow * 2));
-                const u32x2_t lo2 = __builtin_bit_cast(u32x2_t, lo), hi2 = __builtin_bit_cast(u32x2_t, hi);
-                const u32x4_t u = {lo2[0], lo2[1], hi2[0], hi2[1]};
+                const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&tile_v[(32 * dt + col) * kVtRow + 32 * kt + 16 * sp + 8 * half]);
                 const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, u);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][sp], acc[dt][nt], 0, 0, 0);
@@ -251,17 +277,17 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         return j0 > q0 + kWaveQueries - 1 || (a.streaming && j0 >= a.w_sink && j0 + 31 <= q0 - a.w_recent);
     };
 
-    u32x4_t pre_k[kPieces], pre_v[kPieces];
+    u32x4_t pre_k[kPieces], pre_v[4];
     auto prefetch = [&](int t) {
         if (t < n_tiles) {
             fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), a.n);
-            fetch_tile<W>(pre_v, vb, a.kv_stride_t, tile_key(t), a.n);
+            fetch_v(pre_v, vb, a.kv_stride_t, tile_key(t), a.n);
         }
     };
     auto park = [&](int t) {                     // registers of tile t -> its LDS buffer, then everyone may read it
         if (t < n_tiles) {
             commit_tile<W, kKRow>(pre_k, sh_k[t & 1]);
-            commit_tile<W, kVRow>(pre_v, sh_v[t & 1]);
+            commit_v(pre_v, sh_v[t & 1]);
         }
         __syncthreads();
     };
@@ -368,15 +394,15 @@ hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-// Up to four wavefronts per workgroup run alone on their SIMD with the whole register file and take
-// 64 queries each; larger groups share SIMDs and take 32.
+// Eight wavefronts per workgroup where the group size allows: two per SIMD, so that one's matrix
+// instructions overlap the other's exponentials; each takes 32 queries.
 hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream)
 {
     switch (a.n_q_heads / a.n_kv_heads) {
-    case 1: return launch_prefill<1, 4, 2>(a, stream);
-    case 2: return launch_prefill<2, 2, 2>(a, stream);
-    case 3: return launch_prefill<3, 1, 2>(a, stream);
-    case 4: return launch_prefill<4, 1, 2>(a, stream);
+    case 1: return launch_prefill<1, 8, 1>(a, stream);
+    case 2: return launch_prefill<2, 4, 1>(a, stream);
+    case 3: return launch_prefill<3, 2, 1>(a, stream);
+    case 4: return launch_prefill<4, 2, 1>(a, stream);
     case 5: return launch_prefill<5, 1, 1>(a, stream);
     case 6: return launch_prefill<6, 1, 1>(a, stream);
     case 7: return launch_prefill<7, 1, 1>(a, stream);
