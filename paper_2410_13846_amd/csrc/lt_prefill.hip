@@ -205,6 +205,9 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
+        // the chain runs at raised priority: the SIMD's other wavefront fills the gaps between the
+        // matrix instructions with its exponentials instead of delaying them
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&tile_k[(32 * kt + col) * kKRow + 16 * s + 8 * half]);
@@ -212,6 +215,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
         }
+        __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const int64_t p_min = q0 + nt * 32, p_max = p_min + 31;
