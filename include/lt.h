@@ -180,6 +180,16 @@ lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, co
 lt_status lt_select_lazy(const float *ratios_host, int32_t n_layers, int32_t n_lazy, uint8_t *is_lazy_out,
                          int32_t *order_out);
 
+/* Pre-selection of a fixed lazy set from many samples (Section "LightTransfer-Train"; pure host
+ * code): every sample contributes the lazy set it would choose on its own (lt_lazy_ratio +
+ * lt_select_lazy on the sample's question + answer); the n_lazy layers chosen most often become
+ * the fixed set, equal frequencies going to the lower layer index.
+ *   is_lazy_samples  host, uint8 [n_samples][n_layers], non-zero = sample chose the layer
+ *   is_lazy_out      host, uint8 [n_layers], 1 = selected
+ *   count_out        host, int32 [n_layers], frequency of every layer; may be NULL */
+lt_status lt_preselect_lazy(const uint8_t *is_lazy_samples, int32_t n_samples, int32_t n_layers, int32_t n_lazy,
+                            uint8_t *is_lazy_out, int32_t *count_out);
+
 /* ---- online identification during prefill (Section "LightTransfer-Test", Figure 3) ---------- */
 
 /* The paper's procedure: after each layer's prefill its (ratio, layer) is pushed into a

@@ -65,6 +65,8 @@ def _load():
         lib.lto_select_lazy.restype = c_int
         lib.lto_select_lazy_queue.argtypes = [f64p, c_int, c_int, u8p, i32p]
         lib.lto_select_lazy_queue.restype = c_int
+        lib.lto_preselect_lazy.argtypes = [u8p, c_int, c_int, c_int, i32p, u8p]
+        lib.lto_preselect_lazy.restype = c_int
         lib.lto_num_threads.restype = c_int
         lib.lto_set_num_threads.argtypes = [c_int]
         _lib = lib
@@ -232,6 +234,18 @@ def select_lazy_queue(ratios, n_lazy):
                                        _ptr(is_lazy, ctypes.c_ubyte), _ptr(pop_step, ctypes.c_int))
     _check(st, "select_lazy_queue")
     return is_lazy, pop_step
+
+
+def preselect_lazy(sets, n_lazy):
+    """LightTransfer-Train pre-selection.  sets uint8 [S, L]; returns (is_lazy u8 [L], count i32 [L])."""
+    m = np.ascontiguousarray(np.asarray(sets) != 0, dtype=np.uint8)
+    S, L = m.shape
+    is_lazy = np.zeros((L,), dtype=np.uint8)
+    count = np.zeros((L,), dtype=np.int32)
+    st = _load().lto_preselect_lazy(_ptr(m, ctypes.c_ubyte), S, L, int(n_lazy), _ptr(count, ctypes.c_int),
+                                    _ptr(is_lazy, ctypes.c_ubyte))
+    _check(st, "preselect_lazy")
+    return is_lazy, count
 
 
 class History:

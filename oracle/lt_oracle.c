@@ -479,6 +479,38 @@ int lto_select_lazy_queue(const double *r, int L, int n_lazy, unsigned char *is_
 }
 
 /* Threads the parallel loops above will use (1 when built without OpenMP). */
+/*
+ * LightTransfer-Train pre-selection: every training sample, fed with question and answer,
+ * yields its own set of lazy layers; a layer's frequency is the number of samples that chose
+ * it, and the n_lazy most frequent layers become the fixed lazy set (equal frequencies go to
+ * the lower layer index, the rule of the priority queue).
+ *
+ *   sets     [S, L]  1 where sample s chose layer l
+ *   count    [L]     frequency of every layer (may be NULL)
+ *   is_lazy  [L]     1 for the selected layers
+ */
+int lto_preselect_lazy(const unsigned char *sets, int S, int L, int n_lazy, int *count, unsigned char *is_lazy)
+{
+    if (!sets || !is_lazy || S <= 0 || L <= 0 || n_lazy < 0 || n_lazy > L) return LTO_ERR_ARG;
+    int *freq = (int *)calloc((size_t)L, sizeof(int));
+    if (!freq) return LTO_ERR_NOMEM;
+    for (int s = 0; s < S; ++s)
+        for (int l = 0; l < L; ++l)
+            if (sets[(size_t)s * L + l]) freq[l] += 1;
+    memset(is_lazy, 0, (size_t)L);
+    for (int pick = 0; pick < n_lazy; ++pick) {
+        int best = -1;
+        for (int l = 0; l < L; ++l) {
+            if (is_lazy[l]) continue;
+            if (best < 0 || freq[l] > freq[best]) best = l;     /* strict: the first of equals stays */
+        }
+        is_lazy[best] = 1;
+    }
+    if (count) memcpy(count, freq, (size_t)L * sizeof(int));
+    free(freq);
+    return LTO_OK;
+}
+
 #ifdef _OPENMP
 #include <omp.h>
 int lto_num_threads(void) { return omp_get_max_threads(); }

@@ -546,6 +546,29 @@ lt_status lt_select_lazy(const float *ratios_host, int32_t n_layers, int32_t n_l
     return LT_OK;
 }
 
+lt_status lt_preselect_lazy(const uint8_t *is_lazy_samples, int32_t n_samples, int32_t n_layers, int32_t n_lazy,
+                            uint8_t *is_lazy_out, int32_t *count_out)
+{
+    if (is_lazy_samples == nullptr || is_lazy_out == nullptr || n_samples <= 0 || n_layers <= 0 || n_lazy < 0 || n_lazy > n_layers)
+        return LT_ERR_INVALID_ARG;
+    std::vector<int32_t> count, order;
+    try {
+        count.assign(n_layers, 0);
+        order.resize(n_layers);
+    } catch (const std::bad_alloc &) {
+        return LT_ERR_NOMEM;
+    }
+    for (int64_t s = 0; s < n_samples; ++s)
+        for (int l = 0; l < n_layers; ++l) count[l] += is_lazy_samples[s * n_layers + l] != 0;
+    for (int l = 0; l < n_layers; ++l) order[l] = l;
+    // most frequent first; equal counts keep layer order
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return count[x] > count[y]; });
+    std::memset(is_lazy_out, 0, (size_t)n_layers);
+    for (int i = 0; i < n_lazy; ++i) is_lazy_out[order[i]] = 1;
+    if (count_out != nullptr) std::memcpy(count_out, count.data(), (size_t)n_layers * sizeof(int32_t));
+    return LT_OK;
+}
+
 // ---- decoding ------------------------------------------------------------------------------------
 
 lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new, void *stream)

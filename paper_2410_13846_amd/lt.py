@@ -23,7 +23,7 @@ EXPORTS = [
     "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
     "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
-    "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn",
+    "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
 ]
 
 
@@ -84,6 +84,8 @@ def load() -> ctypes.CDLL:
     lib.lt_prefill_attn.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, vp, vp]
     lib.lt_prefill_attn.restype = ctypes.c_int
     lib.lt_select_lazy.argtypes = [vp, i32, i32, vp, vp]
+    lib.lt_preselect_lazy.argtypes = [vp, i32, i32, i32, vp, vp]
+    lib.lt_preselect_lazy.restype = ctypes.c_int
     lib.lt_select_lazy.restype = ctypes.c_int
     lib.lt_append_kv.argtypes = [vp, i32, vp, vp, i64, vp]
     lib.lt_append_kv.restype = ctypes.c_int
@@ -168,6 +170,18 @@ def select_lazy(ratios, n_lazy: int):
     st = load().lt_select_lazy(r.ctypes.data, L, int(n_lazy), is_lazy.ctypes.data, order.ctypes.data)
     _check(st, "lt_select_lazy")
     return is_lazy, order
+
+
+def preselect_lazy(is_lazy_samples, n_lazy: int):
+    """Host-only.  is_lazy_samples uint8 [S, L].  Returns (is_lazy uint8 [L], count int32 [L])."""
+    m = np.ascontiguousarray(np.asarray(is_lazy_samples, dtype=np.uint8))
+    if m.ndim != 2:
+        raise TypeError("is_lazy_samples must be [samples, layers]")
+    S, L = m.shape
+    is_lazy = np.zeros(L, dtype=np.uint8)
+    count = np.zeros(L, dtype=np.int32)
+    _check(load().lt_preselect_lazy(m.ctypes.data, S, L, int(n_lazy), is_lazy.ctypes.data, count.ctypes.data), "lt_preselect_lazy")
+    return is_lazy, count
 
 
 def lazy_ratio(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_last: int, mode: int = RECENT_PER_QUERY,

@@ -163,6 +163,22 @@ def test_select_lazy_rejects_bad_input():
     assert lt.status_str(lt.ERR_CAPACITY) == "capacity exceeded"
 
 
+def test_preselect_lazy_matches_the_oracle():
+    """Pre-selection over many samples (host code): frequencies and the most frequent layers, ties to the lower index."""
+    rng = np.random.default_rng(13)
+    for S, L in ((1, 4), (9, 32), (300, 64)):
+        for n_lazy in {0, 1, L // 2, L}:
+            sets = (rng.random((S, L)) < rng.random(L)).astype(np.uint8)
+            if S > 1:
+                sets[:, 1] = sets[:, 0]                                  # two layers with equal frequency
+            got, count = lt.preselect_lazy(sets, n_lazy)
+            ref, ref_count = oracle.preselect_lazy(sets, n_lazy)
+            np.testing.assert_array_equal(got, ref)
+            np.testing.assert_array_equal(count, ref_count)
+    with pytest.raises(lt.LtError):
+        lt.preselect_lazy(np.zeros((2, 4), np.uint8), 5)
+
+
 # ---- online identification (priority queue + slot pools), host side only -----------------------
 
 def test_select_push_reproduces_the_queue_procedure():

@@ -80,3 +80,44 @@ def test_paper_settings_half_and_quarter(hyperparams):
     assert half.sum() == 16 and quarter.sum() == 8
     assert ((quarter == 1) <= (half == 1)).all()           # nested: the laziest quarter is inside the laziest half
     assert r[half == 1].min() >= r[half == 0].max()
+
+
+# ---- LightTransfer-Train pre-selection: per-sample sets -> layer frequencies -> most frequent layers ----
+
+def numpy_preselect(sets, n_lazy):
+    count = np.asarray(sets, dtype=np.int64).astype(bool).sum(axis=0)
+    order = np.lexsort((np.arange(len(count)), -count))                     # frequency desc, index asc
+    mask = np.zeros(len(count), dtype=np.uint8)
+    mask[order[:n_lazy]] = 1
+    return mask, count
+
+
+@pytest.mark.parametrize("S,L", [(1, 8), (5, 8), (40, 32), (200, 64)])
+def test_preselection_counts_and_picks_most_frequent(S, L):
+    for n_lazy in sorted({0, 1, L // 2, L - 1, L}):
+        sets = (RNG.random((S, L)) < RNG.random(L)).astype(np.uint8)       # layers with different propensities
+        mask, count = oracle.preselect_lazy(sets, n_lazy)
+        ref_mask, ref_count = numpy_preselect(sets, n_lazy)
+        np.testing.assert_array_equal(count, ref_count)
+        np.testing.assert_array_equal(mask, ref_mask)
+        assert mask.sum() == n_lazy
+
+
+def test_preselection_special_cases():
+    one = np.array([[0, 1, 1, 0, 1, 0]], dtype=np.uint8)
+    mask, count = oracle.preselect_lazy(one, 3)                              # one sample: its own set
+    np.testing.assert_array_equal(mask, one[0])
+    same = np.repeat(one, 7, axis=0)
+    mask, count = oracle.preselect_lazy(same, 3)                             # unanimous samples: that set, count = S
+    np.testing.assert_array_equal(mask, one[0])
+    np.testing.assert_array_equal(count, 7 * one[0])
+    tie = np.array([[1, 0, 1, 0], [0, 1, 0, 1]], dtype=np.uint8)             # all frequencies equal: lowest indices
+    mask, _ = oracle.preselect_lazy(tie, 2)
+    np.testing.assert_array_equal(mask, [1, 1, 0, 0])
+    # per-sample sets chosen by ratio, then pre-selected: a layer that is lazy in most samples wins over one
+    # that has the single largest ratio once
+    ratios = np.array([[0.9, 0.5, 0.1], [0.2, 0.6, 0.1], [0.3, 0.7, 0.1]])
+    sets = np.stack([oracle.select_lazy(r, 1)[0] for r in ratios])
+    mask, count = oracle.preselect_lazy(sets, 1)
+    np.testing.assert_array_equal(count, [1, 2, 0])
+    np.testing.assert_array_equal(mask, [0, 1, 0])
