@@ -235,21 +235,45 @@ lt_status lt_truncate_layer(lt_ctx *ctx, int32_t layer, void *stream);
 lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new,
                        void *stream);
 
+/* Ragged batches (serving: prompts of different lengths in one batch).  Like lt_append_kv, but
+ * sequence b brings only its first n_per_seq_host[b] tokens of the padded input (0 <= n <= n_max);
+ * from then on the layer keeps one token count per sequence: later lt_append_kv / lt_decode_step
+ * calls add the same number of tokens to every sequence, lt_decode_attn / lt_decode_step attend,
+ * for sequence b, over that sequence's own stored entries (all of its tokens in a full layer, its
+ * own first w_sink and last w_recent in a lazy layer), and a sequence without tokens yields out = 0,
+ * lse = -inf.  lt_layer_len then reports the longest sequence, lt_seq_len one sequence.
+ *   k_new, v_new     device, bf16 [B][Hkv][n_max][128]; rows past a sequence's count are not read
+ *   n_per_seq_host   host, int64 [B]
+ * The per-sequence counts travel to the kernels as launch arguments: nothing is allocated or copied.
+ * LT_ERR_SHAPE if batch > 64; LT_ERR_STATE on a context made by lt_create_online; LT_ERR_CAPACITY
+ * if the longest sequence would exceed max_tokens. */
+lt_status lt_append_kv_ragged(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_max,
+                              const int64_t *n_per_seq_host, void *stream);
+
+/* Tokens appended to / stored for one sequence of a layer (equal for all sequences unless
+ * lt_append_kv_ragged was used).  Either output may be NULL. */
+lt_status lt_seq_len(const lt_ctx *ctx, int32_t layer, int32_t sequence, int64_t *total_tokens, int64_t *stored_tokens);
+
+/* Element type of `out` in lt_decode_attn / lt_decode_step from now on: LT_OUT_F32 (the default)
+ * or LT_OUT_BF16 (rounded to nearest even from the fp32 result; what a bf16 model consumes). */
+lt_status lt_set_output_dtype(lt_ctx *ctx, lt_out_dtype dtype);
+
 /* Attention of the newest token of every sequence over the layer's cache, to be called after the
  * token's own K/V were appended (the causal mask keeps the diagonal).
  *   q        device, bf16 [B][Hq][128]
- *   out      device, fp32 [B][Hq][128]: sum_j softmax_j(softmax_scale * q.k_j) v_j over the stored entries
+ *   out      device, [B][Hq][128], fp32 unless lt_set_output_dtype chose bf16:
+ *            sum_j softmax_j(softmax_scale * q.k_j) v_j over the stored entries
  *   lse_out  device, fp32 [B][Hq]: natural-log of the softmax denominator; may be NULL
  * One launch: workgroups each take a range of the stored entries and the last one to finish
  * merges the ranges by their log-sum-exp.  LT_ERR_STATE if the layer is empty. */
-lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream);
+lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, void *out, float *lse_out, void *stream);
 
 /* One decoding step of a layer in a single launch: lt_append_kv of one token followed by
  * lt_decode_attn, with the same result and the same effect on the cache and the token count.
  *   k_new, v_new  device, bf16 [B][Hkv][128], the K/V of the token being generated
  * The decode kernel takes the new token from k_new / v_new and stores it into its cache slot on
  * the way.  LT_ERR_CAPACITY as for lt_append_kv; on error nothing is enqueued or counted. */
-lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out,
+lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
                          float *lse_out, void *stream);
 
 /* ---- tuning and measurement ---------------------------------------------------------------- */

@@ -75,7 +75,8 @@ int64_t max_splits(const lt_config *c)
 struct Layer {
     uint16_t *k = nullptr, *v = nullptr;
     int64_t capacity = 0;
-    int64_t total = 0;
+    int64_t total = 0;                          // tokens appended so far (ragged batches: of the longest sequence)
+    std::vector<int64_t> total_b;               // ragged batches: tokens of every sequence; empty while all are equal
     bool lazy = false;
     int32_t slot = -1;                          // online mode: index of the full / ring slot in use, -1 = none yet
 };
@@ -95,6 +96,7 @@ struct lt_ctx {
     bool tickets_ready = false;                // zeroed by the first decode call (lt_create enqueues nothing)
     int64_t splits_cap = 0;
     int32_t keys_full = 0, keys_lazy = 0;      // 0 = heuristic
+    bool out_bf16 = false;                     // decode outputs are bf16 instead of fp32
     bool profiling = false;
     std::vector<EventPair> events;             // pool, created on first enable
     size_t events_used = 0;
@@ -300,6 +302,7 @@ lt_status lt_reset(lt_ctx *ctx)
     if (ctx == nullptr) return LT_ERR_INVALID_ARG;
     for (Layer &l : ctx->layers) {
         l.total = 0;
+        l.total_b.clear();
         if (ctx->online) {                      // back to "full, no storage yet"
             l.k = l.v = nullptr;
             l.slot = -1;
@@ -571,14 +574,39 @@ lt_status lt_preselect_lazy(const uint8_t *is_lazy_samples, int32_t n_samples, i
 
 // ---- decoding ------------------------------------------------------------------------------------
 
-lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new, void *stream)
+static lt_status append_impl(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new,
+                             const int64_t *n_per_seq, void *stream)
 {
     if (ctx == nullptr || k_new == nullptr || v_new == nullptr || layer < 0 || layer >= ctx->cfg.n_layers || n_new <= 0)
         return LT_ERR_INVALID_ARG;
     if (((uintptr_t)k_new % 16) != 0 || ((uintptr_t)v_new % 16) != 0) return LT_ERR_INVALID_ARG;
     Layer &l = ctx->layers[layer];
+    const int32_t B = ctx->cfg.batch;
+    if (n_per_seq != nullptr) {
+        if (ctx->online) return LT_ERR_STATE;   // online identification works on whole batches of equal length
+        if (B > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
+        for (int b = 0; b < B; ++b)
+            if (n_per_seq[b] < 0 || n_per_seq[b] > n_new) return LT_ERR_INVALID_ARG;
+    }
+    const bool ragged = n_per_seq != nullptr || !l.total_b.empty();
+    if (ragged && B > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
     if (n_new > kMaxTokens || l.total + n_new > kMaxTokens) return LT_ERR_CAPACITY;
-    if (!l.lazy && l.total + n_new > l.capacity) return LT_ERR_CAPACITY;
+    int64_t longest_after = l.total + n_new;
+    if (ragged) {
+        longest_after = 0;
+        for (int b = 0; b < B; ++b) {
+            const int64_t before = l.total_b.empty() ? l.total : l.total_b[b];
+            longest_after = std::max(longest_after, before + (n_per_seq != nullptr ? n_per_seq[b] : n_new));
+        }
+    }
+    if (!l.lazy && longest_after > l.capacity) return LT_ERR_CAPACITY;
+    if (ragged && l.total_b.empty()) {
+        try {
+            l.total_b.assign((size_t)B, l.total);
+        } catch (const std::bad_alloc &) {
+            return LT_ERR_NOMEM;
+        }
+    }
     if (ctx->online && l.slot < 0) {
         const lt_status st = assign_full_slot(ctx, l);
         if (st != LT_OK) return st;             // every full-size slot is taken: truncate a layer first
@@ -593,15 +621,53 @@ lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void
         a.stride_b = a.stride_h * ctx->cfg.n_kv_heads;
         a.n_new = n_new;
         a.total_before = l.total;
-        a.batch = ctx->cfg.batch;
+        a.batch = B;
         a.n_kv_heads = ctx->cfg.n_kv_heads;
         a.is_lazy = l.lazy ? 1 : 0;
         a.w_sink = ctx->cfg.w_sink;
         a.w_recent = ctx->cfg.w_recent;
+        a.ragged = ragged ? 1 : 0;
+        if (ragged)
+            for (int b = 0; b < B; ++b) {
+                a.n_new_b[b] = n_per_seq != nullptr ? n_per_seq[b] : n_new;
+                a.total_before_b[b] = l.total_b[b];
+            }
         ScopedEvents ev(ctx, static_cast<hipStream_t>(stream), LT_KERNEL_APPEND);
         if (ltk::append(a, static_cast<hipStream_t>(stream)) != hipSuccess) return LT_ERR_HIP;
     }
-    l.total += n_new;
+    if (ragged)
+        for (int b = 0; b < B; ++b) l.total_b[b] += n_per_seq != nullptr ? n_per_seq[b] : n_new;
+    l.total = longest_after;
+    return LT_OK;
+}
+
+lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_new, void *stream)
+{
+    return append_impl(ctx, layer, k_new, v_new, n_new, nullptr, stream);
+}
+
+lt_status lt_append_kv_ragged(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_max,
+                              const int64_t *n_per_seq_host, void *stream)
+{
+    if (n_per_seq_host == nullptr) return LT_ERR_INVALID_ARG;
+    return append_impl(ctx, layer, k_new, v_new, n_max, n_per_seq_host, stream);
+}
+
+lt_status lt_seq_len(const lt_ctx *ctx, int32_t layer, int32_t sequence, int64_t *total_tokens, int64_t *stored_tokens)
+{
+    if (ctx == nullptr || layer < 0 || layer >= ctx->cfg.n_layers || sequence < 0 || sequence >= ctx->cfg.batch)
+        return LT_ERR_INVALID_ARG;
+    const Layer &l = ctx->layers[layer];
+    const int64_t total = l.total_b.empty() ? l.total : l.total_b[sequence];
+    if (total_tokens != nullptr) *total_tokens = total;
+    if (stored_tokens != nullptr) *stored_tokens = l.lazy ? std::min(total, window_of(&ctx->cfg)) : total;
+    return LT_OK;
+}
+
+lt_status lt_set_output_dtype(lt_ctx *ctx, lt_out_dtype dtype)
+{
+    if (ctx == nullptr || (dtype != LT_OUT_BF16 && dtype != LT_OUT_F32)) return LT_ERR_INVALID_ARG;
+    ctx->out_bf16 = dtype == LT_OUT_BF16;
     return LT_OK;
 }
 
@@ -614,7 +680,7 @@ static int64_t slot_of(const lt_config &c, const Layer &l, int64_t p)
 }
 
 // One launch: optional on-the-fly append of this step's token, split attention, merge.
-static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out,
+static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
                                float *lse_out, void *stream)
 {
     if (ctx == nullptr || q == nullptr || out == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
@@ -626,6 +692,8 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     const int64_t total = l.total + (fused ? 1 : 0);
     const int64_t stored = std::min(total, l.capacity);
     if (stored <= 0) return LT_ERR_STATE;
+    const bool ragged = !l.total_b.empty();
+    if (ragged && c.batch > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
 
     ltk::DecodeArgs a{};
     a.k_cache = l.k;
@@ -652,6 +720,14 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     if (a.n_splits > ctx->splits_cap) return LT_ERR_CAPACITY;
     a.scale_log2e = c.softmax_scale * kLog2e;
     a.lazy_tag = l.lazy ? 1 : 0;
+    a.out_bf16 = ctx->out_bf16 ? 1 : 0;
+    a.ragged = ragged ? 1 : 0;
+    if (ragged)
+        for (int b = 0; b < c.batch; ++b) {
+            const int64_t total_b = l.total_b[b] + (fused ? 1 : 0);
+            a.stored_b[b] = (int32_t)std::min(total_b, l.capacity);
+            a.new_slot_b[b] = fused ? (int32_t)slot_of(c, l, l.total_b[b]) : -1;
+        }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ctx->tickets_ready) {
         if (ltk::zero_tickets(ctx->tickets, c.batch * c.n_kv_heads * ltk::kTicketStride, s) != hipSuccess) return LT_ERR_HIP;
@@ -662,15 +738,17 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
         if (ltk::decode(a, s) != hipSuccess) return LT_ERR_HIP;
     }
     l.total = total;
+    if (ragged && fused)
+        for (int b = 0; b < c.batch; ++b) l.total_b[b] += 1;
     return LT_OK;
 }
 
-lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, float *out, float *lse_out, void *stream)
+lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, void *out, float *lse_out, void *stream)
 {
     return launch_decode(ctx, layer, q, nullptr, nullptr, out, lse_out, stream);
 }
 
-lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, float *out,
+lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
                          float *lse_out, void *stream)
 {
     if (k_new == nullptr || v_new == nullptr) return LT_ERR_INVALID_ARG;

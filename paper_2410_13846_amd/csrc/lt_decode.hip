@@ -55,17 +55,19 @@ __device__ __forceinline__ float observe(const float *p) { return __hip_atomic_l
 // ---------------------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
 {
-    const int64_t per_stream = a.n_new * 16;                       // uint4 units per (b, g)
+    const int g = blockIdx.y, b = blockIdx.z;
+    const int64_t n_new = a.ragged ? a.n_new_b[b] : a.n_new;       // tokens this sequence brings
+    const int64_t total_before = a.ragged ? a.total_before_b[b] : a.total_before;
+    const int64_t per_stream = n_new * 16;                         // uint4 units per (b, g)
     const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (idx >= per_stream) return;
-    const int g = blockIdx.y, b = blockIdx.z;
     const int64_t j = idx >> 4;
     const int c = (int)(idx & 15);
-    const int64_t p = a.total_before + j;                          // absolute position of the token
+    const int64_t p = total_before + j;                            // absolute position of the token
     int64_t slot = p;
     if (a.is_lazy) {
         if (p >= a.w_sink) {
-            const int64_t total_after = a.total_before + a.n_new;
+            const int64_t total_after = total_before + n_new;
             if (a.w_recent == 0 || p < total_after - a.w_recent) return;   // a later token of this call owns the slot
             slot = a.w_sink + (p - a.w_sink) % a.w_recent;
         }
@@ -313,6 +315,13 @@ __device__ __forceinline__ void process_tile(const Tile &t, const uint32_t (&qf)
 // per workgroup: four when a workgroup has a long range to stream (memory-bound: more wavefronts
 // per compute unit only lower the bandwidth), eight when the range is short and the launch is
 // bound by how fast one wavefront gets through its tiles.
+// Final output element: fp32, or bf16 (round to nearest even) when the caller asked for it.
+__device__ __forceinline__ void store_out(const DecodeArgs &a, int64_t index, float value)
+{
+    if (a.out_bf16) reinterpret_cast<__bf16 *>(a.out)[index] = (__bf16)value;
+    else reinterpret_cast<float *>(a.out)[index] = value;
+}
+
 template <int G, int LAZY_TAG, int kWaves>
 __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
 {
@@ -329,13 +338,17 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: tile indices stay in SGPRs
     const int sub = lane >> 4, chunk = lane & 15;
 
+    // in a ragged batch a sequence may end before this workgroup's range: then the range is empty and
+    // the workgroup contributes an empty partial result
+    const int stored = a.ragged ? a.stored_b[b] : a.stored;
     const int begin_key = split * a.keys_per_block;
-    const int end_key = min(a.stored, begin_key + a.keys_per_block);
-    const int n_tiles = (end_key - begin_key + 15) >> 4;
+    const int end_key = min(stored, begin_key + a.keys_per_block);
+    const int n_tiles = max((end_key - begin_key + 15) >> 4, 0);
+    const int wrap = max(n_tiles, 1);
     uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     // fused append: the one tile that holds new_slot takes the token from k_new / v_new
-    const int new_slot = a.k_new != nullptr ? a.new_slot : -1;
+    const int new_slot = a.k_new != nullptr ? (a.ragged ? a.new_slot_b[b] : a.new_slot) : -1;
     const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
@@ -373,14 +386,14 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
     // matter to the result, so each workgroup starts at its own pseudo-random tile of its range
     // and wraps around.
     const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    const int phase = (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)n_tiles);
+    const int phase = (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     int next_tile = wave + phase, fetched = 0;
-    while (next_tile >= n_tiles) next_tile -= n_tiles;
+    while (next_tile >= wrap) next_tile -= wrap;
     auto advance = [&]() {                                          // first key of the next tile to fetch, -1 past the last
         const int cur = next_tile;
         next_tile += kWaves;
-        while (next_tile >= n_tiles) next_tile -= n_tiles;
+        while (next_tile >= wrap) next_tile -= wrap;
         return fetched++ < my_tiles ? begin_key + 16 * cur : -1;
     };
     Tile t0, t1;
@@ -447,7 +460,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
         }
         const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
         if (single) {
-            a.out[head * kHeadDim + dim] = o / l;
+            store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);                  // a sequence without tokens gives 0
             if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
         } else {
             const int64_t row = head * a.n_splits + split;
@@ -511,13 +524,13 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
 #pragma unroll
             for (int u = 0; u < 8; ++u) {
                 if (c0 + u < a.n_splits) {
-                    const float wgt = fast_exp2(sh_merge_m[h][c0 + u] - mx);
+                    const float wgt = sh_merge_m[h][c0 + u] == -INFINITY ? 0.f : fast_exp2(sh_merge_m[h][c0 + u] - mx);
                     l += wgt * sh_merge_l[h][c0 + u];
                     o += wgt * v[u];
                 }
             }
         }
-        a.out[head * kHeadDim + dim] = o / l;
+        store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);
         if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
     }
     if (threadIdx.x == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch

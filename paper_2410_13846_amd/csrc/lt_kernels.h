@@ -14,6 +14,7 @@ constexpr int kWideBlockKeys = 2048;    // decode workgroups with at most this m
 constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
 constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head) is split into
 constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels
+constexpr int kMaxRaggedBatch = 64;    // sequences a launch can give their own lengths (the lengths travel as kernel arguments)
 constexpr int kScoreTileKeys = 64;     // keys staged in LDS per step of the scoring kernel
 
 struct AppendArgs {
@@ -23,6 +24,9 @@ struct AppendArgs {
     int64_t n_new, total_before;       // tokens in this call, tokens already in the layer
     int32_t batch, n_kv_heads;
     int32_t is_lazy, w_sink, w_recent;
+    // ragged batches: sequence b brings n_new_b[b] <= n_new tokens (rows beyond are padding) and holds total_before_b[b]
+    int32_t ragged;
+    int64_t n_new_b[kMaxRaggedBatch], total_before_b[kMaxRaggedBatch];
 };
 hipError_t append(const AppendArgs &a, hipStream_t stream);
 
@@ -43,7 +47,7 @@ struct DecodeArgs {
     const uint16_t *q;                 // [B][Hq][128]
     float *part_acc;                   // [B][Hq][S][128]  un-normalised partial outputs
     float *part_ml;                    // [B][Hq][S][2]    running max (log2 units) and sum
-    float *out;                        // [B][Hq][128]
+    void *out;                         // [B][Hq][128] fp32, or bf16 when out_bf16
     float *lse;                        // [B][Hq] or nullptr
     int64_t stride_b, stride_h;
     int32_t batch, n_q_heads, n_kv_heads;
@@ -51,6 +55,10 @@ struct DecodeArgs {
     int32_t keys_per_block, n_splits;
     float scale_log2e;                 // softmax_scale * log2(e)
     int32_t lazy_tag;                  // selects the kernel instantiation (name) only
+    int32_t out_bf16;                  // out holds bf16 instead of fp32
+    // ragged batches: per-sequence stored entries (<= stored, which sizes the grid) and new-token slots (-1: dropped)
+    int32_t ragged;
+    int32_t stored_b[kMaxRaggedBatch], new_slot_b[kMaxRaggedBatch];
 };
 hipError_t decode(const DecodeArgs &a, hipStream_t stream);
 hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream);

@@ -24,6 +24,7 @@ EXPORTS = [
     "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
+    "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype",
 ]
 
 
@@ -89,6 +90,12 @@ def load() -> ctypes.CDLL:
     lib.lt_select_lazy.restype = ctypes.c_int
     lib.lt_append_kv.argtypes = [vp, i32, vp, vp, i64, vp]
     lib.lt_append_kv.restype = ctypes.c_int
+    lib.lt_append_kv_ragged.argtypes = [vp, i32, vp, vp, i64, vp, vp]
+    lib.lt_append_kv_ragged.restype = ctypes.c_int
+    lib.lt_seq_len.argtypes = [vp, i32, i32, ctypes.POINTER(i64), ctypes.POINTER(i64)]
+    lib.lt_seq_len.restype = ctypes.c_int
+    lib.lt_set_output_dtype.argtypes = [vp, ctypes.c_int]
+    lib.lt_set_output_dtype.restype = ctypes.c_int
     lib.lt_decode_attn.argtypes = [vp, i32, vp, vp, vp, vp]
     lib.lt_decode_attn.restype = ctypes.c_int
     lib.lt_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
@@ -323,6 +330,7 @@ class Context:
                                self.workspace.data_ptr(), wsb, ctypes.byref(handle))
             _check(st, "lt_create")
         self._h = handle
+        self.out_dtype = torch.float32
 
     def truncate_layer(self, layer: int, stream=None):
         _check(load().lt_truncate_layer(self._h, int(layer), _stream_ptr(stream)), "lt_truncate_layer")
@@ -374,16 +382,41 @@ class Context:
         st = load().lt_append_kv(self._h, int(layer), kp, vp, int(k_new.shape[2]), _stream_ptr(stream))
         _check(st, "lt_append_kv")
 
+    def append_kv_ragged(self, layer: int, k_new: torch.Tensor, v_new: torch.Tensor, lengths, stream=None):
+        """k_new / v_new: bf16 [B,Hkv,n_max,128] (padded); lengths: B token counts, each in 0..n_max."""
+        kp, vp = _dev_ptr(k_new, torch.bfloat16, "k_new"), _dev_ptr(v_new, torch.bfloat16, "v_new")
+        expect = (self.cfg.batch, self.cfg.n_kv_heads, k_new.shape[2] if k_new.dim() == 4 else -1, self.cfg.head_dim)
+        if tuple(k_new.shape) != expect or tuple(v_new.shape) != expect:
+            raise LtError(ERR_SHAPE, "lt_append_kv_ragged (k_new / v_new must be [B,Hkv,n_max,128])")
+        n = np.ascontiguousarray(np.asarray(lengths, dtype=np.int64))
+        if n.shape != (self.cfg.batch,):
+            raise LtError(ERR_SHAPE, "lt_append_kv_ragged (one length per sequence)")
+        st = load().lt_append_kv_ragged(self._h, int(layer), kp, vp, int(k_new.shape[2]), n.ctypes.data, _stream_ptr(stream))
+        _check(st, "lt_append_kv_ragged")
+
+    def seq_len(self, layer: int, sequence: int):
+        """(tokens appended, entries stored) of one sequence of a layer."""
+        total, stored = ctypes.c_int64(0), ctypes.c_int64(0)
+        _check(load().lt_seq_len(self._h, int(layer), int(sequence), ctypes.byref(total), ctypes.byref(stored)), "lt_seq_len")
+        return total.value, stored.value
+
+    def set_output_dtype(self, dtype):
+        """torch.float32 (default) or torch.bfloat16 for the `out` of decode_attn / decode_step."""
+        if dtype not in (torch.float32, torch.bfloat16):
+            raise TypeError("output dtype must be float32 or bfloat16")
+        _check(load().lt_set_output_dtype(self._h, OUT_F32 if dtype == torch.float32 else OUT_BF16), "lt_set_output_dtype")
+        self.out_dtype = dtype
+
     def decode_attn(self, layer: int, q: torch.Tensor, out: Optional[torch.Tensor] = None,
                     lse: Optional[torch.Tensor] = None, want_lse: bool = False, stream=None):
         qp = _dev_ptr(q, torch.bfloat16, "q")
         if tuple(q.shape) != (self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim):
             raise LtError(ERR_SHAPE, "lt_decode_attn (q must be [B,Hq,128])")
         if out is None:
-            out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=torch.float32, device=q.device)
+            out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.out_dtype, device=q.device)
         if lse is None and want_lse:
             lse = torch.empty((self.cfg.batch, self.cfg.n_q_heads), dtype=torch.float32, device=q.device)
-        st = load().lt_decode_attn(self._h, int(layer), qp, _dev_ptr(out, torch.float32, "out"),
+        st = load().lt_decode_attn(self._h, int(layer), qp, _dev_ptr(out, self.out_dtype, "out"),
                                    _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
         _check(st, "lt_decode_attn")
         return (out, lse) if (want_lse or lse is not None) else out
@@ -398,10 +431,10 @@ class Context:
         if k_new.numel() != self.cfg.batch * self.cfg.n_kv_heads * self.cfg.head_dim or v_new.numel() != k_new.numel():
             raise LtError(ERR_SHAPE, "lt_decode_step (k_new / v_new must hold one token: [B,Hkv,128])")
         if out is None:
-            out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=torch.float32, device=q.device)
+            out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.out_dtype, device=q.device)
         if lse is None and want_lse:
             lse = torch.empty((self.cfg.batch, self.cfg.n_q_heads), dtype=torch.float32, device=q.device)
-        st = load().lt_decode_step(self._h, int(layer), qp, kp, vp, _dev_ptr(out, torch.float32, "out"),
+        st = load().lt_decode_step(self._h, int(layer), qp, kp, vp, _dev_ptr(out, self.out_dtype, "out"),
                                    _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
         _check(st, "lt_decode_step")
         return (out, lse) if (want_lse or lse is not None) else out
