@@ -43,6 +43,8 @@ def parse_args():
     ap.add_argument("--no-profile-pass", action="store_true", help="skip the second pass that times kernels with HIP events")
     ap.add_argument("--prefill", action="store_true",
                     help="time lt_prefill_attn (causal and streaming masks) and lt_lazy_ratio_lse on layers of the workload")
+    ap.add_argument("--grid", action="store_true",
+                    help="decode and scoring times over the paper's ablation grid of w_recent, w_sink and w_last (Table 7)")
     ap.add_argument("--scoring-only", action="store_true", help="run and report only the lazy-ratio scoring of every layer")
     ap.add_argument("--online", action="store_true",
                     help="set the stack up the paper's way: prefill layer by layer, score each layer from its cache, push "
@@ -341,6 +343,55 @@ def prefill_bench(args, lt, W, wl, dev):
             "kv_heads": wl.n_kv_heads, "context": n, "w_sink": wl.w_sink, "w_recent": wl.w_recent, "w_last": w}, "layers": rows}
 
 
+def window_grid(args, lt, W, wl, dev):
+    """The ablation grid of Table 7 as a cost sweep: decode time per step of the hybrid stack (planted mask) for every
+    w_recent at w_sink = 4 and every w_sink at w_recent = 1020, and scoring time of one layer for every w_last."""
+    import numpy as np
+    import torch
+    K = min(args.steps, 32)
+    is_lazy = [1 if l in W.planted_lazy_layers(wl) else 0 for l in range(wl.n_layers)]
+    points = [(4, wr) for wr in (252, 508, 1020, 2044)] + [(ws, 1020) for ws in (0, 2, 6)]
+    decode = []
+    for ws, wr in points:
+        w = wl.scaled(w_sink=ws, w_recent=wr, bias="none")
+        stack = Stack(lt, W, w, is_lazy, 2 * K + 4, dev)
+        stack.run(4)
+        elapsed = timed(stack, K)
+        stack.ctx.profile_enable(True)
+        timed(stack, K)
+        stack.ctx.profile_enable(False)
+        n_lazy_launches, lazy_ms = stack.ctx.profile_read(lt.KERNEL_DECODE_LAZY)
+        nbytes = W.kv_bytes_per_step(w, is_lazy, stack.tokens_now())
+        decode.append({"w_sink": ws, "w_recent": wr, "ms_per_step": elapsed / K * 1e3, "tokens_per_s": w.batch * K / elapsed,
+                       "kv_gbs": nbytes / (elapsed / K) / 1e9, "lazy_launch_us": lazy_ms / max(n_lazy_launches, 1) * 1e3})
+        log("w_sink %d w_recent %4d: %.3f ms/step, %.0f tokens/s, lazy launch %.1f us" % (
+            ws, wr, elapsed / K * 1e3, w.batch * K / elapsed, decode[-1]["lazy_launch_us"]))
+        stack.close()
+        del stack
+        torch.cuda.empty_cache()
+    scoring = []
+    layer = W.planted_lazy_layers(wl)[0]
+    k, _ = W.prefill_kv(wl, layer, dev)
+    for w_last in (8, 16, 32, 64):
+        cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink, wl.w_recent, wl.context)
+        q_last = W.last_queries(wl, layer, dev, w_last)
+        ws_buf = torch.empty(max(lt.lazy_ratio_workspace_bytes(cfg, wl.context, w_last), 256), dtype=torch.uint8, device=dev)
+        lt.lazy_ratio(cfg, q_last, k, wl.context, w_last, workspace=ws_buf)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            mean, _, _ = lt.lazy_ratio(cfg, q_last, k, wl.context, w_last, workspace=ws_buf)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1) / 10
+        scoring.append({"w_last": w_last, "ms_per_layer": ms, "ratio": float(mean.cpu()[0])})
+        log("w_last %2d: %.3f ms per layer, r = %.4f" % (w_last, ms, scoring[-1]["ratio"]))
+    return {"metric": "decode ms/step and scoring ms/layer over the window grid", "n_gpus": 1, "steps": K, "data": "synthetic",
+            "config": {"workload": wl.name, "layers": wl.n_layers, "lazy_layers": int(sum(is_lazy)), "batch": wl.batch,
+                       "context": wl.context}, "decode": decode, "scoring": scoring}
+
+
 def main():
     args = parse_args()
     if args.gpus != 1:
@@ -378,6 +429,9 @@ def main():
         return 0
     if args.prefill:
         print(json.dumps(prefill_bench(args, lt, W, wl, dev)))
+        return 0
+    if args.grid:
+        print(json.dumps(window_grid(args, lt, W, wl, dev)))
         return 0
 
     # ---- identification: score every layer, select ------------------------------------------------
