@@ -167,3 +167,45 @@ def test_llama31_8b_128k_batch_16_one_full_layer():
     lazy_layers = W.planted_lazy_layers(wl)
     full_layer = [l for l in range(wl.n_layers) if l not in lazy_layers][0]
     run_sampled(wl, [full_layer], [0], samples=[(0, 15), (0, 8)], steps=1)
+
+
+def test_llama3_8b_32k_prefill_and_ratio_from_lse_sampled():
+    """Prefill attention of one planted-lazy layer at batch 8, 32/8 heads, n = 32768 in the launch configuration
+    bench.py --prefill times: sampled rows against the oracle's decode of the truncated history (prefill row p ==
+    decoding token p over keys 0..p), properties of every row, and the lazy ratio taken from that log-sum-exp."""
+    wl = W.WORKLOADS["llama3_8b_32k"]
+    layer = W.planted_lazy_layers(wl)[0]
+    cfg = make_cfg(wl)
+    n, w = wl.context, wl.w_last
+    q = W.prefill_queries(wl, layer, DEV)
+    k, v = W.prefill_kv(wl, layer, DEV)
+    say(wl.name, "prefill layer", layer, "causal")
+    out, lse = lt.prefill_attn(cfg, q, k, v, n, out_dtype=torch.float32)
+    say(wl.name, "prefill layer", layer, "streaming")
+    out_s, lse_s = lt.prefill_attn(cfg, q, k, v, n, lt.MASK_STREAMING, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    for o, l in ((out, lse), (out_s, lse_s)):
+        assert torch.isfinite(o).all() and torch.isfinite(l).all()
+        assert o.abs().max().item() <= 8.0
+    assert (lse_s <= lse + 1e-4).all()                                   # a subset of the keys
+    window = wl.w_sink + wl.w_recent
+    assert torch.equal(out[:, :, :window], out_s[:, :, :window])         # the window still covers the whole history
+    eps = 2.0 ** -8
+    for b, p in [(0, 0), (1, 31), (2, 32), (3, 63), (4, 64), (5, 2047), (5, 2048), (6, 20000), (7, n - 1)]:
+        K, V = bits(k[b:b + 1, :, :p + 1].contiguous()), bits(v[b:b + 1, :, :p + 1].contiguous())
+        qp = bits(q[b:b + 1, :, p].contiguous())
+        for mode, o, l in ((oracle.MODE_FULL, out, lse), (oracle.MODE_LAZY, out_s, lse_s)):
+            ref, ref_lse, probs = oracle.decode_attn(qp, K, V, mode, wl.w_sink, wl.w_recent, return_probs=True)
+            absw = np.einsum("bht,bhtd->bhd", probs, np.abs(oracle.bf16_bits_to_f64(np.repeat(V, wl.group, axis=1))))
+            err = np.abs(f64(o[b:b + 1, :, p]) - ref)
+            say(wl.name, "prefill row b", b, "p", p, "lazy" if mode else "full", "err", err.max())
+            assert (err <= eps * absw + 2e-5).all()
+            assert np.abs(f64(l[b:b + 1, :, p]) - ref_lse).max() <= 1e-4
+    q_last = q[:, :, n - w:].contiguous()
+    mean, seq, rho = lt.lazy_ratio_lse(cfg, q_last, k, n, w, lse[:, :, n - w:], want_rho=True)
+    mean_d, seq_d, rho_d = lt.lazy_ratio(cfg, q_last, k, n, w, want_rho=True)
+    assert (rho - rho_d).abs().max().item() <= TOL_RATIO and abs(float(mean.cpu()[0]) - float(mean_d.cpu()[0])) <= TOL_RATIO
+    for b, g in [(2, 1), (6, 7)]:
+        G = wl.group
+        ref_rho, _, _ = oracle.lazy_ratio(bits(q_last[b:b + 1, g * G:(g + 1) * G]), bits(k[b:b + 1, g:g + 1]), wl.w_sink, wl.w_recent)
+        assert np.abs(f64(rho)[b, g * G:(g + 1) * G] - ref_rho[0]).max() <= TOL_RATIO
