@@ -398,17 +398,17 @@ hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-// Eight wavefronts per workgroup where the group size allows: two per SIMD, so that one's matrix
-// instructions overlap the other's exponentials; each takes 32 queries.
+// Up to twelve wavefronts per workgroup (three per SIMD, 168 registers each), so that one's matrix
+// instructions overlap the others' exponentials; each takes 32 queries.
 hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream)
 {
     switch (a.n_q_heads / a.n_kv_heads) {
-    case 1: return launch_prefill<1, 8, 1>(a, stream);
-    case 2: return launch_prefill<2, 4, 1>(a, stream);
-    case 3: return launch_prefill<3, 2, 1>(a, stream);
-    case 4: return launch_prefill<4, 2, 1>(a, stream);
-    case 5: return launch_prefill<5, 1, 1>(a, stream);
-    case 6: return launch_prefill<6, 1, 1>(a, stream);
+    case 1: return launch_prefill<1, 12, 1>(a, stream);
+    case 2: return launch_prefill<2, 6, 1>(a, stream);
+    case 3: return launch_prefill<3, 4, 1>(a, stream);
+    case 4: return launch_prefill<4, 3, 1>(a, stream);
+    case 5: return launch_prefill<5, 2, 1>(a, stream);
+    case 6: return launch_prefill<6, 2, 1>(a, stream);
     case 7: return launch_prefill<7, 1, 1>(a, stream);
     case 8: return launch_prefill<8, 1, 1>(a, stream);
     default: return hipErrorInvalidValue;
