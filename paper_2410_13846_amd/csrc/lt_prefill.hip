@@ -199,8 +199,8 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     const int win_sink = a.streaming ? a.w_sink : 0x3fffffff;       // causal attention: every key counts as "initial"
 
     // S^T of one 32-key sub-tile for this wavefront's queries, masked, and the sub-tile maximum of
-    // every query column in log2 units (both halves of a column agree on it)
-    auto logits = [&](floatx16_t (&c)[NT], float (&tmax)[NT], const uint16_t *tile_k, int kt, int64_t j0) {
+    // every query column in log2 units (of the lane's 16 keys, or of all 32 when `agree`)
+    auto logits = [&](floatx16_t (&c)[NT], float (&tmax)[NT], const uint16_t *tile_k, int kt, int64_t j0, bool agree) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -238,7 +238,8 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
             float t = c[nt][0];
 #pragma unroll
             for (int i = 1; i < 16; ++i) t = fmaxf(t, c[nt][i]);
-            tmax[nt] = max_halves(t) * a.scale_log2e;
+            // the two lanes of a column must agree on the maximum only where it becomes the reference
+            tmax[nt] = (agree ? max_halves(t) : t) * a.scale_log2e;
         }
     };
 
@@ -302,7 +303,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         if (dead(j0)) return;
         floatx16_t c[NT];
         float tmax[NT];
-        logits(c, tmax, sh_k[t & 1], kt, j0);
+        logits(c, tmax, sh_k[t & 1], kt, j0, true);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             const bool grow = tmax[nt] > m_ref[nt] + kRescaleStep;
@@ -323,7 +324,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         if (dead(j0)) return true;
         floatx16_t c[NT];
         float tmax[NT];
-        logits(c, tmax, sh_k[t & 1], kt, j0);
+        logits(c, tmax, sh_k[t & 1], kt, j0, false);
         bool grow = false;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) grow = grow || tmax[nt] > m_ref[nt] + kRescaleStep;
