@@ -138,6 +138,70 @@ def test_lazy_ratio_argument_validation():
     assert call(ws=need - 1) == lt.ERR_CAPACITY
 
 
+def test_prefill_and_ratio_from_lse_argument_validation():
+    """Error paths of lt_prefill_attn / lt_lazy_ratio_lse that return before anything is enqueued."""
+    lib, c = lt.load(), cfg()
+
+    def prefill(q=FAKE_DEV, k=FAKE_DEV, v=FAKE_DEV, out=FAKE_DEV, n=500, mask=0, dtype=0, sb=500 * 128 * 2, sh=500 * 128, st=128, conf=c):
+        return lib.lt_prefill_attn(ctypes.byref(conf), q, k, v, sb, sh, st, n, mask, dtype, out, None, None)
+
+    assert prefill(q=None) == lt.ERR_INVALID_ARG
+    assert prefill(out=None) == lt.ERR_INVALID_ARG
+    assert prefill(n=0) == lt.ERR_INVALID_ARG
+    assert prefill(mask=2) == lt.ERR_INVALID_ARG
+    assert prefill(dtype=5) == lt.ERR_INVALID_ARG
+    assert prefill(k=FAKE_DEV + 2) == lt.ERR_INVALID_ARG
+    assert prefill(st=64) == lt.ERR_SHAPE
+    assert prefill(st=1 << 24) == lt.ERR_SHAPE
+    assert prefill(sh=500 * 128 + 4) == lt.ERR_SHAPE
+    empty = lt.make_config(4, 2, 4, 2, 128, 0, 0, 1000)
+    assert prefill(mask=1, conf=empty) == lt.ERR_SHAPE          # streaming attention with an empty window
+
+    need = lt.lazy_ratio_lse_workspace_bytes(c, 500, 16)
+    assert need > 0
+    assert lt.lazy_ratio_lse_workspace_bytes(c, 500, 65) == 0
+    assert lt.lazy_ratio_lse_workspace_bytes(c, 8, 16) == 0
+
+    def ratio(n=500, w=16, mode=0, ws=need, lse=FAKE_DEV, lsb=4 * 500, lsh=500):
+        return lib.lt_lazy_ratio_lse(ctypes.byref(c), FAKE_DEV, FAKE_DEV, 500 * 128 * 2, 500 * 128, 128, n, w, mode, lse, lsb, lsh,
+                                     FAKE_DEV, ws, None, None, FAKE_DEV, None)
+
+    assert ratio(lse=None) == lt.ERR_INVALID_ARG
+    assert ratio(lse=FAKE_DEV + 2) == lt.ERR_INVALID_ARG
+    assert ratio(lsb=-1) == lt.ERR_INVALID_ARG
+    assert ratio(mode=2) == lt.ERR_INVALID_ARG
+    assert ratio(n=8, w=16) == lt.ERR_SHAPE
+    assert ratio(ws=need - 1) == lt.ERR_CAPACITY
+    # the window-only form needs less workspace than the dense form on a long prompt
+    long_cfg = lt.make_config(1, 8, 32, 8, 128, 4, 2044, 32768)
+    assert lt.lazy_ratio_lse_workspace_bytes(long_cfg, 32768, 64) <= lt.lazy_ratio_workspace_bytes(long_cfg, 32768, 64)
+
+
+def test_ragged_and_output_dtype_argument_validation():
+    lib, c = lt.load(), cfg()
+    h = make_ctx(c, [0, 1, 0, 1])
+    counts = (ctypes.c_int64 * 2)(5, 3)
+    assert lib.lt_append_kv_ragged(h, 0, FAKE_DEV, FAKE_DEV, 5, None, None) == lt.ERR_INVALID_ARG
+    bad = (ctypes.c_int64 * 2)(6, 3)
+    assert lib.lt_append_kv_ragged(h, 0, FAKE_DEV, FAKE_DEV, 5, bad, None) == lt.ERR_INVALID_ARG
+    over = (ctypes.c_int64 * 2)(1001, 3)
+    assert lib.lt_append_kv_ragged(h, 0, FAKE_DEV, FAKE_DEV, 1001, over, None) == lt.ERR_CAPACITY
+    total, stored = ctypes.c_int64(-1), ctypes.c_int64(-1)
+    assert lib.lt_seq_len(h, 0, 1, ctypes.byref(total), ctypes.byref(stored)) == lt.OK
+    assert (total.value, stored.value) == (0, 0)
+    assert lib.lt_seq_len(h, 0, 2, ctypes.byref(total), ctypes.byref(stored)) == lt.ERR_INVALID_ARG
+    assert lib.lt_set_output_dtype(h, 7) == lt.ERR_INVALID_ARG
+    assert lib.lt_set_output_dtype(h, lt.OUT_BF16) == lt.OK
+    assert lib.lt_set_output_dtype(None, lt.OUT_BF16) == lt.ERR_INVALID_ARG
+    lib.lt_destroy(h)
+    wide = lt.make_config(1, 65, 4, 2, 128, 4, 60, 100)              # ragged lengths travel as launch arguments: at most 64 sequences
+    hw = make_ctx(wide, [0])
+    many = (ctypes.c_int64 * 65)(*([1] * 65))
+    assert lib.lt_append_kv_ragged(hw, 0, FAKE_DEV, FAKE_DEV, 1, many, None) == lt.ERR_SHAPE
+    lib.lt_destroy(hw)
+    del counts
+
+
 def test_select_lazy_matches_the_oracle_and_the_queue():
     rng = np.random.default_rng(7)
     for L in (1, 2, 32, 64):
