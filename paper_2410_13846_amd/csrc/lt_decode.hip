@@ -322,7 +322,7 @@ __device__ __forceinline__ void store_out(const DecodeArgs &a, int64_t index, fl
     else reinterpret_cast<float *>(a.out)[index] = value;
 }
 
-template <int G, int LAZY_TAG, int kWaves>
+template <int G, int LAZY_TAG, int kWaves, bool kRagged>
 __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
 {
     constexpr int kThreads = 64 * kWaves;
@@ -340,7 +340,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
 
     // in a ragged batch a sequence may end before this workgroup's range: then the range is empty and
     // the workgroup contributes an empty partial result
-    const int stored = a.ragged ? a.stored_b[b] : a.stored;
+    const int stored = kRagged ? a.stored_b[b] : a.stored;
     const int begin_key = split * a.keys_per_block;
     const int end_key = min(stored, begin_key + a.keys_per_block);
     const int n_tiles = max((end_key - begin_key + 15) >> 4, 0);
@@ -348,7 +348,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
     uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     // fused append: the one tile that holds new_slot takes the token from k_new / v_new
-    const int new_slot = a.k_new != nullptr ? (a.ragged ? a.new_slot_b[b] : a.new_slot) : -1;
+    const int new_slot = a.k_new != nullptr ? (kRagged ? a.new_slot_b[b] : a.new_slot) : -1;
     const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
@@ -542,19 +542,23 @@ __global__ void lt_zero_tickets_kernel(unsigned int *tickets, int n)
     if (i < n) tickets[i] = 0u;
 }
 
+template <int G, int LAZY_TAG, bool kRagged>
+hipError_t launch_decode_as(const DecodeArgs &a, hipStream_t stream)
+{
+    const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
+    if (a.keys_per_block <= kWideBlockKeys)                         // short ranges: eight wavefronts per workgroup
+        hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kRagged>), grid, dim3(512), 0, stream, a);
+    else
+        hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, kRagged>), grid, dim3(256), 0, stream, a);
+    return hipGetLastError();
+}
+
+// The instantiation for equal-length batches never looks at the per-sequence arrays.
 template <int G>
 hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
 {
-    const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
-    const bool wide = a.keys_per_block <= kWideBlockKeys;          // short ranges: eight wavefronts per workgroup
-    if (a.lazy_tag) {
-        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, 1, 8>), grid, dim3(512), 0, stream, a);
-        else hipLaunchKernelGGL((lt_decode_kernel<G, 1, 4>), grid, dim3(256), 0, stream, a);
-    } else {
-        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, 0, 8>), grid, dim3(512), 0, stream, a);
-        else hipLaunchKernelGGL((lt_decode_kernel<G, 0, 4>), grid, dim3(256), 0, stream, a);
-    }
-    return hipGetLastError();
+    if (a.ragged) return a.lazy_tag ? launch_decode_as<G, 1, true>(a, stream) : launch_decode_as<G, 0, true>(a, stream);
+    return a.lazy_tag ? launch_decode_as<G, 1, false>(a, stream) : launch_decode_as<G, 0, false>(a, stream);
 }
 
 }  // namespace
