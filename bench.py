@@ -509,6 +509,25 @@ def main():
             "bytes_per_launch": launch_bytes, "ms_per_step_with_events": elapsed_p / K * 1e3, "kernels": per_kernel,
         }
         log("roofline pass: %d launches, %.1f us each, %.1f GB/s (%.1f%% of 8 TB/s)" % (launches, avg_ms * 1e3, achieved, achieved / 80))
+        # what a plain streaming read reaches on this device: 1 GiB inside the layer-0 cache (or all of it)
+        try:
+            probe_buf = stack.ctx.kv_slab[: min(stack.ctx.kv_slab.numel(), 1 << 30)]
+            sink = torch.zeros(256, dtype=torch.uint8, device=dev)
+            lt.probe_read(probe_buf, sink)
+            torch.cuda.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                lt.probe_read(probe_buf, sink)
+            e1.record()
+            torch.cuda.synchronize()
+            probe_gbs = probe_buf.numel() * 10 / e0.elapsed_time(e1) / 1e6
+            roofline["read_probe_gbs"] = probe_gbs
+            roofline["frac_of_read_probe"] = achieved / probe_gbs
+            log("plain streaming read of %.2f GB: %.0f GB/s; the decode kernel reaches %.1f%% of it" % (
+                probe_buf.numel() / 1e9, probe_gbs, 100 * achieved / probe_gbs))
+        except lt.LtError as e:                        # measurement aid only
+            log("read probe skipped: %s" % e)
 
     # ---- oracle on host cores --------------------------------------------------------------------------------
     cpu = None if args.no_cpu_baseline else cpu_baseline(W, wl, stack, [int(x) for x in is_lazy])

@@ -282,6 +282,14 @@ lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *
  * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
 lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
 
+/* Measurement aid: one launch that reads `bytes` of `buf_dev` (rounded down to a multiple of
+ * 16 KiB, and at least that) once, with the same kind of loads the decode kernel uses, and discards
+ * them; timed by the caller, it gives the read rate this device sustains, the practical ceiling of
+ * the decode kernels.
+ *   buf_dev   device, 16-byte aligned, at least `bytes` long
+ *   sink_dev  device, at least 256 bytes; practically never written */
+lt_status lt_probe_read(const void *buf_dev, size_t bytes, void *sink_dev, void *stream);
+
 enum { LT_KERNEL_DECODE_FULL = 0, LT_KERNEL_DECODE_LAZY = 1, LT_KERNEL_APPEND = 2, LT_KERNEL_COUNT = 3 };
 
 /* Bracket every later kernel launch of this context with a pair of HIP events on the launch

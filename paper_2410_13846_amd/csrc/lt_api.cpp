@@ -851,6 +851,14 @@ lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_pe
     return LT_OK;
 }
 
+lt_status lt_probe_read(const void *buf_dev, size_t bytes, void *sink_dev, void *stream)
+{
+    if (buf_dev == nullptr || sink_dev == nullptr || bytes < 16 * 1024 || ((uintptr_t)buf_dev % 16) != 0 || ((uintptr_t)sink_dev % 4) != 0)
+        return LT_ERR_INVALID_ARG;
+    return ltk::probe_read(buf_dev, (int64_t)bytes, static_cast<uint32_t *>(sink_dev), static_cast<hipStream_t>(stream)) == hipSuccess
+               ? LT_OK : LT_ERR_HIP;
+}
+
 lt_status lt_profile_enable(lt_ctx *ctx, int32_t on)
 {
     if (ctx == nullptr) return LT_ERR_INVALID_ARG;

@@ -594,6 +594,37 @@ hipError_t decode(const DecodeArgs &a, hipStream_t stream)
     }
 }
 
+namespace {
+// Plain streaming read of a buffer: every workgroup reads its own contiguous share with 16-byte
+// non-temporal loads, eight in flight per lane.  The read rate this device sustains, against which
+// the decode kernel's rate can be read.
+constexpr int kProbeBlocks = 1024;
+__global__ __launch_bounds__(256) void lt_probe_read_kernel(const u32x4_t *buf, int64_t per_block, uint32_t *sink)
+{
+    const u32x4_t *base = buf + (int64_t)blockIdx.x * per_block;
+    uint32_t acc = 0;
+    for (int64_t i = threadIdx.x; i < per_block; i += 256 * 8) {
+        u32x4_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            int64_t idx = i + u * 256;
+            idx = idx < per_block ? idx : per_block - 1;
+            v[u] = __builtin_nontemporal_load(base + idx);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u][0] ^ v[u][1] ^ v[u][2] ^ v[u][3];
+    }
+    if (acc == 0x9e3779b9u) sink[threadIdx.x & 63] = acc;          // keeps the loads; practically never taken
+}
+}  // namespace
+
+hipError_t probe_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t stream)
+{
+    const int64_t per_block = bytes / 16 / kProbeBlocks;            // the API layer asks for at least 16 bytes per workgroup
+    hipLaunchKernelGGL(lt_probe_read_kernel, dim3(kProbeBlocks), dim3(256), 0, stream, static_cast<const u32x4_t *>(buf), per_block, sink);
+    return hipGetLastError();
+}
+
 hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream)
 {
     hipLaunchKernelGGL(lt_zero_tickets_kernel, dim3((n + 255) / 256), dim3(256), 0, stream, tickets, n);

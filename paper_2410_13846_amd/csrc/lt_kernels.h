@@ -62,6 +62,7 @@ struct DecodeArgs {
 };
 hipError_t decode(const DecodeArgs &a, hipStream_t stream);
 hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream);
+hipError_t probe_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t stream);
 
 struct ScoreArgs {
     const uint16_t *q_last;            // [B][Hq][w][128]

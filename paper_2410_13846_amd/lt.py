@@ -24,7 +24,7 @@ EXPORTS = [
     "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
-    "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype",
+    "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
 ]
 
 
@@ -118,6 +118,8 @@ def load() -> ctypes.CDLL:
     lib.lt_create_online.restype = ctypes.c_int
     lib.lt_truncate_layer.argtypes = [vp, i32, vp]
     lib.lt_truncate_layer.restype = ctypes.c_int
+    lib.lt_probe_read.argtypes = [vp, sz, vp, vp]
+    lib.lt_probe_read.restype = ctypes.c_int
     lib.lt_status_str.argtypes = [ctypes.c_int]
     lib.lt_status_str.restype = ctypes.c_char_p
     _lib = lib
@@ -153,6 +155,13 @@ def _dev_ptr(t: Optional[torch.Tensor], dtype, what: str) -> Optional[int]:
 def _stream_ptr(stream) -> int:
     s = torch.cuda.current_stream() if stream is None else stream
     return s.cuda_stream
+
+
+def probe_read(buf: torch.Tensor, sink: torch.Tensor, stream=None) -> None:
+    """One streaming read of `buf` (any dtype, contiguous, device); `sink`: >= 256 bytes on the device."""
+    if not buf.is_cuda or not buf.is_contiguous() or not sink.is_cuda or sink.numel() * sink.element_size() < 256:
+        raise TypeError("buf and sink must be contiguous device tensors, sink of at least 256 bytes")
+    _check(load().lt_probe_read(buf.data_ptr(), buf.numel() * buf.element_size(), sink.data_ptr(), _stream_ptr(stream)), "lt_probe_read")
 
 
 def kv_bytes(cfg: Config, is_lazy) -> int:
