@@ -721,6 +721,11 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     a.scale_log2e = c.softmax_scale * kLog2e;
     a.lazy_tag = l.lazy ? 1 : 0;
     a.out_bf16 = ctx->out_bf16 ? 1 : 0;
+    // window over which the workgroups' start addresses are spread: the largest power of two of 4 KB tiles that
+    // fits a workgroup's key range, at most 4 MB; short ranges start at pseudo-random tiles instead
+    a.spread_tiles = 0;
+    for (uint32_t w = 1024; w >= 128; w >>= 1)
+        if ((int64_t)w * 16 <= a.keys_per_block) { a.spread_tiles = w; break; }
     a.ragged = ragged ? 1 : 0;
     if (ragged)
         for (int b = 0; b < c.batch; ++b) {

@@ -383,10 +383,18 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
     // Workgroups run in lockstep, and their ranges start at multiples of the same strides, so
     // without care they all hit the same few memory channels at the same moment (measured: 185
     // vs 162 us per launch depending on the cache capacity alone).  The order of keys does not
-    // matter to the result, so each workgroup starts at its own pseudo-random tile of its range
-    // and wraps around.
+    // matter to the result, so each workgroup starts at a tile of its own inside its range and
+    // wraps around.  The start tiles are chosen by absolute address (the memory channels are
+    // picked from the address bits): workgroup i of n starts where its address is i * window / n
+    // modulo a window of spread_tiles 4 KB tiles, so the n address streams, which advance at the
+    // same pace, stay evenly spread over that window (measured 5 % faster than pseudo-random
+    // starts, which remain for ranges shorter than any useful window).
     const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    const int phase = (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+    const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
+    const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)begin_key * kHeadDim)) >> 12);
+    const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
+    const int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
+                                     : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     int next_tile = wave + phase, fetched = 0;
     while (next_tile >= wrap) next_tile -= wrap;

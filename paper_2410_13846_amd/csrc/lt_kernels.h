@@ -56,6 +56,7 @@ struct DecodeArgs {
     float scale_log2e;                 // softmax_scale * log2(e)
     int32_t lazy_tag;                  // selects the kernel instantiation (name) only
     int32_t out_bf16;                  // out holds bf16 instead of fp32
+    uint32_t spread_tiles;             // window (4 KB tiles, a power of two) the workgroups' start addresses are spread over; 0: pseudo-random starts
     // ragged batches: per-sequence stored entries (<= stored, which sizes the grid) and new-token slots (-1: dropped)
     int32_t ragged;
     int32_t stored_b[kMaxRaggedBatch], new_slot_b[kMaxRaggedBatch];
