@@ -726,12 +726,12 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     a.spread_tiles = 0;
     for (uint32_t w = 1024; w >= 128; w >>= 1)
         if ((int64_t)w * 16 <= a.keys_per_block) { a.spread_tiles = w; break; }
-    a.ragged = ragged ? 1 : 0;
+    ltk::RaggedArgs per_seq;
     if (ragged)
         for (int b = 0; b < c.batch; ++b) {
             const int64_t total_b = l.total_b[b] + (fused ? 1 : 0);
-            a.stored_b[b] = (int32_t)std::min(total_b, l.capacity);
-            a.new_slot_b[b] = fused ? (int32_t)slot_of(c, l, l.total_b[b]) : -1;
+            per_seq.stored_b[b] = (int32_t)std::min(total_b, l.capacity);
+            per_seq.new_slot_b[b] = fused ? (int32_t)slot_of(c, l, l.total_b[b]) : -1;
         }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ctx->tickets_ready) {
@@ -740,7 +740,7 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     }
     {
         ScopedEvents ev(ctx, s, l.lazy ? LT_KERNEL_DECODE_LAZY : LT_KERNEL_DECODE_FULL);
-        if (ltk::decode(a, s) != hipSuccess) return LT_ERR_HIP;
+        if (ltk::decode(a, ragged ? &per_seq : nullptr, s) != hipSuccess) return LT_ERR_HIP;
     }
     l.total = total;
     if (ragged && fused)

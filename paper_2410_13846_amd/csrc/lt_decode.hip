@@ -8,6 +8,8 @@
 // once from HBM and applies it to all G query heads of that KV head.
 #include "lt_kernels.h"
 
+#include <type_traits>
+
 namespace ltk {
 namespace {
 
@@ -322,8 +324,9 @@ __device__ __forceinline__ void store_out(const DecodeArgs &a, int64_t index, fl
     else reinterpret_cast<float *>(a.out)[index] = value;
 }
 
+struct NoRaggedArgs {};
 template <int G, int LAZY_TAG, int kWaves, bool kRagged>
-__global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
+__global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, std::conditional_t<kRagged, RaggedArgs, NoRaggedArgs> r)
 {
     constexpr int kThreads = 64 * kWaves;
     __shared__ float sh_m[kWaves][G];
@@ -340,7 +343,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
 
     // in a ragged batch a sequence may end before this workgroup's range: then the range is empty and
     // the workgroup contributes an empty partial result
-    const int stored = kRagged ? a.stored_b[b] : a.stored;
+    int stored = a.stored;
+    if constexpr (kRagged) stored = r.stored_b[b];
     const int begin_key = split * a.keys_per_block;
     const int end_key = min(stored, begin_key + a.keys_per_block);
     const int n_tiles = max((end_key - begin_key + 15) >> 4, 0);
@@ -348,7 +352,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a)
     uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     // fused append: the one tile that holds new_slot takes the token from k_new / v_new
-    const int new_slot = a.k_new != nullptr ? (kRagged ? a.new_slot_b[b] : a.new_slot) : -1;
+    int new_slot = a.k_new != nullptr ? a.new_slot : -1;
+    if constexpr (kRagged) new_slot = a.k_new != nullptr ? r.new_slot_b[b] : -1;
     const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
@@ -551,22 +556,26 @@ __global__ void lt_zero_tickets_kernel(unsigned int *tickets, int n)
 }
 
 template <int G, int LAZY_TAG, bool kRagged>
-hipError_t launch_decode_as(const DecodeArgs &a, hipStream_t stream)
+hipError_t launch_decode_as(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
 {
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
-    if (a.keys_per_block <= kWideBlockKeys)                         // short ranges: eight wavefronts per workgroup
-        hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kRagged>), grid, dim3(512), 0, stream, a);
-    else
-        hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, kRagged>), grid, dim3(256), 0, stream, a);
+    const bool wide = a.keys_per_block <= kWideBlockKeys;           // short ranges: eight wavefronts per workgroup
+    if constexpr (kRagged) {
+        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, true>), grid, dim3(512), 0, stream, a, *ragged);
+        else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, true>), grid, dim3(256), 0, stream, a, *ragged);
+    } else {
+        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, false>), grid, dim3(512), 0, stream, a, NoRaggedArgs{});
+        else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, false>), grid, dim3(256), 0, stream, a, NoRaggedArgs{});
+    }
     return hipGetLastError();
 }
 
-// The instantiation for equal-length batches never looks at the per-sequence arrays.
 template <int G>
-hipError_t launch_decode(const DecodeArgs &a, hipStream_t stream)
+hipError_t launch_decode(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
 {
-    if (a.ragged) return a.lazy_tag ? launch_decode_as<G, 1, true>(a, stream) : launch_decode_as<G, 0, true>(a, stream);
-    return a.lazy_tag ? launch_decode_as<G, 1, false>(a, stream) : launch_decode_as<G, 0, false>(a, stream);
+    if (ragged != nullptr)
+        return a.lazy_tag ? launch_decode_as<G, 1, true>(a, ragged, stream) : launch_decode_as<G, 0, true>(a, ragged, stream);
+    return a.lazy_tag ? launch_decode_as<G, 1, false>(a, ragged, stream) : launch_decode_as<G, 0, false>(a, ragged, stream);
 }
 
 }  // namespace
@@ -587,17 +596,17 @@ hipError_t truncate(const TruncateArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t decode(const DecodeArgs &a, hipStream_t stream)
+hipError_t decode(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
 {
     switch (a.n_q_heads / a.n_kv_heads) {
-    case 1: return launch_decode<1>(a, stream);
-    case 2: return launch_decode<2>(a, stream);
-    case 3: return launch_decode<3>(a, stream);
-    case 4: return launch_decode<4>(a, stream);
-    case 5: return launch_decode<5>(a, stream);
-    case 6: return launch_decode<6>(a, stream);
-    case 7: return launch_decode<7>(a, stream);
-    case 8: return launch_decode<8>(a, stream);
+    case 1: return launch_decode<1>(a, ragged, stream);
+    case 2: return launch_decode<2>(a, ragged, stream);
+    case 3: return launch_decode<3>(a, ragged, stream);
+    case 4: return launch_decode<4>(a, ragged, stream);
+    case 5: return launch_decode<5>(a, ragged, stream);
+    case 6: return launch_decode<6>(a, ragged, stream);
+    case 7: return launch_decode<7>(a, ragged, stream);
+    case 8: return launch_decode<8>(a, ragged, stream);
     default: return hipErrorInvalidValue;
     }
 }

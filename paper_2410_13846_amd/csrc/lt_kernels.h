@@ -57,11 +57,13 @@ struct DecodeArgs {
     int32_t lazy_tag;                  // selects the kernel instantiation (name) only
     int32_t out_bf16;                  // out holds bf16 instead of fp32
     uint32_t spread_tiles;             // window (4 KB tiles, a power of two) the workgroups' start addresses are spread over; 0: pseudo-random starts
-    // ragged batches: per-sequence stored entries (<= stored, which sizes the grid) and new-token slots (-1: dropped)
-    int32_t ragged;
+};
+// ragged batches: per-sequence stored entries (<= stored, which sizes the grid) and new-token slots (-1: dropped);
+// a separate argument block, so that launches for equal-length batches do not carry it
+struct RaggedArgs {
     int32_t stored_b[kMaxRaggedBatch], new_slot_b[kMaxRaggedBatch];
 };
-hipError_t decode(const DecodeArgs &a, hipStream_t stream);
+hipError_t decode(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream);   // ragged == nullptr: equal lengths
 hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream);
 hipError_t probe_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t stream);
 
