@@ -72,10 +72,10 @@ struct Stage {
 // Rows past the end of the prompt are read from its last key (they are masked as non-causal).
 // The row offset inside a tile is a 32-bit product: the API keeps the token stride below 2^24.
 template <int W>
-__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int64_t j0, int64_t n)
+__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int j0, int n)
 {
-    const uint16_t *tile = base + j0 * stride_t;                         // uniform
-    const int last = (int)min(n - 1 - j0, (int64_t)(kTileKeys - 1));
+    const uint16_t *tile = base + (int64_t)j0 * stride_t;                // uniform
+    const int last = min(n - 1 - j0, kTileKeys - 1);
 #pragma unroll
     for (int i = 0; i < Stage<W>::kPieces; ++i) {
         int idx = threadIdx.x + i * Stage<W>::kThreads;
@@ -100,12 +100,12 @@ __device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kPiec
 // dim chunks fall on the same banks take key groups 32 keys apart, so that a write of 32 lanes covers all banks.
 // Slot of key j (0..63) in a V^T row: 16 (j / 16) + {0, 8, 4, 12}[(j % 16) / 4] + j % 4, i.e. within 16 keys the
 // order 0-3, 8-11, 4-7, 12-15: slots 8 h .. 8 h + 7 then hold keys 4 h + {0..3} and 8 + 4 h + {0..3}.
-__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base, int64_t stride_t, int64_t j0, int64_t n)
+__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base, int64_t stride_t, int j0, int n)
 {
     if (threadIdx.x >= 256) return;
     const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2);
-    const uint16_t *tile = base + j0 * stride_t;
-    const int last = (int)min(n - 1 - j0, (int64_t)(kTileKeys - 1));
+    const uint16_t *tile = base + (int64_t)j0 * stride_t;
+    const int last = min(n - 1 - j0, kTileKeys - 1);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
         const int row = min(4 * kg + r, last);
@@ -146,7 +146,10 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     // Workgroups that run at the same time on one XCD (linear index mod 8) work on neighbouring
     // query blocks of the same (sequence, KV head): they walk the same K/V tiles at the same pace
     // and share them in that XCD's L2.  Within a pair the long (late) query blocks go first.
-    const int n_qb = (int)((a.n + kBlockQueries - 1) / kBlockQueries);
+    // positions are 32-bit (the API keeps prompts below 2^30 tokens); a window longer than the prompt is the prompt
+    const int n = (int)a.n;
+    const int w_sink = min(a.w_sink, n), w_recent = min(a.w_recent, n);
+    const int n_qb = (n + kBlockQueries - 1) / kBlockQueries;
     const int64_t total = (int64_t)n_qb * a.n_kv_heads * a.batch;
     const int64_t per_xcd = (total + 7) / 8;
     const int64_t vid = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -154,19 +157,19 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     const int pair = (int)(vid / n_qb), qb = n_qb - 1 - (int)(vid % n_qb);
     const int b = pair / a.n_kv_heads, g = pair % a.n_kv_heads;
     const int h = g * G + wave % G;
-    const int64_t q_block = (int64_t)qb * kBlockQueries;
-    const int64_t q0 = q_block + (wave / G) * kWaveQueries;         // first query of this wavefront
+    const int q_block = qb * kBlockQueries;
+    const int q0 = q_block + (wave / G) * kWaveQueries;             // first query of this wavefront
 
     // key tiles the block needs: [0, n_a) and [t_b, t_last]
-    const int t_last = (int)(min(q_block + kBlockQueries, a.n) - 1) / kTileKeys;
+    const int t_last = (min(q_block + kBlockQueries, n) - 1) / kTileKeys;
     int n_a = 0, t_b = 0;
     if (a.streaming) {
-        n_a = min((a.w_sink + kTileKeys - 1) / kTileKeys, t_last + 1);
-        const int64_t first_recent = max(q_block - (int64_t)a.w_recent + 1, (int64_t)0);
-        t_b = max(n_a, (int)(first_recent / kTileKeys));
+        n_a = min((w_sink + kTileKeys - 1) / kTileKeys, t_last + 1);
+        const int first_recent = max(q_block - w_recent + 1, 0);
+        t_b = max(n_a, first_recent / kTileKeys);
     }
     const int n_tiles = n_a + (t_last + 1 - t_b);
-    auto tile_key = [&](int i) { return (int64_t)(i < n_a ? i : t_b + (i - n_a)) * kTileKeys; };
+    auto tile_key = [&](int i) { return (i < n_a ? i : t_b + (i - n_a)) * kTileKeys; };
 
     const uint16_t *kb = a.k + (int64_t)b * a.kv_stride_b + (int64_t)g * a.kv_stride_h;
     const uint16_t *vb = a.v + (int64_t)b * a.kv_stride_b + (int64_t)g * a.kv_stride_h;
@@ -175,11 +178,11 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     bf16x8_t qf[NT][8];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int64_t p = q0 + nt * 32 + col;
+        const int p = q0 + nt * 32 + col;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             u32x4_t u = {0u, 0u, 0u, 0u};
-            if (p < a.n)
+            if (p < n)
                 u = *reinterpret_cast<const u32x4_t *>(a.q + (((int64_t)b * a.n_q_heads + h) * a.n + p) * kHeadDim + 16 * s + 8 * half);
             qf[nt][s] = __builtin_bit_cast(bf16x8_t, u);
         }
@@ -196,11 +199,11 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { m_ref[nt] = -INFINITY; l_sum[nt] = 0.f; }
 
-    const int win_sink = a.streaming ? a.w_sink : 0x3fffffff;       // causal attention: every key counts as "initial"
+    const int win_sink = a.streaming ? w_sink : 0x7fffffff;       // causal attention: every key counts as "initial"
 
     // S^T of one 32-key sub-tile for this wavefront's queries, masked, and the sub-tile maximum of
     // every query column in log2 units (of the lane's 16 keys, or of all 32 when `agree`)
-    auto logits = [&](floatx16_t (&c)[NT], float (&tmax)[NT], const uint16_t *tile_k, int kt, int64_t j0, bool agree) {
+    auto logits = [&](floatx16_t (&c)[NT], float (&tmax)[NT], const uint16_t *tile_k, int kt, int j0, bool agree) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -218,16 +221,16 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         __builtin_amdgcn_s_setprio(0);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const int64_t p_min = q0 + nt * 32, p_max = p_min + 31;
+            const int p_min = q0 + nt * 32, p_max = p_min + 31;
             // every (key, query) pair of the sub-tile is attended: causal, and inside the initial tokens or
             // inside every query's recent window
-            const bool clear = (j0 + 31 <= p_min) && (!a.streaming || j0 + 31 < a.w_sink || j0 > p_max - a.w_recent);
+            const bool clear = (j0 + 31 <= p_min) && (!a.streaming || j0 + 31 < w_sink || j0 > p_max - w_recent);
             if (!clear) {
                 // positions relative to the sub-tile, clamped so that 32-bit compares decide
-                const int64_t p = p_min + col;
-                const int p_rel = (int)min(max(p - j0, (int64_t)-1), (int64_t)32);
-                const int sink_rel = (int)min(max((int64_t)win_sink - j0, (int64_t)0), (int64_t)32);
-                const int old_rel = (int)min(max(p - a.w_recent - j0, (int64_t)-1), (int64_t)32);   // last key before the window
+                const int p = p_min + col;
+                const int p_rel = min(max(p - j0, -1), 32);
+                const int sink_rel = min(max(win_sink - j0, 0), 32);
+                const int old_rel = min(max(p - w_recent - j0, -1), 32);   // last key before the window
 #pragma unroll
                 for (int i = 0; i < 16; ++i) {
                     const int j_rel = 8 * (i >> 2) + 4 * half + (i & 3);
@@ -278,15 +281,15 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 
     // nothing of the sub-tile is visible to this wavefront's queries: later than all of them, or,
     // for streaming attention, between the initial tokens and every query's window
-    auto dead = [&](int64_t j0) {
-        return j0 > q0 + kWaveQueries - 1 || (a.streaming && j0 >= a.w_sink && j0 + 31 <= q0 - a.w_recent);
+    auto dead = [&](int j0) {
+        return j0 > q0 + kWaveQueries - 1 || (a.streaming && j0 >= w_sink && j0 + 31 <= q0 - w_recent);
     };
 
     u32x4_t pre_k[kPieces], pre_v[4];
     auto prefetch = [&](int t) {
         if (t < n_tiles) {
-            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), a.n);
-            fetch_v(pre_v, vb, a.kv_stride_t, tile_key(t), a.n);
+            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), n);
+            fetch_v(pre_v, vb, a.kv_stride_t, tile_key(t), n);
         }
     };
     auto park = [&](int t) {                     // registers of tile t -> its LDS buffer, then everyone may read it
@@ -299,7 +302,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 
     // One sub-tile with the reference of every row moved first where its maximum has outgrown it.
     auto careful = [&](int t, int kt) {
-        const int64_t j0 = tile_key(t) + 32 * kt;
+        const int j0 = tile_key(t) + 32 * kt;
         if (dead(j0)) return;
         floatx16_t c[NT];
         float tmax[NT];
@@ -320,7 +323,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     // The same without touching the references: returns false, having changed nothing, when some
     // row's maximum has outgrown its reference.
     auto quick = [&](int t, int kt) {
-        const int64_t j0 = tile_key(t) + 32 * kt;
+        const int j0 = tile_key(t) + 32 * kt;
         if (dead(j0)) return true;
         floatx16_t c[NT];
         float tmax[NT];
@@ -363,9 +366,9 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     // normalise and store: a lane holds, for its query, dims 32 dt + 8 (i / 4) + 4 half + (i % 4)
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int64_t p = q0 + nt * 32 + col;
+        const int p = q0 + nt * 32 + col;
         const float l_tot = sum_halves(l_sum[nt]);
-        if (p >= a.n) continue;
+        if (p >= n) continue;
         const float inv = 1.f / l_tot;
         const int64_t row = ((int64_t)b * a.n_q_heads + h) * a.n + p;
         if (a.lse != nullptr && half == 0) a.lse[row] = (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
