@@ -559,7 +559,9 @@ template <int G, int LAZY_TAG, bool kRagged>
 hipError_t launch_decode_as(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
 {
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
-    const bool wide = a.keys_per_block <= kWideBlockKeys;           // short ranges: eight wavefronts per workgroup
+    // short ranges: eight wavefronts per workgroup; not for groups of eight heads, whose state needs more than
+    // the 256 registers a wavefront has when two share a SIMD
+    const bool wide = G < 8 && a.keys_per_block <= kWideBlockKeys;
     if constexpr (kRagged) {
         if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, true>), grid, dim3(512), 0, stream, a, *ragged);
         else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, true>), grid, dim3(256), 0, stream, a, *ragged);
