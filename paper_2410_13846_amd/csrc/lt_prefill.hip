@@ -268,11 +268,17 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         }
         // k slots 0..7 of a lane are keys 16 sp + 4 half + {0..3} and 16 sp + 8 + 4 half + {0..3}: the order the
         // logits sit in the accumulator registers 8 sp .. 8 sp + 7, and the order of the V^T slots
+        // The lane's offset into the V^T tile is rebuilt from the lane number here rather than kept in a register
+        // across the loop: with every register taken the compiler parks such a value in scratch memory, and the
+        // reload's wait would also wait for the next tile's global loads.
+        int lane_now;
+        asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(lane_now));
+        const uint16_t *v_rows = tile_v + (lane_now & 31) * kVtRow + 8 * (lane_now >> 5) + 32 * kt;
 #pragma unroll
         for (int sp = 0; sp < 2; ++sp)
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt) {
-                const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&tile_v[(32 * dt + col) * kVtRow + 32 * kt + 16 * sp + 8 * half]);
+                const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&v_rows[32 * dt * kVtRow + 16 * sp]);
                 const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, u);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) acc[dt][nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[nt][sp], acc[dt][nt], 0, 0, 0);
