@@ -312,7 +312,7 @@ class Context:
     With a lazy mask: lt_create.  With `n_full_online` instead: lt_create_online (layers take storage on
     demand and turn lazy through truncate_layer)."""
 
-    def __init__(self, cfg: Config, is_lazy=None, device="cuda:0", n_full_online: Optional[int] = None):
+    def __init__(self, cfg: Config, is_lazy=None, device="cuda:0", n_full_online: Optional[int] = None, guard_bytes: int = 0):
         lib = load()
         self.cfg = cfg
         online = n_full_online is not None
@@ -327,8 +327,15 @@ class Context:
         if kvb == 0 or wsb == 0:
             raise LtError(ERR_INVALID_ARG, "lt_kv_bytes / lt_workspace_bytes")
         self.device = torch.device(device)
-        self.kv_slab = torch.empty(kvb, dtype=torch.uint8, device=self.device)
-        self.workspace = torch.empty(wsb, dtype=torch.uint8, device=self.device)
+        # testing aid: `guard_bytes` (a multiple of 256) of a known pattern on both sides of the slab and the
+        # workspace; check_guards() tells whether anything wrote there
+        self._guard = int(guard_bytes)
+        if self._guard % 256:
+            raise ValueError("guard_bytes must be a multiple of 256")
+        self._slab_all = torch.full((kvb + 2 * self._guard,), 0xA5, dtype=torch.uint8, device=self.device)
+        self._ws_all = torch.full((wsb + 2 * self._guard,), 0xA5, dtype=torch.uint8, device=self.device)
+        self.kv_slab = self._slab_all[self._guard: self._guard + kvb]
+        self.workspace = self._ws_all[self._guard: self._guard + wsb]
         handle = ctypes.c_void_p()
         if online:
             st = lib.lt_create_online(ctypes.byref(cfg), int(n_full_online), self.kv_slab.data_ptr(), kvb,
@@ -340,6 +347,14 @@ class Context:
             _check(st, "lt_create")
         self._h = handle
         self.out_dtype = torch.float32
+
+    def check_guards(self) -> bool:
+        """True when the guard bands around the slab and the workspace still hold their pattern."""
+        g = self._guard
+        if g == 0:
+            return True
+        bands = (self._slab_all[:g], self._slab_all[-g:], self._ws_all[:g], self._ws_all[-g:])
+        return all(bool((b == 0xA5).all().item()) for b in bands)
 
     def truncate_layer(self, layer: int, stream=None):
         _check(load().lt_truncate_layer(self._h, int(layer), _stream_ptr(stream)), "lt_truncate_layer")
