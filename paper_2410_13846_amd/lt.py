@@ -332,8 +332,10 @@ class Context:
         self._guard = int(guard_bytes)
         if self._guard % 256:
             raise ValueError("guard_bytes must be a multiple of 256")
-        self._slab_all = torch.full((kvb + 2 * self._guard,), 0xA5, dtype=torch.uint8, device=self.device)
-        self._ws_all = torch.full((wsb + 2 * self._guard,), 0xA5, dtype=torch.uint8, device=self.device)
+        make = (lambda nbytes: torch.full((nbytes,), 0xA5, dtype=torch.uint8, device=self.device)) if self._guard else \
+            (lambda nbytes: torch.empty(nbytes, dtype=torch.uint8, device=self.device))
+        self._slab_all = make(kvb + 2 * self._guard)
+        self._ws_all = make(wsb + 2 * self._guard)
         self.kv_slab = self._slab_all[self._guard: self._guard + kvb]
         self.workspace = self._ws_all[self._guard: self._guard + wsb]
         handle = ctypes.c_void_p()
