@@ -209,3 +209,35 @@ def test_llama3_8b_32k_prefill_and_ratio_from_lse_sampled():
         G = wl.group
         ref_rho, _, _ = oracle.lazy_ratio(bits(q_last[b:b + 1, g * G:(g + 1) * G]), bits(k[b:b + 1, g:g + 1]), wl.w_sink, wl.w_recent)
         assert np.abs(f64(rho)[b, g * G:(g + 1) * G] - ref_rho[0]).max() <= TOL_RATIO
+
+
+def test_llama31_8b_128k_prefill_sampled():
+    """Prefill attention at n = 131072 (batch 1, 4 + 4092 window): row offsets pass 2^31 bytes; sampled rows of
+    both masks against the oracle's decode of the truncated history, and the ratio from the log-sum-exp."""
+    wl = W.WORKLOADS["llama31_8b_128k_b1"]
+    layer = W.planted_lazy_layers(wl)[0]
+    cfg = make_cfg(wl)
+    n, w = wl.context, wl.w_last
+    q = W.prefill_queries(wl, layer, DEV)
+    k, v = W.prefill_kv(wl, layer, DEV)
+    say(wl.name, "prefill layer", layer, "causal, n =", n)
+    out, lse = lt.prefill_attn(cfg, q, k, v, n, out_dtype=torch.float32)
+    say(wl.name, "prefill layer", layer, "streaming")
+    out_s, lse_s = lt.prefill_attn(cfg, q, k, v, n, lt.MASK_STREAMING, out_dtype=torch.float32)
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all() and torch.isfinite(out_s).all() and torch.isfinite(lse_s).all()
+    eps = 2.0 ** -8
+    for p in (0, 4095, 4096, 65535, 100001, n - 1):
+        K, V = bits(k[:, :, :p + 1].contiguous()), bits(v[:, :, :p + 1].contiguous())
+        qp = bits(q[:, :, p].contiguous())
+        for mode, o, l in ((oracle.MODE_FULL, out, lse), (oracle.MODE_LAZY, out_s, lse_s)):
+            ref, ref_lse, probs = oracle.decode_attn(qp, K, V, mode, wl.w_sink, wl.w_recent, return_probs=True)
+            absw = np.einsum("bht,bhtd->bhd", probs, np.abs(oracle.bf16_bits_to_f64(np.repeat(V, wl.group, axis=1))))
+            err = np.abs(f64(o[:, :, p]) - ref)
+            say(wl.name, "prefill row p", p, "lazy" if mode else "full", "err", err.max())
+            assert (err <= eps * absw + 2e-5).all()
+            assert np.abs(f64(l[:, :, p]) - ref_lse).max() <= 1e-4
+    q_last = q[:, :, n - w:].contiguous()
+    mean, _, rho = lt.lazy_ratio_lse(cfg, q_last, k, n, w, lse[:, :, n - w:], want_rho=True)
+    mean_d, _, rho_d = lt.lazy_ratio(cfg, q_last, k, n, w, want_rho=True)
+    assert (rho - rho_d).abs().max().item() <= TOL_RATIO and abs(float(mean.cpu()[0]) - float(mean_d.cpu()[0])) <= TOL_RATIO
