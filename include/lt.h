@@ -138,7 +138,8 @@ size_t lt_lazy_ratio_lse_workspace_bytes(const lt_config *cfg, int64_t n, int32_
  * cost does not grow with n.  Same result as lt_lazy_ratio when lse_rows holds the rows' true LSE.
  *   lse_rows      device, fp32: natural-log LSE (softmax_scale included) of the causal row of
  *                 (sequence b, head h, position n-w_last+t) at element b*lse_stride_b +
- *                 h*lse_stride_h + t; lt_prefill_attn's lse_out + (n - w_last) with strides Hq*n, n
+ *                 h*lse_stride_h + t; lt_prefill_attn's lse_out + (n_queries - w_last) with strides
+ *                 Hq*n_queries, n_queries
  *   workspace     device, >= lt_lazy_ratio_lse_workspace_bytes(cfg, n, w_last), 256-byte aligned
  * Every other argument, the outputs and the errors are those of lt_lazy_ratio. */
 lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b,
@@ -147,28 +148,31 @@ lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void
                             int64_t lse_stride_h, void *workspace, size_t ws_bytes, float *rho_dev,
                             float *ratio_seq_dev, float *ratio_mean_dev, void *stream);
 
-/* Prefill attention of one layer over a prompt of n tokens (Section "Preliminary", prefilling:
- * position p attends to positions 0..p; Appendix "Theoretical Analysis": softmax(Q K^T + M) V).
+/* Prefill attention of one layer (Section "Preliminary", prefilling: position p attends to
+ * positions 0..p; Appendix "Theoretical Analysis": softmax(Q K^T + M) V) for the last n_queries of
+ * n positions: n_queries = n is the prefill of a whole prompt, a smaller n_queries one chunk of a
+ * chunked prefill whose earlier keys and values are already in place.
  *   mask  LT_MASK_CAUSAL: M is the causal mask.  LT_MASK_STREAMING: the sink mask, position p
  *         attends to the first w_sink and the last w_recent positions of 0..p (p included), as a
  *         layer that runs streaming attention from the start does (LightTransfer-Train).
- *   q         device, bf16 [B][Hq][n][128]
- *   k, v      device, bf16; (sequence b, KV head g, position j) at element offset b*kv_stride_b +
- *             g*kv_stride_h + j*kv_stride_t of each; 128 dims contiguous, strides multiples of 8,
- *             128 <= kv_stride_t < 2^24
- *             (may point into the KV slab of a full layer after lt_append_kv of the prompt)
- *   out       device, [B][Hq][n][128], bf16 (LT_OUT_BF16) or fp32 (LT_OUT_F32)
- *   lse_out   device, fp32 [B][Hq][n]: natural log of each row's softmax denominator
+ *   q         device, bf16 [B][Hq][n_queries][128], the queries of positions n-n_queries .. n-1
+ *   k, v      device, bf16, positions 0 .. n-1; (sequence b, KV head g, position j) at element
+ *             offset b*kv_stride_b + g*kv_stride_h + j*kv_stride_t of each; 128 dims contiguous,
+ *             strides multiples of 8, 128 <= kv_stride_t < 2^24 (may point into the KV slab of a
+ *             full layer after lt_append_kv)
+ *   out       device, [B][Hq][n_queries][128], bf16 (LT_OUT_BF16) or fp32 (LT_OUT_F32)
+ *   lse_out   device, fp32 [B][Hq][n_queries]: natural log of each row's softmax denominator
  *             (softmax_scale included), may be NULL
  * Logits and sums are fp32; the probabilities enter the P V product rounded to bf16 (the values are
  * bf16 already), accumulation is fp32.  Uses cfg->batch, head counts, head_dim, w_sink, w_recent,
  * softmax_scale.  Nothing is allocated; the launch is asynchronous on `stream`.
- * Errors: LT_ERR_INVALID_ARG (NULL or misaligned pointers, bad enums, n <= 0), LT_ERR_SHAPE
- * (unsupported head shape or strides, streaming mask with an empty window). */
+ * Errors: LT_ERR_INVALID_ARG (NULL or misaligned pointers, bad enums, n or n_queries <= 0),
+ * LT_ERR_SHAPE (n_queries > n, unsupported head shape or strides, streaming mask with an empty
+ * window). */
 typedef enum lt_mask_mode { LT_MASK_CAUSAL = 0, LT_MASK_STREAMING = 1 } lt_mask_mode;
 typedef enum lt_out_dtype { LT_OUT_BF16 = 0, LT_OUT_F32 = 1 } lt_out_dtype;
 lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, const void *v,
-                          int64_t kv_stride_b, int64_t kv_stride_h, int64_t kv_stride_t, int64_t n,
+                          int64_t kv_stride_b, int64_t kv_stride_h, int64_t kv_stride_t, int64_t n, int64_t n_queries,
                           lt_mask_mode mask, lt_out_dtype out_dtype, void *out, float *lse_out, void *stream);
 
 /* Choose the lazy layers (pure host code): the n_lazy layers with the largest ratios, ties going

@@ -487,16 +487,16 @@ lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void
 // ---- prefill attention -------------------------------------------------------------------------
 
 lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, const void *v, int64_t kv_stride_b,
-                          int64_t kv_stride_h, int64_t kv_stride_t, int64_t n, lt_mask_mode mask, lt_out_dtype out_dtype,
-                          void *out, float *lse_out, void *stream)
+                          int64_t kv_stride_h, int64_t kv_stride_t, int64_t n, int64_t n_queries, lt_mask_mode mask,
+                          lt_out_dtype out_dtype, void *out, float *lse_out, void *stream)
 {
     if (!config_ok(cfg) || q == nullptr || k == nullptr || v == nullptr || out == nullptr) return LT_ERR_INVALID_ARG;
     if (mask != LT_MASK_CAUSAL && mask != LT_MASK_STREAMING) return LT_ERR_INVALID_ARG;
     if (out_dtype != LT_OUT_BF16 && out_dtype != LT_OUT_F32) return LT_ERR_INVALID_ARG;
-    if (n <= 0 || kv_stride_b < 0 || kv_stride_h < 0 || kv_stride_t <= 0) return LT_ERR_INVALID_ARG;
+    if (n <= 0 || n_queries <= 0 || kv_stride_b < 0 || kv_stride_h < 0 || kv_stride_t <= 0) return LT_ERR_INVALID_ARG;
     const lt_status shape = config_shape(cfg);
     if (shape != LT_OK) return shape;
-    if (n > kMaxTokens) return LT_ERR_SHAPE;
+    if (n > kMaxTokens || n_queries > n) return LT_ERR_SHAPE;
     if (mask == LT_MASK_STREAMING && cfg->w_sink + cfg->w_recent < 1) return LT_ERR_SHAPE;
     if (kv_stride_t < ltk::kHeadDim || kv_stride_t >= ((int64_t)1 << 24) || (kv_stride_b % 8) != 0 || (kv_stride_h % 8) != 0 ||
         (kv_stride_t % 8) != 0)
@@ -504,7 +504,7 @@ lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, co
     if (((uintptr_t)q % 16) != 0 || ((uintptr_t)k % 16) != 0 || ((uintptr_t)v % 16) != 0 || ((uintptr_t)out % 16) != 0 ||
         ((uintptr_t)lse_out % 4) != 0)
         return LT_ERR_INVALID_ARG;
-    const int64_t blocks = ceil_div(n, 32) * cfg->n_kv_heads * cfg->batch;     // upper bound of the grid
+    const int64_t blocks = ceil_div(n_queries, 32) * cfg->n_kv_heads * cfg->batch;     // upper bound of the grid
     if (blocks + 8 > (int64_t)0x7fffffff) return LT_ERR_SHAPE;
 
     ltk::PrefillArgs a{};
@@ -517,6 +517,7 @@ lt_status lt_prefill_attn(const lt_config *cfg, const void *q, const void *k, co
     a.out = out;
     a.lse = lse_out;
     a.n = n;
+    a.n_q = n_queries;
     a.batch = cfg->batch;
     a.n_q_heads = cfg->n_q_heads;
     a.n_kv_heads = cfg->n_kv_heads;

@@ -89,12 +89,12 @@ struct ScoreArgs {
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);
 
 struct PrefillArgs {
-    const uint16_t *q;                 // [B][Hq][n][128]
+    const uint16_t *q;                 // [B][Hq][n_q][128]: the queries of positions n - n_q .. n - 1
     const uint16_t *k, *v;             // [B][Hkv][n][128] through the strides below (elements)
     int64_t kv_stride_b, kv_stride_h, kv_stride_t;
-    void *out;                         // [B][Hq][n][128] bf16, or fp32 when out_f32
-    float *lse;                        // [B][Hq][n] natural-log row denominators, or nullptr
-    int64_t n;
+    void *out;                         // [B][Hq][n_q][128] bf16, or fp32 when out_f32
+    float *lse;                        // [B][Hq][n_q] natural-log row denominators, or nullptr
+    int64_t n, n_q;
     int32_t batch, n_q_heads, n_kv_heads;
     int32_t streaming, w_sink, w_recent;
     int32_t out_f32;

@@ -149,7 +149,8 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     // positions are 32-bit (the API keeps prompts below 2^30 tokens); a window longer than the prompt is the prompt
     const int n = (int)a.n;
     const int w_sink = min(a.w_sink, n), w_recent = min(a.w_recent, n);
-    const int n_qb = (n + kBlockQueries - 1) / kBlockQueries;
+    const int n_q = (int)a.n_q, q_first = n - n_q;              // the queries are the last n_q of the n positions
+    const int n_qb = (n_q + kBlockQueries - 1) / kBlockQueries;
     const int64_t total = (int64_t)n_qb * a.n_kv_heads * a.batch;
     const int64_t per_xcd = (total + 7) / 8;
     const int64_t vid = (int64_t)(blockIdx.x % 8) * per_xcd + blockIdx.x / 8;
@@ -157,7 +158,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     const int pair = (int)(vid / n_qb), qb = n_qb - 1 - (int)(vid % n_qb);
     const int b = pair / a.n_kv_heads, g = pair % a.n_kv_heads;
     const int h = g * G + wave % G;
-    const int q_block = qb * kBlockQueries;
+    const int q_block = q_first + qb * kBlockQueries;
     const int q0 = q_block + (wave / G) * kWaveQueries;             // first query of this wavefront
 
     // key tiles the block needs: [0, n_a) and [t_b, t_last]
@@ -183,7 +184,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         for (int s = 0; s < 8; ++s) {
             u32x4_t u = {0u, 0u, 0u, 0u};
             if (p < n)
-                u = *reinterpret_cast<const u32x4_t *>(a.q + (((int64_t)b * a.n_q_heads + h) * a.n + p) * kHeadDim + 16 * s + 8 * half);
+                u = *reinterpret_cast<const u32x4_t *>(a.q + (((int64_t)b * a.n_q_heads + h) * n_q + (p - q_first)) * kHeadDim + 16 * s + 8 * half);
             qf[nt][s] = __builtin_bit_cast(bf16x8_t, u);
         }
     }
@@ -376,7 +377,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         const float l_tot = sum_halves(l_sum[nt]);
         if (p >= n) continue;
         const float inv = 1.f / l_tot;
-        const int64_t row = ((int64_t)b * a.n_q_heads + h) * a.n + p;
+        const int64_t row = ((int64_t)b * a.n_q_heads + h) * n_q + (p - q_first);
         if (a.lse != nullptr && half == 0) a.lse[row] = (m_ref[nt] + __builtin_amdgcn_logf(l_tot)) * 0.69314718055994530942f;
 #pragma unroll
         for (int dt = 0; dt < 4; ++dt)
@@ -402,7 +403,7 @@ template <int G, int QB, int NT>
 hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream)
 {
     const int64_t block_queries = 32 * NT * QB;
-    const int64_t total = (a.n + block_queries - 1) / block_queries * a.n_kv_heads * a.batch;
+    const int64_t total = (a.n_q + block_queries - 1) / block_queries * a.n_kv_heads * a.batch;
     const int64_t grid = (total + 7) / 8 * 8;
     hipLaunchKernelGGL((lt_prefill_attn_kernel<G, QB, NT>), dim3((unsigned)grid), dim3(64 * G * QB), 0, stream, a);
     return hipGetLastError();

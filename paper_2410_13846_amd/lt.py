@@ -82,7 +82,7 @@ def load() -> ctypes.CDLL:
     lib.lt_lazy_ratio_lse_workspace_bytes.restype = sz
     lib.lt_lazy_ratio_lse.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, i64, i64, vp, sz, vp, vp, vp, vp]
     lib.lt_lazy_ratio_lse.restype = ctypes.c_int
-    lib.lt_prefill_attn.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, vp, vp]
+    lib.lt_prefill_attn.argtypes = [cfgp, vp, vp, vp, i64, i64, i64, i64, i64, ctypes.c_int, ctypes.c_int, vp, vp, vp]
     lib.lt_prefill_attn.restype = ctypes.c_int
     lib.lt_select_lazy.argtypes = [vp, i32, i32, vp, vp]
     lib.lt_preselect_lazy.argtypes = [vp, i32, i32, i32, vp, vp]
@@ -257,20 +257,22 @@ def lazy_ratio_lse(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w
 
 def prefill_attn(cfg: Config, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor, n: int, mask: int = MASK_CAUSAL,
                  out_dtype=torch.bfloat16, want_lse: bool = True, stream=None):
-    """q bf16 [B,Hq,n,128] contiguous; k, v bf16 [B,Hkv,>=n,128] with equal strides and contiguous dims.
-    Returns (out [B,Hq,n,128] in out_dtype, lse fp32 [B,Hq,n] or None)."""
+    """q bf16 [B,Hq,n_q,128] contiguous, the queries of the last n_q of n positions (n_q = n: a whole prompt);
+    k, v bf16 [B,Hkv,>=n,128] with equal strides and contiguous dims.
+    Returns (out [B,Hq,n_q,128] in out_dtype, lse fp32 [B,Hq,n_q] or None)."""
     lib = load()
     for t in (q, k, v):
         if t.dtype != torch.bfloat16 or not t.is_cuda:
             raise TypeError("q, k, v must be bf16 device tensors")
-    if not q.is_contiguous() or k.dim() != 4 or k.stride(3) != 1 or k.stride() != v.stride():
-        raise TypeError("q must be contiguous; k and v need equal strides and contiguous head_dim")
+    if not q.is_contiguous() or q.dim() != 4 or k.dim() != 4 or k.stride(3) != 1 or k.stride() != v.stride():
+        raise TypeError("q must be contiguous [B,Hq,n_q,128]; k and v need equal strides and contiguous head_dim")
     if out_dtype not in (torch.bfloat16, torch.float32):
         raise TypeError("out_dtype must be bfloat16 or float32")
-    out = torch.empty((cfg.batch, cfg.n_q_heads, int(n), cfg.head_dim), dtype=out_dtype, device=q.device)
-    lse = torch.empty((cfg.batch, cfg.n_q_heads, int(n)), dtype=torch.float32, device=q.device) if want_lse else None
+    n_q = int(q.shape[2])
+    out = torch.empty((cfg.batch, cfg.n_q_heads, n_q, cfg.head_dim), dtype=out_dtype, device=q.device)
+    lse = torch.empty((cfg.batch, cfg.n_q_heads, n_q), dtype=torch.float32, device=q.device) if want_lse else None
     st = lib.lt_prefill_attn(ctypes.byref(cfg), q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
-                             int(n), int(mask), OUT_F32 if out_dtype == torch.float32 else OUT_BF16, out.data_ptr(),
+                             int(n), n_q, int(mask), OUT_F32 if out_dtype == torch.float32 else OUT_BF16, out.data_ptr(),
                              lse.data_ptr() if lse is not None else None, _stream_ptr(stream))
     _check(st, "lt_prefill_attn")
     return out, lse

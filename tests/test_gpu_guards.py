@@ -108,7 +108,7 @@ def test_scoring_and_prefill_stay_inside_their_buffers(B, Hq, Hkv, n, w, ws, wr)
             out_all, out_mem = guarded(B * Hq * n * 128 * esz)
             lse_all, lse_mem = guarded(B * Hq * n * 4)
             st = lib.lt_prefill_attn(ctypes.byref(cfg), q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
-                                     n, mask, dtype_flag, out_mem.data_ptr(), lse_mem.data_ptr(), stream)
+                                     n, n, mask, dtype_flag, out_mem.data_ptr(), lse_mem.data_ptr(), stream)
             assert st == lt.OK
             bands += [out_all, lse_all]
     lse = lse_mem[: B * Hq * n * 4].view(torch.float32).view(B, Hq, n)       # the last one is a streaming-mask LSE: redo causal

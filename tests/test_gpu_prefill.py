@@ -138,3 +138,54 @@ def test_ratio_from_lse_windows_and_both_readings(ws, wr, mode):
 @pytest.mark.parametrize("group", [1, 5])
 def test_ratio_from_lse_scored_queries_and_groups(w, group):
     check_ratio_lse(B=1, Hq=group, Hkv=1, n=900, w=w, ws=4, wr=124, seed=6200 + w + group)
+
+
+# ---- chunked prefill: the queries are the last n_q of n positions ------------------------------------------
+
+@pytest.mark.parametrize("n,n_q", [(300, 1), (300, 37), (300, 64), (1000, 333), (777, 776), (129, 65), (2000, 96)])
+@pytest.mark.parametrize("mask", [lt.MASK_CAUSAL, lt.MASK_STREAMING])
+def test_chunk_of_queries_equals_the_rows_of_the_whole_prompt(n, n_q, mask):
+    B, Hq, Hkv, ws, wr = 2, 8, 2, 4, 100
+    say("chunked prefill", dict(n=n, n_q=n_q, mask=mask))
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, ws, wr, n)
+    q = randn_bf16((B, Hq, n, 128), 7000 + n + n_q)
+    k, v = randn_bf16((B, Hkv, n, 128), 7001 + n), randn_bf16((B, Hkv, n, 128), 7002 + n)
+    q_chunk = q[:, :, n - n_q:].contiguous()
+    out, lse = lt.prefill_attn(cfg, q_chunk, k, v, n, mask, out_dtype=torch.float32)
+    assert out.shape == (B, Hq, n_q, 128) and lse.shape == (B, Hq, n_q)
+    mode = oracle.MODE_LAZY if mask == lt.MASK_STREAMING else oracle.MODE_FULL
+    ref, ref_lse, absw = oracle.prefill_attn(bits(q), bits(k), bits(v), mode, ws, wr, return_absw=True)
+    ref, ref_lse, absw = ref[:, :, n - n_q:], ref_lse[:, :, n - n_q:], absw[:, :, n - n_q:]
+    assert (np.abs(f64(out) - ref) <= out_tolerance(absw, ref, torch.float32)).all()
+    assert np.abs(f64(lse) - ref_lse).max() <= TOL_PREFILL_LSE
+
+
+@pytest.mark.parametrize("group", [1, 3, 5, 8])
+def test_chunked_prefill_through_the_cache_chunk_by_chunk(group):
+    """A prompt prefilled in three chunks, keys and values read in place from the cache after each append: the
+    concatenated rows equal the one-shot prefill's; the last chunk's log-sum-exp feeds the lazy ratio."""
+    B, Hkv, ws, wr, w = 1, 2, 4, 60, 32
+    Hq = group * Hkv
+    chunks = [211, 64, 390]
+    n = sum(chunks)
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, ws, wr, n)
+    ctx = lt.Context(cfg, [0], DEV)
+    q = randn_bf16((B, Hq, n, 128), 7100 + group, scale=2.0)
+    k, v = randn_bf16((B, Hkv, n, 128), 7101 + group), randn_bf16((B, Hkv, n, 128), 7102 + group)
+    kc, vc = ctx.layer_tensors(0)
+    outs, lses, done = [], [], 0
+    for m in chunks:
+        ctx.append_kv(0, k[:, :, done:done + m].contiguous(), v[:, :, done:done + m].contiguous())
+        done += m
+        o, l = lt.prefill_attn(cfg, q[:, :, done - m:done].contiguous(), kc, vc, done, out_dtype=torch.float32)
+        outs.append(o)
+        lses.append(l)
+    out, lse = torch.cat(outs, dim=2), torch.cat(lses, dim=2)
+    ref, ref_lse, absw = oracle.prefill_attn(bits(q), bits(k), bits(v), oracle.MODE_FULL, return_absw=True)
+    assert (np.abs(f64(out) - ref) <= out_tolerance(absw, ref, torch.float32)).all()
+    assert np.abs(f64(lse) - ref_lse).max() <= TOL_PREFILL_LSE
+    q_last = q[:, :, n - w:].contiguous()
+    mean, _, rho = lt.lazy_ratio_lse(cfg, q_last, kc, n, w, lses[-1][:, :, chunks[-1] - w:], want_rho=True)
+    ref_rho, _, ref_r = oracle.lazy_ratio(bits(q_last), bits(k), ws, wr)
+    assert np.abs(f64(rho) - ref_rho).max() <= TOL_RATIO and abs(float(mean.cpu()[0]) - ref_r) <= TOL_RATIO
+    ctx.close()

@@ -142,12 +142,15 @@ def test_prefill_and_ratio_from_lse_argument_validation():
     """Error paths of lt_prefill_attn / lt_lazy_ratio_lse that return before anything is enqueued."""
     lib, c = lt.load(), cfg()
 
-    def prefill(q=FAKE_DEV, k=FAKE_DEV, v=FAKE_DEV, out=FAKE_DEV, n=500, mask=0, dtype=0, sb=500 * 128 * 2, sh=500 * 128, st=128, conf=c):
-        return lib.lt_prefill_attn(ctypes.byref(conf), q, k, v, sb, sh, st, n, mask, dtype, out, None, None)
+    def prefill(q=FAKE_DEV, k=FAKE_DEV, v=FAKE_DEV, out=FAKE_DEV, n=500, nq=None, mask=0, dtype=0, sb=500 * 128 * 2, sh=500 * 128, st=128,
+                conf=c):
+        return lib.lt_prefill_attn(ctypes.byref(conf), q, k, v, sb, sh, st, n, n if nq is None else nq, mask, dtype, out, None, None)
 
     assert prefill(q=None) == lt.ERR_INVALID_ARG
     assert prefill(out=None) == lt.ERR_INVALID_ARG
     assert prefill(n=0) == lt.ERR_INVALID_ARG
+    assert prefill(nq=0) == lt.ERR_INVALID_ARG
+    assert prefill(nq=501) == lt.ERR_SHAPE                   # more queries than positions
     assert prefill(mask=2) == lt.ERR_INVALID_ARG
     assert prefill(dtype=5) == lt.ERR_INVALID_ARG
     assert prefill(k=FAKE_DEV + 2) == lt.ERR_INVALID_ARG
