@@ -32,10 +32,11 @@ struct TileClass {
     bool kept;      // on the fast path: all pairs are kept
 };
 
-__device__ __forceinline__ TileClass classify(int64_t j0, int64_t n, int w, int w_sink, int w_recent, int fixed_mode)
+// Positions are 32-bit: the API keeps prompts below 2^30 tokens and the kernel clamps the windows to the prompt.
+__device__ __forceinline__ TileClass classify(int j0, int n, int w, int w_sink, int w_recent, int fixed_mode)
 {
-    const int64_t j1 = j0 + 31;
-    const int64_t p_min = n - w, p_max = n - 1;
+    const int j1 = j0 + 31;
+    const int p_min = n - w, p_max = n - 1;
     TileClass c;
     const bool all_causal = j1 <= p_min;
     bool all_kept, none_kept;
@@ -66,14 +67,14 @@ __device__ __forceinline__ void update_fast(const floatx16_t &c, LaneState &st, 
     st.m = m_new;
 }
 
-__device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st, float scale_log2e, int64_t j_base,
-                                              int64_t p, int64_t n, int w_sink, int w_recent, int fixed_mode)
+__device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st, float scale_log2e, int j_base,
+                                              int p, int n, int w_sink, int w_recent, int fixed_mode)
 {
     // key row of accumulator register i in this lane: j_base + 8*(i/4) + (i%4)
     float tmax = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int64_t j = j_base + 8 * (i >> 2) + (i & 3);
+        const int j = j_base + 8 * (i >> 2) + (i & 3);
         if (j <= p) tmax = fmaxf(tmax, c[i]);
     }
     const float m_new = fmaxf(st.m, tmax * scale_log2e);
@@ -82,7 +83,7 @@ __device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st
     float sum = 0.f, kept = 0.f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
-        const int64_t j = j_base + 8 * (i >> 2) + (i & 3);
+        const int j = j_base + 8 * (i >> 2) + (i & 3);
         const bool causal = j <= p;
         const bool recent = fixed_mode ? (j >= n - w_recent) : (j > p - w_recent);
         const float e = causal ? fast_exp2(fmaf(c[i], scale_log2e, -m_new)) : 0.f;
@@ -105,16 +106,15 @@ struct Staging {
 };
 
 template <int G>
-__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Staging<G>::kPieces], const uint16_t *kb, int64_t stride_t, int64_t j0,
-                                           int64_t n)
+__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Staging<G>::kPieces], const uint16_t *kb, int64_t stride_t, int j0, int n)
 {
 #pragma unroll
     for (int i = 0; i < Staging<G>::kPieces; ++i) {
         int idx = threadIdx.x + i * Staging<G>::kThreads;
         idx = idx < Staging<G>::kTotal ? idx : Staging<G>::kTotal - 1;   // surplus threads re-read the last piece
-        int64_t j = j0 + (idx >> 4);
+        int j = j0 + (idx >> 4);
         j = j < n ? j : n - 1;                                          // clamp; such keys are masked as non-causal
-        pre[i] = *reinterpret_cast<const u32x4_t *>(kb + j * stride_t + (idx & 15) * 8);
+        pre[i] = *reinterpret_cast<const u32x4_t *>(kb + (int64_t)j * stride_t + (idx & 15) * 8);
     }
 }
 
@@ -137,19 +137,22 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
 
     constexpr int kPieces = Staging<G>::kPieces;
     const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it stays in scalar registers
     const int col = lane & 31, half = lane >> 5;
     const int h = g * G + wave;
 
-    int64_t begin_key, end_key;
+    const int n = (int)a.n;
+    const int w_sink = min(a.w_sink, n), w_recent = min(a.w_recent, n);   // a window longer than the prompt is the prompt
+    int begin_key, end_key;
     if (chunk < a.n_chunks_a) {
-        begin_key = (int64_t)chunk * a.keys_per_block;
-        end_key = min(a.range_a_end, begin_key + (int64_t)a.keys_per_block);
+        begin_key = chunk * a.keys_per_block;
+        end_key = min((int)a.range_a_end, begin_key + a.keys_per_block);
     } else {
-        begin_key = a.range_b_begin + (int64_t)(chunk - a.n_chunks_a) * a.keys_per_block;
-        end_key = min(a.n, begin_key + (int64_t)a.keys_per_block);
+        begin_key = (int)a.range_b_begin + (chunk - a.n_chunks_a) * a.keys_per_block;
+        end_key = min(n, begin_key + a.keys_per_block);
     }
-    const int n_tiles = (int)((end_key - begin_key + kScoreTileKeys - 1) / kScoreTileKeys);
+    const int n_tiles = (end_key - begin_key + kScoreTileKeys - 1) / kScoreTileKeys;
     const uint16_t *kb = a.k + (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
 
     // Q^T fragments (B operand): lane holds, for its query column, the 8 dims 16*s + 8*half .. +7
@@ -186,16 +189,16 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
         }
     };
     // Fold one sub-tile's logits into the running max and the two sums of every query column.
-    auto fold = [&](const floatx16_t (&c)[NT], int64_t j0) {
-        const TileClass cls = classify(j0, a.n, a.w_last, a.w_sink, a.w_recent, a.fixed_mode);
+    auto fold = [&](const floatx16_t (&c)[NT], int j0) {
+        const TileClass cls = classify(j0, n, a.w_last, w_sink, w_recent, a.fixed_mode);
         if (cls.fast) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) update_fast(c[nt], st[nt], a.scale_log2e, cls.kept);
         } else {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
-                const int64_t p = a.n - a.w_last + nt * 32 + col;       // query position of this lane's column
-                update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, p, a.n, a.w_sink, a.w_recent, a.fixed_mode);
+                const int p = n - a.w_last + nt * 32 + col;             // query position of this lane's column
+                update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, p, n, w_sink, w_recent, a.fixed_mode);
             }
         }
     };
@@ -203,7 +206,7 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
     // Two wavefronts per SIMD (from two workgroups) overlap one's matrix-core work with the
     // other's exponentials.  The K tiles are prefetched two tiles ahead in two register sets, so
     // a global load has two tiles of compute (about 2.5 us) to arrive before it is parked in LDS.
-    auto compute = [&](const uint16_t *tile, int64_t j0) {
+    auto compute = [&](const uint16_t *tile, int j0) {
 #pragma unroll
         for (int kt = 0; kt < kScoreTileKeys / 32; ++kt) {
             if (j0 + 32 * kt >= end_key) break;
@@ -212,22 +215,22 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
             fold(c, j0 + 32 * kt);
         }
     };
-    auto tile_key = [&](int tile) { return begin_key + (int64_t)tile * kScoreTileKeys; };
+    auto tile_key = [&](int tile) { return begin_key + tile * kScoreTileKeys; };
 
     u32x4_t pre_even[kPieces], pre_odd[kPieces];
     if (n_tiles > 0) {
-        fetch_tile<G>(pre_even, kb, a.k_stride_t, tile_key(0), a.n);
+        fetch_tile<G>(pre_even, kb, a.k_stride_t, tile_key(0), n);
         commit_tile<G>(pre_even, sh_k[0]);
     }
     __syncthreads();
-    if (n_tiles > 1) fetch_tile<G>(pre_odd, kb, a.k_stride_t, tile_key(1), a.n);
+    if (n_tiles > 1) fetch_tile<G>(pre_odd, kb, a.k_stride_t, tile_key(1), n);
     for (int tile = 0; tile < n_tiles; tile += 2) {
-        if (tile + 2 < n_tiles) fetch_tile<G>(pre_even, kb, a.k_stride_t, tile_key(tile + 2), a.n);
+        if (tile + 2 < n_tiles) fetch_tile<G>(pre_even, kb, a.k_stride_t, tile_key(tile + 2), n);
         compute(sh_k[0], tile_key(tile));
         if (tile + 1 < n_tiles) {
             commit_tile<G>(pre_odd, sh_k[1]);
             __syncthreads();
-            if (tile + 3 < n_tiles) fetch_tile<G>(pre_odd, kb, a.k_stride_t, tile_key(tile + 3), a.n);
+            if (tile + 3 < n_tiles) fetch_tile<G>(pre_odd, kb, a.k_stride_t, tile_key(tile + 3), n);
             compute(sh_k[1], tile_key(tile + 1));
             if (tile + 2 < n_tiles) {
                 commit_tile<G>(pre_even, sh_k[0]);
