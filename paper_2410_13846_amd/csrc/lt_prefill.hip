@@ -69,19 +69,29 @@ struct Stage {
     static constexpr int kPieces = (kTotal + kThreads - 1) / kThreads;
 };
 
-// Rows past the end of the prompt are read from its last key (they are masked as non-causal).
-// The row offset inside a tile is a 32-bit product: the API keeps the token stride below 2^24.
+// The staging loads go through buffer descriptors: a load is (uniform descriptor) + (one per-lane byte
+// offset that is the same for every tile and every piece), so moving to the next tile or piece costs
+// scalar instructions and no vector ones.  A descriptor covers exactly the rows of the tile that lie
+// inside the prompt from its own first row on; the hardware returns zeros for anything past that,
+// which is how the ragged last tile is handled (those keys are masked as non-causal anyway).
+// Offsets inside a tile are 32-bit: the API keeps the token stride below 2^24.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_from(const uint16_t *first_row, int rows_left, int64_t stride_t)
+{
+    const uint32_t bytes = rows_left > 0 ? ((uint32_t)(rows_left - 1) * (uint32_t)stride_t + kHeadDim) * 2u : 0u;
+    return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(first_row), 0, (int)bytes, 0x00020000);   // raw buffer of 32-bit words
+}
+
 template <int W>
-__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int j0, int n)
+__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int j0, int n, uint32_t lane_bytes)
 {
     const uint16_t *tile = base + (int64_t)j0 * stride_t;                // uniform
-    const int last = min(n - 1 - j0, kTileKeys - 1);
+    const int rows = min(n - j0, kTileKeys);
+    constexpr int kPieceRows = Stage<W>::kThreads / 16;
 #pragma unroll
     for (int i = 0; i < Stage<W>::kPieces; ++i) {
-        int idx = threadIdx.x + i * Stage<W>::kThreads;
-        idx = idx < Stage<W>::kTotal ? idx : Stage<W>::kTotal - 1;       // surplus threads re-read the last piece
-        const int row = min(idx >> 4, last);
-        pre[i] = *reinterpret_cast<const u32x4_t *>(tile + (row * (int)stride_t + (idx & 15) * 8));
+        const __amdgpu_buffer_rsrc_t src = rows_from(tile + (int64_t)(i * kPieceRows) * stride_t, rows - i * kPieceRows, stride_t);
+        if ((i + 1) * Stage<W>::kThreads <= Stage<W>::kTotal || (int)threadIdx.x + i * Stage<W>::kThreads < Stage<W>::kTotal)
+            pre[i] = __builtin_amdgcn_raw_buffer_load_b128(src, lane_bytes, 0, 0);
     }
 }
 
@@ -100,17 +110,14 @@ __device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kPiec
 // dim chunks fall on the same banks take key groups 32 keys apart, so that a write of 32 lanes covers all banks.
 // Slot of key j (0..63) in a V^T row: 16 (j / 16) + {0, 8, 4, 12}[(j % 16) / 4] + j % 4, i.e. within 16 keys the
 // order 0-3, 8-11, 4-7, 12-15: slots 8 h .. 8 h + 7 then hold keys 4 h + {0..3} and 8 + 4 h + {0..3}.
-__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base, int64_t stride_t, int j0, int n)
+__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base, int64_t stride_t, int j0, int n, uint32_t lane_bytes)
 {
     if (threadIdx.x >= 256) return;
-    const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2);
     const uint16_t *tile = base + (int64_t)j0 * stride_t;
-    const int last = min(n - 1 - j0, kTileKeys - 1);
+    const int rows = min(n - j0, kTileKeys);
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-        const int row = min(4 * kg + r, last);
-        pre[r] = *reinterpret_cast<const u32x4_t *>(tile + (row * (int)stride_t + c * 8));
-    }
+    for (int r = 0; r < 4; ++r)                  // key r of every group of four: one descriptor, r rows further on
+        pre[r] = __builtin_amdgcn_raw_buffer_load_b128(rows_from(tile + (int64_t)r * stride_t, rows - r, stride_t), lane_bytes, 0, 0);
 }
 
 __device__ __forceinline__ void commit_v(const u32x4_t (&pre)[4], uint16_t *sh)
@@ -293,10 +300,14 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     };
 
     u32x4_t pre_k[kPieces], pre_v[4];
+    // per-lane byte offsets of the staging loads inside a whole tile (see fetch_tile, fetch_v)
+    const uint32_t k_lane_bytes = 2u * ((threadIdx.x >> 4) * (uint32_t)a.kv_stride_t + (threadIdx.x & 15) * 8);
+    const uint32_t v_lane_bytes = 2u * (4 * (((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2)) * (uint32_t)a.kv_stride_t
+                                        + (4 * (threadIdx.x >> 6) + (threadIdx.x & 3)) * 8);
     auto prefetch = [&](int t) {
         if (t < n_tiles) {
-            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), n);
-            fetch_v(pre_v, vb, a.kv_stride_t, tile_key(t), n);
+            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), n, k_lane_bytes);
+            fetch_v(pre_v, vb, a.kv_stride_t, tile_key(t), n, v_lane_bytes);
         }
     };
     auto park = [&](int t) {                     // registers of tile t -> its LDS buffer, then everyone may read it
