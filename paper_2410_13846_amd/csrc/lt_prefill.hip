@@ -33,6 +33,7 @@ constexpr int kTileKeys = 64;                 // keys per LDS tile
 constexpr int kKRow = kHeadDim + 8;           // 272-byte K rows: 16-byte reads of 32 rows spread over the banks
 constexpr int kVtRow = kTileKeys + 8;         // V^T tile: 128 dim rows of 64 key slots, 144-byte rows (16-byte reads of 16 rows spread over the banks)
 constexpr float kRescaleStep = 8.f;           // log2 units the row maximum may exceed the reference before it moves
+constexpr float kQuickSumLimit = 4096.f;      // 2^(kRescaleStep + 4): 16 probabilities of at most 2^kRescaleStep
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
@@ -62,11 +63,18 @@ __device__ __forceinline__ uint32_t pack_bf16(float lo, float hi)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
 }
 
+// Who stages what.  The first four wavefronts transpose V (four 16-byte loads each); with eight or more
+// wavefronts the others copy K and the first four do not, so that no wavefront holds both sets of
+// staging registers: they share the slots of one array.
 template <int kWaves>
 struct Stage {
-    static constexpr int kThreads = 64 * kWaves;
+    static constexpr bool kSplit = kWaves >= 8;
+    static constexpr int kFirst = kSplit ? 256 : 0;                      // first thread that copies K
+    static constexpr int kThreads = 64 * kWaves - kFirst;
     static constexpr int kTotal = kTileKeys * 16;                        // 16-byte pieces of one 64 x 128 tile
     static constexpr int kPieces = (kTotal + kThreads - 1) / kThreads;
+    static constexpr int kFirstSlot = kSplit ? 0 : 4;                    // K's first slot
+    static constexpr int kSlots = kSplit ? (kPieces > 4 ? kPieces : 4) : 4 + kPieces;
 };
 
 // The staging loads go through buffer descriptors: a load is (uniform descriptor) + (one per-lane byte
@@ -81,27 +89,32 @@ __device__ __forceinline__ __amdgpu_buffer_rsrc_t rows_from(const uint16_t *firs
     return __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t *>(first_row), 0, (int)bytes, 0x00020000);   // raw buffer of 32-bit words
 }
 
+// K: thread i of the copying threads takes pieces i, i + kThreads, ...; piece x is 16 bytes (x % 16) of row x / 16.
 template <int W>
-__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kPieces], const uint16_t *base, int64_t stride_t, int j0, int n, uint32_t lane_bytes)
+__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Stage<W>::kSlots], const uint16_t *base, int64_t stride_t, int j0, int n, uint32_t lane_bytes)
 {
+    const int me = (int)threadIdx.x - Stage<W>::kFirst;
+    if (me < 0) return;
     const uint16_t *tile = base + (int64_t)j0 * stride_t;                // uniform
     const int rows = min(n - j0, kTileKeys);
     constexpr int kPieceRows = Stage<W>::kThreads / 16;
 #pragma unroll
     for (int i = 0; i < Stage<W>::kPieces; ++i) {
         const __amdgpu_buffer_rsrc_t src = rows_from(tile + (int64_t)(i * kPieceRows) * stride_t, rows - i * kPieceRows, stride_t);
-        if ((i + 1) * Stage<W>::kThreads <= Stage<W>::kTotal || (int)threadIdx.x + i * Stage<W>::kThreads < Stage<W>::kTotal)
-            pre[i] = __builtin_amdgcn_raw_buffer_load_b128(src, lane_bytes, 0, 0);
+        if ((i + 1) * Stage<W>::kThreads <= Stage<W>::kTotal || me + i * Stage<W>::kThreads < Stage<W>::kTotal)
+            pre[Stage<W>::kFirstSlot + i] = __builtin_amdgcn_raw_buffer_load_b128(src, lane_bytes, 0, 0);
     }
 }
 
 template <int W, int kRow>
-__device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kPieces], uint16_t *sh)
+__device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kSlots], uint16_t *sh)
 {
+    const int me = (int)threadIdx.x - Stage<W>::kFirst;
+    if (me < 0) return;
 #pragma unroll
     for (int i = 0; i < Stage<W>::kPieces; ++i) {
-        const int idx = threadIdx.x + i * Stage<W>::kThreads;
-        if (idx < Stage<W>::kTotal) *reinterpret_cast<u32x4_t *>(&sh[(idx >> 4) * kRow + (idx & 15) * 8]) = pre[i];
+        const int idx = me + i * Stage<W>::kThreads;
+        if (idx < Stage<W>::kTotal) *reinterpret_cast<u32x4_t *>(&sh[(idx >> 4) * kRow + (idx & 15) * 8]) = pre[Stage<W>::kFirstSlot + i];
     }
 }
 
@@ -110,7 +123,8 @@ __device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kPiec
 // dim chunks fall on the same banks take key groups 32 keys apart, so that a write of 32 lanes covers all banks.
 // Slot of key j (0..63) in a V^T row: 16 (j / 16) + {0, 8, 4, 12}[(j % 16) / 4] + j % 4, i.e. within 16 keys the
 // order 0-3, 8-11, 4-7, 12-15: slots 8 h .. 8 h + 7 then hold keys 4 h + {0..3} and 8 + 4 h + {0..3}.
-__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base, int64_t stride_t, int j0, int n, uint32_t lane_bytes)
+template <int kSlots>
+__device__ __forceinline__ void fetch_v(u32x4_t (&pre)[kSlots], const uint16_t *base, int64_t stride_t, int j0, int n, uint32_t lane_bytes)
 {
     if (threadIdx.x >= 256) return;
     const uint16_t *tile = base + (int64_t)j0 * stride_t;
@@ -120,7 +134,8 @@ __device__ __forceinline__ void fetch_v(u32x4_t (&pre)[4], const uint16_t *base,
         pre[r] = __builtin_amdgcn_raw_buffer_load_b128(rows_from(tile + (int64_t)r * stride_t, rows - r, stride_t), lane_bytes, 0, 0);
 }
 
-__device__ __forceinline__ void commit_v(const u32x4_t (&pre)[4], uint16_t *sh)
+template <int kSlots>
+__device__ __forceinline__ void commit_v(const u32x4_t (&pre)[kSlots], uint16_t *sh)
 {
     if (threadIdx.x >= 256) return;
     const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2);
@@ -144,7 +159,6 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     __shared__ __attribute__((aligned(16))) uint16_t sh_k[2][kTileKeys * kKRow];
     __shared__ __attribute__((aligned(16))) uint16_t sh_v[2][kHeadDim * kVtRow];
     static_assert(W >= 4, "V staging needs 256 threads");
-    constexpr int kPieces = Stage<W>::kPieces;
 
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // in a scalar register: what depends on it branches uniformly
@@ -209,15 +223,14 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
 
     const int win_sink = a.streaming ? w_sink : 0x7fffffff;       // causal attention: every key counts as "initial"
 
-    // S^T of one 32-key sub-tile for this wavefront's queries, masked, and the sub-tile maximum of
-    // every query column in log2 units (of the lane's 16 keys, or of all 32 when `agree`)
-    auto logits = [&](floatx16_t (&c)[NT], float (&tmax)[NT], const uint16_t *tile_k, int kt, int j0, bool agree) {
+    // S^T of one 32-key sub-tile for this wavefront's queries, masked (raw dot products; -inf where masked)
+    auto scores = [&](floatx16_t (&c)[NT], const uint16_t *tile_k, int kt, int j0) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
-        // the chain runs at raised priority: the SIMD's other wavefront fills the gaps between the
-        // matrix instructions with its exponentials instead of delaying them
+        // the chain runs at raised priority: the SIMD's other wavefronts fill the gaps between the
+        // matrix instructions with their exponentials instead of delaying them
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
@@ -246,34 +259,31 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
                     c[nt][i] = keep ? c[nt][i] : -INFINITY;
                 }
             }
-            float t = c[nt][0];
-#pragma unroll
-            for (int i = 1; i < 16; ++i) t = fmaxf(t, c[nt][i]);
-            // the two lanes of a column must agree on the maximum only where it becomes the reference
-            tmax[nt] = (agree ? max_halves(t) : t) * a.scale_log2e;
         }
     };
 
-    // probabilities against the current reference, their sum, and O^T += V^T P^T
+    // c -> probabilities against the reference `mu` (log2 units), in place; returns each column's sum over the lane's 16 keys
+    auto probabilities = [&](floatx16_t &c, float mu) {
+        float sum = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            c[i] = fast_exp2(fmaf(c[i], a.scale_log2e, -mu));
+            sum += c[i];
+        }
+        return sum;
+    };
+
+    // O^T += V^T P^T for the probabilities in c
     auto accumulate = [&](const floatx16_t (&c)[NT], const uint16_t *tile_v, int kt) {
         bf16x8_t pf[NT][2];                      // P^T fragments: [query tile][16-key step]
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const float mu = m_ref[nt] == -INFINITY ? 0.f : m_ref[nt];
-            float pr[16], sum = 0.f;
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                pr[i] = fast_exp2(fmaf(c[nt][i], a.scale_log2e, -mu));
-                sum += pr[i];
-            }
-            l_sum[nt] += sum;
+        for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
             for (int sp = 0; sp < 2; ++sp) {
-                const u32x4_t u = {pack_bf16(pr[8 * sp + 0], pr[8 * sp + 1]), pack_bf16(pr[8 * sp + 2], pr[8 * sp + 3]),
-                                   pack_bf16(pr[8 * sp + 4], pr[8 * sp + 5]), pack_bf16(pr[8 * sp + 6], pr[8 * sp + 7])};
+                const u32x4_t u = {pack_bf16(c[nt][8 * sp + 0], c[nt][8 * sp + 1]), pack_bf16(c[nt][8 * sp + 2], c[nt][8 * sp + 3]),
+                                   pack_bf16(c[nt][8 * sp + 4], c[nt][8 * sp + 5]), pack_bf16(c[nt][8 * sp + 6], c[nt][8 * sp + 7])};
                 pf[nt][sp] = __builtin_bit_cast(bf16x8_t, u);
             }
-        }
         // k slots 0..7 of a lane are keys 16 sp + 4 half + {0..3} and 16 sp + 8 + 4 half + {0..3}: the order the
         // logits sit in the accumulator registers 8 sp .. 8 sp + 7, and the order of the V^T slots
         // The lane's offset into the V^T tile is rebuilt from the lane number here rather than kept in a register
@@ -299,21 +309,22 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         return j0 > q0 + kWaveQueries - 1 || (a.streaming && j0 >= w_sink && j0 + 31 <= q0 - w_recent);
     };
 
-    u32x4_t pre_k[kPieces], pre_v[4];
+    u32x4_t pre[Stage<W>::kSlots];             // staging registers: V in slots 0..3 of the first four wavefronts, K see Stage
     // per-lane byte offsets of the staging loads inside a whole tile (see fetch_tile, fetch_v)
-    const uint32_t k_lane_bytes = 2u * ((threadIdx.x >> 4) * (uint32_t)a.kv_stride_t + (threadIdx.x & 15) * 8);
+    const uint32_t k_me = threadIdx.x - Stage<W>::kFirst;               // unused by the threads that copy no K
+    const uint32_t k_lane_bytes = 2u * ((k_me >> 4) * (uint32_t)a.kv_stride_t + (k_me & 15) * 8);
     const uint32_t v_lane_bytes = 2u * (4 * (((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2)) * (uint32_t)a.kv_stride_t
                                         + (4 * (threadIdx.x >> 6) + (threadIdx.x & 3)) * 8);
     auto prefetch = [&](int t) {
         if (t < n_tiles) {
-            fetch_tile<W>(pre_k, kb, a.kv_stride_t, tile_key(t), n, k_lane_bytes);
-            fetch_v(pre_v, vb, a.kv_stride_t, tile_key(t), n, v_lane_bytes);
+            fetch_tile<W>(pre, kb, a.kv_stride_t, tile_key(t), n, k_lane_bytes);
+            fetch_v(pre, vb, a.kv_stride_t, tile_key(t), n, v_lane_bytes);
         }
     };
     auto park = [&](int t) {                     // registers of tile t -> its LDS buffer, then everyone may read it
         if (t < n_tiles) {
-            commit_tile<W, kKRow>(pre_k, sh_k[t & 1]);
-            commit_v(pre_v, sh_v[t & 1]);
+            commit_tile<W, kKRow>(pre, sh_k[t & 1]);
+            commit_v(pre, sh_v[t & 1]);
         }
         __syncthreads();
     };
@@ -323,33 +334,44 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         const int j0 = tile_key(t) + 32 * kt;
         if (dead(j0)) return;
         floatx16_t c[NT];
-        float tmax[NT];
-        logits(c, tmax, sh_k[t & 1], kt, j0, true);
+        scores(c, sh_k[t & 1], kt, j0);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
-            const bool grow = tmax[nt] > m_ref[nt] + kRescaleStep;
-            const float alpha = grow ? fast_exp2(m_ref[nt] - tmax[nt]) : 1.f;   // 0 when the reference was -inf
-            m_ref[nt] = grow ? tmax[nt] : m_ref[nt];
+            float tmax = c[nt][0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) tmax = fmaxf(tmax, c[nt][i]);
+            tmax = max_halves(tmax) * a.scale_log2e;              // the two lanes of a column share one reference
+            const bool grow = tmax > m_ref[nt] + kRescaleStep;
+            const float alpha = grow ? fast_exp2(m_ref[nt] - tmax) : 1.f;   // 0 when the reference was -inf
+            m_ref[nt] = grow ? tmax : m_ref[nt];
             l_sum[nt] *= alpha;
 #pragma unroll
             for (int dt = 0; dt < 4; ++dt)
 #pragma unroll
                 for (int i = 0; i < 16; ++i) acc[dt][nt][i] *= alpha;
+            l_sum[nt] += probabilities(c[nt], m_ref[nt] == -INFINITY ? 0.f : m_ref[nt]);
         }
         accumulate(c, sh_v[t & 1], kt);
     };
-    // The same without touching the references: returns false, having changed nothing, when some
-    // row's maximum has outgrown its reference.
+    // The same without touching the references, and without looking for the maximum: the probabilities are
+    // formed against the current reference and the sub-tile is taken only if every lane's sum of its 16
+    // stays within 2^(kRescaleStep + 4).  A larger sum (or a NaN: no reference yet) means that some logit is
+    // more than kRescaleStep above its reference; then nothing is changed and false is returned.
     auto quick = [&](int t, int kt) {
         const int j0 = tile_key(t) + 32 * kt;
         if (dead(j0)) return true;
         floatx16_t c[NT];
-        float tmax[NT];
-        logits(c, tmax, sh_k[t & 1], kt, j0, false);
-        bool grow = false;
+        scores(c, sh_k[t & 1], kt, j0);
+        float sum[NT];
+        bool fits = true;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) grow = grow || tmax[nt] > m_ref[nt] + kRescaleStep;
-        if (__any(grow)) return false;
+        for (int nt = 0; nt < NT; ++nt) {
+            sum[nt] = probabilities(c[nt], m_ref[nt]);
+            fits = fits && sum[nt] <= kQuickSumLimit;
+        }
+        if (!__all(fits)) return false;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) l_sum[nt] += sum[nt];
         accumulate(c, sh_v[t & 1], kt);
         return true;
     };
