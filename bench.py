@@ -54,6 +54,11 @@ def parse_args():
                     help="long-generation curve: fixed lazy mask, decode from the prompt length up to the workload's "
                          "final length, timing --steps decode steps at each doubling of the history (the tokens in "
                          "between are bulk-appended); reports tokens/s against generated length")
+    ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
+                    help="compare the stack with its full layers stored in pages of this many tokens (shuffled block table) "
+                         "against the contiguous stack; prints its own JSON line")
+    ap.add_argument("--paged-table", choices=("shuffled", "sequential"), default="shuffled",
+                    help="with --paged: pages handed out in a random order (a pool in use for a while) or in sequence")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (outside the timed region) so that hardware-counter "
                          "runs have a kernel of known traffic to scale FETCH_SIZE / WRITE_SIZE by")
@@ -67,7 +72,9 @@ def log(*a):
 class Stack:
     """A hybrid stack with its decode inputs pre-generated on the device."""
 
-    def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0, online=False):
+    def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0, online=False, page_tokens=0,
+                 shuffled=True):
+        import numpy as np
         import torch
 
         self.lt, self.wl, self.dev = lt, wl, dev
@@ -100,7 +107,15 @@ class Stack:
             self.is_lazy = mask
         else:
             self.is_lazy = list(map(int, is_lazy))
-            self.ctx = lt.Context(self.cfg, self.is_lazy, dev)
+            if page_tokens:
+                # every sequence gets the pages of its whole run up front, scattered over the pool
+                max_pages = -(-(wl.context + total_steps) // page_tokens)
+                self.ctx = lt.Context(self.cfg, self.is_lazy, dev, paged=(page_tokens, wl.batch * max_pages))
+                order = np.random.default_rng(7).permutation(wl.batch * max_pages) if shuffled else np.arange(wl.batch * max_pages)
+                table = order.astype(np.int32).reshape(wl.batch, max_pages)
+                self.ctx.set_block_table(table)
+            else:
+                self.ctx = lt.Context(self.cfg, self.is_lazy, dev)
             for layer in range(wl.n_layers):
                 k, v = W.prefill_kv(wl, layer, dev)
                 self.ctx.append_kv(layer, k, v)
@@ -347,6 +362,45 @@ def prefill_bench(args, lt, W, wl, dev):
             "kv_heads": wl.n_kv_heads, "context": n, "w_sink": wl.w_sink, "w_recent": wl.w_recent, "w_last": w}, "layers": rows}
 
 
+def paged_bench(args, lt, W, wl, dev):
+    """The same stack and steps with contiguous and with paged full layers: ms per step and per-launch times."""
+    import torch
+
+    is_lazy = [0] * wl.n_layers
+    for layer in W.planted_lazy_layers(wl)[: wl.n_lazy]:
+        is_lazy[layer] = 1
+    K, Wm = args.steps, args.warmup
+    rows = {}
+    for name, page in (("contiguous", 0), ("paged", args.paged)):
+        stack = Stack(lt, W, wl, is_lazy, Wm + 2 * K, dev, args.keys_full, args.keys_lazy, page_tokens=page,
+                      shuffled=args.paged_table == "shuffled")
+        stack.run(Wm)
+        elapsed = timed(stack, K)
+        stack.ctx.profile_enable(True)
+        T_first = stack.tokens_now() + 1
+        timed(stack, K)
+        T_mean = 0.5 * (T_first + stack.tokens_now())
+        stack.ctx.profile_enable(False)
+        n_full, ms_full = stack.ctx.profile_read(lt.KERNEL_DECODE_FULL)
+        n_lazy, ms_lazy = stack.ctx.profile_read(lt.KERNEL_DECODE_LAZY)
+        launch_bytes = wl.batch * ((2 * wl.n_kv_heads * wl.head_dim * 2) * T_mean + wl.n_q_heads * wl.head_dim * (2 + 4)
+                                   + wl.n_kv_heads * wl.head_dim * 2 * 2)
+        full_us = ms_full / max(n_full, 1) * 1e3
+        rows[name] = {"ms_per_step": elapsed / K * 1e3, "tokens_per_s": wl.batch * K / elapsed, "full_launch_us": full_us,
+                      "full_launch_gbs": launch_bytes / full_us / 1e3, "full_launch_hbm_frac": launch_bytes / full_us / 1e3 / HBM_PEAK_GBS,
+                      "lazy_launch_us": (ms_lazy / n_lazy * 1e3) if n_lazy else None, "kv_slab_gb": stack.ctx.kv_slab.numel() / 1e9}
+        log("%s: %.3f ms/step, full-layer launch %.1f us (%.0f GB/s)" % (name, rows[name]["ms_per_step"], full_us, rows[name]["full_launch_gbs"]))
+        stack.close()
+        del stack
+        torch.cuda.empty_cache()
+    return {"metric": "decode step, paged against contiguous full layers", "n_gpus": 1, "steps": K, "warmup": Wm, "data": "synthetic",
+            "dtype": "bf16 storage, fp32 accumulate",
+            "config": {"workload": wl.name, "page_tokens": args.paged, "batch": wl.batch, "context": wl.context, "lazy_layers": wl.n_lazy,
+                       "block_table": "a random permutation of the pool" if args.paged_table == "shuffled" else "pages in sequence"},
+            "contiguous": rows["contiguous"], "paged": rows["paged"],
+            "paged_over_contiguous_ms": rows["paged"]["ms_per_step"] / rows["contiguous"]["ms_per_step"]}
+
+
 def window_grid(args, lt, W, wl, dev):
     """The ablation grid of Table 7 as a cost sweep: decode time per step of the hybrid stack (planted mask) for every
     w_recent at w_sink = 4 and every w_sink at w_recent = 1020, and scoring time of one layer for every w_last."""
@@ -438,6 +492,9 @@ def main():
         return 0
     if args.grid:
         print(json.dumps(window_grid(args, lt, W, wl, dev)))
+        return 0
+    if args.paged:
+        print(json.dumps(paged_bench(args, lt, W, wl, dev)))
         return 0
 
     # ---- identification: score every layer, select ------------------------------------------------

@@ -258,6 +258,45 @@ lt_status lt_append_kv_ragged(lt_ctx *ctx, int32_t layer, const void *k_new, con
  * lt_append_kv_ragged was used).  Either output may be NULL. */
 lt_status lt_seq_len(const lt_ctx *ctx, int32_t layer, int32_t sequence, int64_t *total_tokens, int64_t *stored_tokens);
 
+/* Forget the tokens of one sequence in every layer (host counters only): the slot is free for a new
+ * prompt, brought by lt_append_kv_ragged with a count of 0 for the other sequences.  Turns the
+ * context into the per-sequence mode of lt_append_kv_ragged.  LT_ERR_SHAPE if batch > 64;
+ * LT_ERR_STATE on a context made by lt_create_online. */
+lt_status lt_reset_sequence(lt_ctx *ctx, int32_t sequence);
+
+/* ---- paged storage for the full layers (serving; the paper's Section "LightTransfer-Test" keeps
+ * the whole cache of a non-lazy layer, which a server stores page by page so that sequences of
+ * different and growing lengths share one pool) -------------------------------------------------
+ *
+ * A full layer owns a K pool and a V pool of bf16 [n_pages][Hkv][page_tokens][128]; ONE block
+ * table, int32 [B][max_pages] with max_pages = ceil(max_tokens / page_tokens), serves all full
+ * layers: token p of sequence b lives in page table[b][p / page_tokens] of each full layer's pools,
+ * at row p mod page_tokens.  -1 = no page.  The caller assigns pages (two sequences may name the same
+ * page only if neither is appended to while they do); the library checks on the host, before every
+ * launch, that each token a kernel will read or write has a page inside the pool, so a bad table is
+ * an error code and never a stray access.  Lazy layers keep their rings, one per sequence, as in
+ * lt_create.  Lengths are per sequence throughout (see lt_append_kv_ragged); every other call works
+ * as on a context from lt_create, except lt_truncate_layer (LT_ERR_STATE), and lt_layer_view, whose
+ * strides for a full layer are those inside one page (stride_b = the stride between pages).
+ *
+ * page_tokens: a power of two, 64 <= page_tokens <= 2^20.  batch <= 64.
+ * lt_kv_bytes_paged: bytes of the slab (table + pools + rings); 0 on invalid arguments.
+ * lt_create_paged: LT_ERR_SHAPE if page_tokens is no such power of two, batch > 64, or max_tokens
+ * exceeds what the split decode kernel covers with pages this small (255 pages per workgroup). */
+size_t lt_kv_bytes_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages);
+lt_status lt_create_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages,
+                          void *kv_slab, size_t kv_bytes, void *workspace, size_t ws_bytes, lt_ctx **out);
+
+/* Replace the block table.
+ *   table_host  host, int32 [B][max_pages]; every entry -1 or in [0, n_pages)
+ * The pages that hold a sequence's tokens so far must stay named (LT_ERR_STATE otherwise); entries
+ * beyond may be set ahead of need.  LT_ERR_INVALID_ARG for an entry outside the pool.  The call waits
+ * for the work already on `stream` (kernels may be reading the old table), copies, and waits for the
+ * copy: tables change when a sequence crosses a page or a slot changes hands, not every step.
+ * lt_append_kv(_ragged) and lt_decode_step return LT_ERR_STATE, with nothing enqueued, when a token
+ * they would store has no page. */
+lt_status lt_set_block_table(lt_ctx *ctx, const int32_t *table_host, void *stream);
+
 /* Element type of `out` in lt_decode_attn / lt_decode_step from now on: LT_OUT_F32 (the default)
  * or LT_OUT_BF16 (rounded to nearest even from the fp32 result; what a bf16 model consumes). */
 lt_status lt_set_output_dtype(lt_ctx *ctx, lt_out_dtype dtype);

@@ -104,6 +104,11 @@ struct lt_ctx {
     bool online = false;
     uint8_t *full_pool = nullptr, *ring_pool = nullptr;
     std::vector<uint8_t> full_used, ring_used;
+    // paged mode (lt_create_paged): full layers are pools of pages addressed through one block table
+    bool paged = false;
+    int32_t page_shift = 0, n_pages = 0, max_pages = 0;
+    int32_t *table_dev = nullptr;              // [B][max_pages], inside the slab
+    std::vector<int32_t> table_host;           // the copy the host checks lengths against; -1 = no page
 };
 
 // Max-priority queue of (ratio, layer) with a fixed capacity; small, so a plain vector.
@@ -287,6 +292,137 @@ lt_status lt_create_online(const lt_config *cfg, int32_t n_full, void *kv_slab, 
     return LT_OK;
 }
 
+// ---- paged storage for the full layers ------------------------------------------------------------
+
+static bool paged_args_ok(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages)
+{
+    if (!config_ok(cfg) || config_shape(cfg) != LT_OK || is_lazy == nullptr) return false;
+    if (page_tokens < 64 || page_tokens > (1 << 20) || (page_tokens & (page_tokens - 1)) != 0 || n_pages <= 0) return false;
+    if (cfg->batch > ltk::kMaxRaggedBatch) return false;
+    return true;
+}
+
+static size_t page_pool_bytes(const lt_config *cfg, int32_t page_tokens, int32_t n_pages)
+{
+    return align_up((size_t)n_pages * cfg->n_kv_heads * (size_t)page_tokens * ltk::kHeadDim * sizeof(uint16_t));
+}
+
+static size_t block_table_bytes(const lt_config *cfg, int32_t page_tokens)
+{
+    return align_up((size_t)cfg->batch * (size_t)ceil_div(cfg->max_tokens, page_tokens) * sizeof(int32_t));
+}
+
+size_t lt_kv_bytes_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages)
+{
+    if (!paged_args_ok(cfg, is_lazy, page_tokens, n_pages)) return 0;
+    size_t total = block_table_bytes(cfg, page_tokens);
+    for (int i = 0; i < cfg->n_layers; ++i)
+        total += is_lazy[i] != 0 ? 2 * block_bytes(cfg, true) : 2 * page_pool_bytes(cfg, page_tokens, n_pages);
+    return total;
+}
+
+lt_status lt_create_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages, void *kv_slab,
+                          size_t kv_bytes, void *workspace, size_t ws_bytes, lt_ctx **out)
+{
+    if (out == nullptr) return LT_ERR_INVALID_ARG;
+    *out = nullptr;
+    if (!config_ok(cfg) || is_lazy == nullptr || kv_slab == nullptr || workspace == nullptr) return LT_ERR_INVALID_ARG;
+    const lt_status shape = config_shape(cfg);
+    if (shape != LT_OK) return shape;
+    if (page_tokens <= 0 || n_pages <= 0) return LT_ERR_INVALID_ARG;
+    if (!paged_args_ok(cfg, is_lazy, page_tokens, n_pages)) return LT_ERR_SHAPE;
+    // a workgroup's key range may touch kMaxRangePages pages and a sequence is cut into at most max_splits ranges
+    if (cfg->max_tokens > max_splits(cfg) * (int64_t)(ltk::kMaxRangePages - 1) * page_tokens) return LT_ERR_SHAPE;
+    if (((uintptr_t)kv_slab % kAlign) != 0 || ((uintptr_t)workspace % kAlign) != 0) return LT_ERR_INVALID_ARG;
+    if (kv_bytes < lt_kv_bytes_paged(cfg, is_lazy, page_tokens, n_pages) || ws_bytes < lt_workspace_bytes(cfg)) return LT_ERR_CAPACITY;
+
+    lt_ctx *ctx = new (std::nothrow) lt_ctx();
+    if (ctx == nullptr) return LT_ERR_NOMEM;
+    ctx->cfg = *cfg;
+    ctx->cfg.softmax_scale = effective_scale(cfg);
+    ctx->paged = true;
+    ctx->n_pages = n_pages;
+    ctx->max_pages = (int32_t)ceil_div(cfg->max_tokens, page_tokens);
+    while ((1 << ctx->page_shift) < page_tokens) ++ctx->page_shift;
+    try {
+        ctx->layers.resize(cfg->n_layers);
+        ctx->table_host.assign((size_t)cfg->batch * ctx->max_pages, -1);
+        for (Layer &l : ctx->layers) l.total_b.assign((size_t)cfg->batch, 0);   // lengths are always per sequence here
+    } catch (const std::bad_alloc &) {
+        delete ctx;
+        return LT_ERR_NOMEM;
+    }
+    uint8_t *cursor = static_cast<uint8_t *>(kv_slab);
+    ctx->table_dev = reinterpret_cast<int32_t *>(cursor);
+    cursor += block_table_bytes(cfg, page_tokens);
+    for (int i = 0; i < cfg->n_layers; ++i) {
+        Layer &l = ctx->layers[i];
+        l.lazy = is_lazy[i] != 0;
+        l.capacity = l.lazy ? window_of(cfg) : (int64_t)ctx->max_pages * page_tokens;
+        const size_t bytes = l.lazy ? block_bytes(cfg, true) : page_pool_bytes(cfg, page_tokens, n_pages);
+        l.k = reinterpret_cast<uint16_t *>(cursor);
+        l.v = reinterpret_cast<uint16_t *>(cursor + bytes);
+        cursor += 2 * bytes;
+    }
+    bind_workspace(ctx, workspace);
+    *out = ctx;
+    return LT_OK;
+}
+
+// Pages a sequence needs for `tokens` tokens are all present in the host copy of the block table.
+static bool pages_cover(const lt_ctx *ctx, int32_t sequence, int64_t tokens)
+{
+    const int64_t pages = (tokens + ((int64_t)1 << ctx->page_shift) - 1) >> ctx->page_shift;
+    if (pages > ctx->max_pages) return false;
+    for (int64_t p = 0; p < pages; ++p)
+        if (ctx->table_host[(size_t)sequence * ctx->max_pages + p] < 0) return false;
+    return true;
+}
+
+lt_status lt_set_block_table(lt_ctx *ctx, const int32_t *table_host, void *stream)
+{
+    if (ctx == nullptr || table_host == nullptr) return LT_ERR_INVALID_ARG;
+    if (!ctx->paged) return LT_ERR_STATE;
+    const size_t entries = (size_t)ctx->cfg.batch * ctx->max_pages;
+    for (size_t i = 0; i < entries; ++i)
+        if (table_host[i] < -1 || table_host[i] >= ctx->n_pages) return LT_ERR_INVALID_ARG;
+    // a page that holds tokens must stay named: every sequence keeps the pages its longest full layer has filled
+    for (int32_t b = 0; b < ctx->cfg.batch; ++b) {
+        int64_t longest = 0;
+        for (const Layer &l : ctx->layers)
+            if (!l.lazy) longest = std::max(longest, l.total_b[b]);
+        const int64_t pages = (longest + ((int64_t)1 << ctx->page_shift) - 1) >> ctx->page_shift;
+        for (int64_t p = 0; p < pages; ++p)
+            if (table_host[(size_t)b * ctx->max_pages + p] < 0) return LT_ERR_STATE;
+    }
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    // kernels enqueued earlier may still read the old table; the host copy must not change under the transfer either
+    if (hipStreamSynchronize(s) != hipSuccess) return LT_ERR_HIP;
+    std::copy(table_host, table_host + entries, ctx->table_host.begin());
+    if (hipMemcpyAsync(ctx->table_dev, ctx->table_host.data(), entries * sizeof(int32_t), hipMemcpyHostToDevice, s) != hipSuccess)
+        return LT_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return LT_ERR_HIP;
+    return LT_OK;
+}
+
+lt_status lt_reset_sequence(lt_ctx *ctx, int32_t sequence)
+{
+    if (ctx == nullptr || sequence < 0 || sequence >= ctx->cfg.batch) return LT_ERR_INVALID_ARG;
+    if (ctx->online) return LT_ERR_STATE;      // online identification works on whole batches of equal length
+    if (ctx->cfg.batch > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
+    try {
+        for (Layer &l : ctx->layers)
+            if (l.total_b.empty()) l.total_b.assign((size_t)ctx->cfg.batch, l.total);
+    } catch (const std::bad_alloc &) {
+        return LT_ERR_NOMEM;
+    }
+    for (Layer &l : ctx->layers) {
+        l.total_b[sequence] = 0;
+        l.total = *std::max_element(l.total_b.begin(), l.total_b.end());
+    }
+    return LT_OK;
+}
+
 void lt_destroy(lt_ctx *ctx)
 {
     if (ctx == nullptr) return;
@@ -302,7 +438,8 @@ lt_status lt_reset(lt_ctx *ctx)
     if (ctx == nullptr) return LT_ERR_INVALID_ARG;
     for (Layer &l : ctx->layers) {
         l.total = 0;
-        l.total_b.clear();
+        if (ctx->paged) std::fill(l.total_b.begin(), l.total_b.end(), 0);
+        else l.total_b.clear();
         if (ctx->online) {                      // back to "full, no storage yet"
             l.k = l.v = nullptr;
             l.slot = -1;
@@ -331,8 +468,9 @@ lt_status lt_layer_view(const lt_ctx *ctx, int32_t layer, void **k_dev, void **v
     const Layer &l = ctx->layers[layer];
     if (k_dev != nullptr) *k_dev = l.k;
     if (v_dev != nullptr) *v_dev = l.v;
-    if (stride_h != nullptr) *stride_h = l.capacity * ltk::kHeadDim;
-    if (stride_b != nullptr) *stride_b = l.capacity * ltk::kHeadDim * ctx->cfg.n_kv_heads;
+    const int64_t head_tokens = ctx->paged && !l.lazy ? (int64_t)1 << ctx->page_shift : l.capacity;
+    if (stride_h != nullptr) *stride_h = head_tokens * ltk::kHeadDim;
+    if (stride_b != nullptr) *stride_b = head_tokens * ltk::kHeadDim * ctx->cfg.n_kv_heads;
     if (capacity != nullptr) *capacity = l.capacity;
     if (is_lazy != nullptr) *is_lazy = l.lazy ? 1 : 0;
     return LT_OK;
@@ -601,6 +739,9 @@ static lt_status append_impl(lt_ctx *ctx, int32_t layer, const void *k_new, cons
         }
     }
     if (!l.lazy && longest_after > l.capacity) return LT_ERR_CAPACITY;
+    if (ctx->paged && !l.lazy)
+        for (int b = 0; b < B; ++b)
+            if (!pages_cover(ctx, b, l.total_b[b] + (n_per_seq != nullptr ? n_per_seq[b] : n_new))) return LT_ERR_STATE;
     if (ragged && l.total_b.empty()) {
         try {
             l.total_b.assign((size_t)B, l.total);
@@ -628,6 +769,11 @@ static lt_status append_impl(lt_ctx *ctx, int32_t layer, const void *k_new, cons
         a.w_sink = ctx->cfg.w_sink;
         a.w_recent = ctx->cfg.w_recent;
         a.ragged = ragged ? 1 : 0;
+        if (ctx->paged && !l.lazy) {
+            a.block_table = ctx->table_dev;
+            a.max_pages = ctx->max_pages;
+            a.page_shift = ctx->page_shift;
+        }
         if (ragged)
             for (int b = 0; b < B; ++b) {
                 a.n_new_b[b] = n_per_seq != nullptr ? n_per_seq[b] : n_new;
@@ -695,6 +841,10 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     if (stored <= 0) return LT_ERR_STATE;
     const bool ragged = !l.total_b.empty();
     if (ragged && c.batch > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
+    const bool paged = ctx->paged && !l.lazy;
+    if (paged && fused)
+        for (int b = 0; b < c.batch; ++b)
+            if (!pages_cover(ctx, b, l.total_b[b] + 1)) return LT_ERR_STATE;   // the new token has no page yet
 
     ltk::DecodeArgs a{};
     a.k_cache = l.k;
@@ -717,6 +867,10 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     a.stored = (int32_t)stored;
     const int32_t forced = l.lazy ? ctx->keys_lazy : ctx->keys_full;
     a.keys_per_block = forced > 0 ? forced : choose_keys_per_block(stored, (int64_t)c.batch * c.n_kv_heads, l.lazy, ctx->splits_cap);
+    if (paged) {                                // a workgroup's range may touch at most kMaxRangePages pages
+        const int64_t most = ((int64_t)(ltk::kMaxRangePages - 1) << ctx->page_shift) / ltk::kKeyGranule * ltk::kKeyGranule;
+        a.keys_per_block = (int32_t)std::min<int64_t>(a.keys_per_block, most);
+    }
     a.n_splits = (int32_t)ceil_div(stored, a.keys_per_block);
     if (a.n_splits > ctx->splits_cap) return LT_ERR_CAPACITY;
     a.scale_log2e = c.softmax_scale * kLog2e;
@@ -725,9 +879,10 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     // window over which the workgroups' start addresses are spread: the largest power of two of 4 KB tiles that
     // fits a workgroup's key range, at most 4 MB; short ranges start at pseudo-random tiles instead
     a.spread_tiles = 0;
-    for (uint32_t w = 1024; w >= 128; w >>= 1)
+    for (uint32_t w = 1024; w >= 128 && !paged; w >>= 1)                     // pages scatter the addresses by themselves
         if ((int64_t)w * 16 <= a.keys_per_block) { a.spread_tiles = w; break; }
-    ltk::RaggedArgs per_seq;
+    ltk::PagedArgs paged_args;
+    ltk::RaggedArgs &per_seq = paged_args.lengths;
     if (ragged)
         for (int b = 0; b < c.batch; ++b) {
             const int64_t total_b = l.total_b[b] + (fused ? 1 : 0);
@@ -741,7 +896,13 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     }
     {
         ScopedEvents ev(ctx, s, l.lazy ? LT_KERNEL_DECODE_LAZY : LT_KERNEL_DECODE_FULL);
-        if (ltk::decode(a, ragged ? &per_seq : nullptr, s) != hipSuccess) return LT_ERR_HIP;
+        if (paged) {
+            paged_args.block_table = ctx->table_dev;
+            paged_args.max_pages = ctx->max_pages;
+            paged_args.page_shift = ctx->page_shift;
+            a.stride_b = a.stride_h = 0;
+        }
+        if (ltk::decode(a, ragged && !paged ? &per_seq : nullptr, paged ? &paged_args : nullptr, s) != hipSuccess) return LT_ERR_HIP;
     }
     l.total = total;
     if (ragged && fused)

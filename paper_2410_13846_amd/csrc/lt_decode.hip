@@ -75,7 +75,11 @@ __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
         }
     }
     const int64_t src = (((int64_t)b * a.n_kv_heads + g) * a.n_new + j) * kHeadDim + c * 8;
-    const int64_t dst = (int64_t)b * a.stride_b + (int64_t)g * a.stride_h + slot * kHeadDim + c * 8;
+    int64_t dst = (int64_t)b * a.stride_b + (int64_t)g * a.stride_h + slot * kHeadDim + c * 8;
+    if (a.block_table != nullptr) {
+        const int64_t page = a.block_table[(int64_t)b * a.max_pages + (slot >> a.page_shift)];
+        dst = (((page * a.n_kv_heads + g) << a.page_shift) + (slot & ((1 << a.page_shift) - 1))) * kHeadDim + c * 8;
+    }
     store16(a.k_cache + dst, load16(a.k_new + src));
     store16(a.v_cache + dst, load16(a.v_new + src));
 }
@@ -325,9 +329,18 @@ __device__ __forceinline__ void store_out(const DecodeArgs &a, int64_t index, fl
 }
 
 struct NoRaggedArgs {};
-template <int G, int LAZY_TAG, int kWaves, bool kRagged>
-__global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, std::conditional_t<kRagged, RaggedArgs, NoRaggedArgs> r)
+// kMode 0: equal lengths; 1: per-sequence lengths; 2: per-sequence lengths and a paged cache
+enum { kUniform = 0, kRaggedMode = 1, kPagedMode = 2 };
+template <int kMode> struct ModeArgs { typedef NoRaggedArgs type; };
+template <> struct ModeArgs<kRaggedMode> { typedef RaggedArgs type; };
+template <> struct ModeArgs<kPagedMode> { typedef PagedArgs type; };
+__device__ __forceinline__ const RaggedArgs &lengths_of(const RaggedArgs &r) { return r; }
+__device__ __forceinline__ const RaggedArgs &lengths_of(const PagedArgs &r) { return r.lengths; }
+
+template <int G, int LAZY_TAG, int kWaves, int kMode>
+__global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
 {
+    constexpr bool kRagged = kMode != kUniform, kPaged = kMode == kPagedMode;
     constexpr int kThreads = 64 * kWaves;
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
@@ -344,7 +357,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, st
     // in a ragged batch a sequence may end before this workgroup's range: then the range is empty and
     // the workgroup contributes an empty partial result
     int stored = a.stored;
-    if constexpr (kRagged) stored = r.stored_b[b];
+    if constexpr (kRagged) stored = lengths_of(r).stored_b[b];
     const int begin_key = split * a.keys_per_block;
     const int end_key = min(stored, begin_key + a.keys_per_block);
     const int n_tiles = max((end_key - begin_key + 15) >> 4, 0);
@@ -353,14 +366,58 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, st
     uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
     // fused append: the one tile that holds new_slot takes the token from k_new / v_new
     int new_slot = a.k_new != nullptr ? a.new_slot : -1;
-    if constexpr (kRagged) new_slot = a.k_new != nullptr ? r.new_slot_b[b] : -1;
+    if constexpr (kRagged) new_slot = a.k_new != nullptr ? lengths_of(r).new_slot_b[b] : -1;
     const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
     const uint16_t *hot = a.q + ((int64_t)b * a.n_q_heads + g * G) * kHeadDim;
-    auto fetch = [&](Tile &t, int key0) { load_tile(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new, hot); };
+    // Paged cache: lane i of every wavefront holds the pages of the range's pages i, 64 + i, 128 + i, 192 + i;
+    // a 16-key tile never straddles pages (their size is a multiple of 16), so a tile costs one cross-lane
+    // read of one of those registers to find its page and no memory access.  tile_shift is the element offset
+    // that, added to the layer's pool, makes "base + key * 128" land on the key inside its page.
+    constexpr int kPageRegs = kPaged ? kMaxRangePages / 64 : 1;
+    int32_t range_pages[kPageRegs] = {};
+    int first_page = 0;
+    if constexpr (kPaged) {
+        first_page = begin_key >> r.page_shift;
+        const int last_page = max(end_key - 1, begin_key) >> r.page_shift;
+#pragma unroll
+        for (int i = 0; i < kPageRegs; ++i)
+            if (n_tiles > 0 && first_page + 64 * i <= last_page)          // uniform
+                range_pages[i] = r.block_table[(int64_t)b * r.max_pages + min(first_page + 64 * i + lane, last_page)];
+    }
+    auto tile_shift = [&](int key0) -> int64_t {
+        int64_t shift = 0;
+        if constexpr (kPaged) {
+            const int key = max(key0, begin_key);                   // key0 < 0: a fetch whose tile is never consumed
+            const int idx = (key >> r.page_shift) - first_page;     // uniform, below kMaxRangePages
+            int32_t page = __builtin_amdgcn_readlane(range_pages[0], idx & 63);
+#pragma unroll
+            for (int i = 1; i < kPageRegs; ++i)
+                if ((idx >> 6) == i) page = __builtin_amdgcn_readlane(range_pages[i], idx & 63);
+            const int64_t in_pool = (((int64_t)page * a.n_kv_heads + g) << r.page_shift) * kHeadDim;
+            shift = in_pool - (int64_t)((key >> r.page_shift) << r.page_shift) * kHeadDim;
+        }
+        return shift;
+    };
+    if constexpr (kPaged) { kb = a.k_cache; vb = a.v_cache; }
+    auto fetch = [&](Tile &t, int key0) {
+        if constexpr (kPaged) {
+            const int64_t shift = tile_shift(key0);
+            load_tile(t, kb + shift, vb + shift, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new, hot);
+        } else {
+            load_tile(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new, hot);
+        }
+    };
     auto consume = [&](const Tile &t, int key0, RowState<G> &st, const uint32_t (&qf)[G][4]) {
-        store_new_token(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot);
+        if constexpr (kPaged) {
+            if (new_slot >= key0 && new_slot < key0 + 16) {         // wave-uniform, true for one tile of one workgroup
+                const int64_t shift = tile_shift(key0);
+                store_new_token(t, kb + shift, vb + shift, key0, sub, chunk, end_key - 1, new_slot);
+            }
+        } else {
+            store_new_token(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot);
+        }
         process_tile<G>(t, qf, st, key0, sub, chunk, end_key, a.scale_log2e);
     };
 
@@ -398,8 +455,19 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, st
     const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
     const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)begin_key * kHeadDim)) >> 12);
     const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
-    const int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
-                                     : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+    int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
+                               : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+    if constexpr (kPaged) {
+        // Pages scatter the high address bits by themselves; what the start tile still decides is the position
+        // inside a page.  The workgroups of one KV head (whose pages all sit at the same offset inside a pool
+        // page) start evenly spread over the tiles of a page, at a pseudo-random page of their range.
+        const unsigned int page_tiles = 1u << (r.page_shift - 4);
+        const unsigned int among = gridDim.x * gridDim.z, mine = blockIdx.z * gridDim.x + blockIdx.x;
+        const unsigned int want = (unsigned int)(((uint64_t)mine * page_tiles) / among) & (page_tiles - 1);
+        const unsigned int in_page = (want - ((unsigned int)begin_key >> 4)) & (page_tiles - 1);
+        const unsigned int pages_here = ((unsigned int)wrap + page_tiles - 1) / page_tiles;
+        phase = (int)((in_page + (((linear_block * 2654435761u) >> 12) % pages_here) * page_tiles) % (unsigned int)wrap);
+    }
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     int next_tile = wave + phase, fetched = 0;
     while (next_tile >= wrap) next_tile -= wrap;
@@ -555,29 +623,25 @@ __global__ void lt_zero_tickets_kernel(unsigned int *tickets, int n)
     if (i < n) tickets[i] = 0u;
 }
 
-template <int G, int LAZY_TAG, bool kRagged>
-hipError_t launch_decode_as(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
+template <int G, int LAZY_TAG, int kMode>
+hipError_t launch_decode_as(const DecodeArgs &a, const typename ModeArgs<kMode>::type &r, hipStream_t stream)
 {
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
     // short ranges: eight wavefronts per workgroup; not for groups of eight heads, whose state needs more than
     // the 256 registers a wavefront has when two share a SIMD
     const bool wide = G < 8 && a.keys_per_block <= kWideBlockKeys;
-    if constexpr (kRagged) {
-        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, true>), grid, dim3(512), 0, stream, a, *ragged);
-        else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, true>), grid, dim3(256), 0, stream, a, *ragged);
-    } else {
-        if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, false>), grid, dim3(512), 0, stream, a, NoRaggedArgs{});
-        else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, false>), grid, dim3(256), 0, stream, a, NoRaggedArgs{});
-    }
+    if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);
+    else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, kMode>), grid, dim3(256), 0, stream, a, r);
     return hipGetLastError();
 }
 
 template <int G>
-hipError_t launch_decode(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
+hipError_t launch_decode(const DecodeArgs &a, const RaggedArgs *ragged, const PagedArgs *paged, hipStream_t stream)
 {
+    if (paged != nullptr) return launch_decode_as<G, 0, kPagedMode>(a, *paged, stream);   // only full layers are paged
     if (ragged != nullptr)
-        return a.lazy_tag ? launch_decode_as<G, 1, true>(a, ragged, stream) : launch_decode_as<G, 0, true>(a, ragged, stream);
-    return a.lazy_tag ? launch_decode_as<G, 1, false>(a, ragged, stream) : launch_decode_as<G, 0, false>(a, ragged, stream);
+        return a.lazy_tag ? launch_decode_as<G, 1, kRaggedMode>(a, *ragged, stream) : launch_decode_as<G, 0, kRaggedMode>(a, *ragged, stream);
+    return a.lazy_tag ? launch_decode_as<G, 1, kUniform>(a, NoRaggedArgs{}, stream) : launch_decode_as<G, 0, kUniform>(a, NoRaggedArgs{}, stream);
 }
 
 }  // namespace
@@ -598,17 +662,17 @@ hipError_t truncate(const TruncateArgs &a, hipStream_t stream)
     return hipGetLastError();
 }
 
-hipError_t decode(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream)
+hipError_t decode(const DecodeArgs &a, const RaggedArgs *ragged, const PagedArgs *paged, hipStream_t stream)
 {
     switch (a.n_q_heads / a.n_kv_heads) {
-    case 1: return launch_decode<1>(a, ragged, stream);
-    case 2: return launch_decode<2>(a, ragged, stream);
-    case 3: return launch_decode<3>(a, ragged, stream);
-    case 4: return launch_decode<4>(a, ragged, stream);
-    case 5: return launch_decode<5>(a, ragged, stream);
-    case 6: return launch_decode<6>(a, ragged, stream);
-    case 7: return launch_decode<7>(a, ragged, stream);
-    case 8: return launch_decode<8>(a, ragged, stream);
+    case 1: return launch_decode<1>(a, ragged, paged, stream);
+    case 2: return launch_decode<2>(a, ragged, paged, stream);
+    case 3: return launch_decode<3>(a, ragged, paged, stream);
+    case 4: return launch_decode<4>(a, ragged, paged, stream);
+    case 5: return launch_decode<5>(a, ragged, paged, stream);
+    case 6: return launch_decode<6>(a, ragged, paged, stream);
+    case 7: return launch_decode<7>(a, ragged, paged, stream);
+    case 8: return launch_decode<8>(a, ragged, paged, stream);
     default: return hipErrorInvalidValue;
     }
 }

@@ -27,6 +27,10 @@ struct AppendArgs {
     // ragged batches: sequence b brings n_new_b[b] <= n_new tokens (rows beyond are padding) and holds total_before_b[b]
     int32_t ragged;
     int64_t n_new_b[kMaxRaggedBatch], total_before_b[kMaxRaggedBatch];
+    // paged full layer (block_table != nullptr): k_cache / v_cache are pools [page][Hkv][1 << page_shift][128] and
+    // token p of sequence b lives in page block_table[b * max_pages + (p >> page_shift)]
+    const int32_t *block_table;
+    int32_t max_pages, page_shift;
 };
 hipError_t append(const AppendArgs &a, hipStream_t stream);
 
@@ -63,7 +67,17 @@ struct DecodeArgs {
 struct RaggedArgs {
     int32_t stored_b[kMaxRaggedBatch], new_slot_b[kMaxRaggedBatch];
 };
-hipError_t decode(const DecodeArgs &a, const RaggedArgs *ragged, hipStream_t stream);   // ragged == nullptr: equal lengths
+// paged full layer: per-sequence lengths as above, and k_cache / v_cache are pools [page][Hkv][1 << page_shift][128];
+// entry (p >> page_shift) of a sequence's row of the block table names the page that holds its token p.  A workgroup's
+// key range may touch at most kMaxRangePages pages (the launcher's keys_per_block sees to that).
+constexpr int kMaxRangePages = 256;     // four registers of 64 lanes
+struct PagedArgs {
+    RaggedArgs lengths;
+    const int32_t *block_table;        // device, [B][max_pages]
+    int32_t max_pages, page_shift;
+};
+// ragged == nullptr and paged == nullptr: equal lengths, contiguous cache.  At most one of the two is given.
+hipError_t decode(const DecodeArgs &a, const RaggedArgs *ragged, const PagedArgs *paged, hipStream_t stream);
 hipError_t zero_tickets(unsigned int *tickets, int n, hipStream_t stream);
 hipError_t probe_read(const void *buf, int64_t bytes, uint32_t *sink, hipStream_t stream);
 

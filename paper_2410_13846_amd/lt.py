@@ -25,6 +25,7 @@ EXPORTS = [
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
     "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
+    "lt_reset_sequence", "lt_kv_bytes_paged", "lt_create_paged", "lt_set_block_table",
 ]
 
 
@@ -120,6 +121,14 @@ def load() -> ctypes.CDLL:
     lib.lt_truncate_layer.restype = ctypes.c_int
     lib.lt_probe_read.argtypes = [vp, sz, vp, vp]
     lib.lt_probe_read.restype = ctypes.c_int
+    lib.lt_reset_sequence.argtypes = [vp, i32]
+    lib.lt_reset_sequence.restype = ctypes.c_int
+    lib.lt_kv_bytes_paged.argtypes = [cfgp, vp, i32, i32]
+    lib.lt_kv_bytes_paged.restype = sz
+    lib.lt_create_paged.argtypes = [cfgp, vp, i32, i32, vp, sz, vp, sz, ctypes.POINTER(vp)]
+    lib.lt_create_paged.restype = ctypes.c_int
+    lib.lt_set_block_table.argtypes = [vp, vp, vp]
+    lib.lt_set_block_table.restype = ctypes.c_int
     lib.lt_status_str.argtypes = [ctypes.c_int]
     lib.lt_status_str.restype = ctypes.c_char_p
     _lib = lib
@@ -308,23 +317,33 @@ def kv_bytes_online(cfg: Config, n_full: int) -> int:
     return int(load().lt_kv_bytes_online(ctypes.byref(cfg), int(n_full)))
 
 
+def kv_bytes_paged(cfg: Config, is_lazy, page_tokens: int, n_pages: int) -> int:
+    mask = _mask_array(is_lazy)
+    return int(load().lt_kv_bytes_paged(ctypes.byref(cfg), mask.ctypes.data, int(page_tokens), int(n_pages)))
+
+
 class Context:
     """Owns the torch tensors used as KV slab and workspace, and the library's host-side context.
 
     With a lazy mask: lt_create.  With `n_full_online` instead: lt_create_online (layers take storage on
-    demand and turn lazy through truncate_layer)."""
+    demand and turn lazy through truncate_layer).  With a lazy mask and `paged=(page_tokens, n_pages)`:
+    lt_create_paged (full layers are pools of pages behind set_block_table)."""
 
-    def __init__(self, cfg: Config, is_lazy=None, device="cuda:0", n_full_online: Optional[int] = None, guard_bytes: int = 0):
+    def __init__(self, cfg: Config, is_lazy=None, device="cuda:0", n_full_online: Optional[int] = None, guard_bytes: int = 0,
+                 paged=None):
         lib = load()
         self.cfg = cfg
         online = n_full_online is not None
+        self.paged = tuple(int(x) for x in paged) if paged is not None else None
+        if online and self.paged:
+            raise ValueError("a context is either online or paged")
         if online:
             kvb = kv_bytes_online(cfg, n_full_online)
         else:
             self.is_lazy = _mask_array(is_lazy)
             if self.is_lazy.shape[0] != cfg.n_layers:
                 raise ValueError("is_lazy needs one entry per layer")
-            kvb = kv_bytes(cfg, self.is_lazy)
+            kvb = kv_bytes_paged(cfg, self.is_lazy, *self.paged) if self.paged else kv_bytes(cfg, self.is_lazy)
         wsb = workspace_bytes(cfg)
         if kvb == 0 or wsb == 0:
             raise LtError(ERR_INVALID_ARG, "lt_kv_bytes / lt_workspace_bytes")
@@ -345,6 +364,10 @@ class Context:
             st = lib.lt_create_online(ctypes.byref(cfg), int(n_full_online), self.kv_slab.data_ptr(), kvb,
                                       self.workspace.data_ptr(), wsb, ctypes.byref(handle))
             _check(st, "lt_create_online")
+        elif self.paged:
+            st = lib.lt_create_paged(ctypes.byref(cfg), self.is_lazy.ctypes.data, self.paged[0], self.paged[1],
+                                     self.kv_slab.data_ptr(), kvb, self.workspace.data_ptr(), wsb, ctypes.byref(handle))
+            _check(st, "lt_create_paged")
         else:
             st = lib.lt_create(ctypes.byref(cfg), self.is_lazy.ctypes.data, self.kv_slab.data_ptr(), kvb,
                                self.workspace.data_ptr(), wsb, ctypes.byref(handle))
@@ -359,6 +382,19 @@ class Context:
             return True
         bands = (self._slab_all[:g], self._slab_all[-g:], self._ws_all[:g], self._ws_all[-g:])
         return all(bool((b == 0xA5).all().item()) for b in bands)
+
+    def set_block_table(self, table, stream=None):
+        """table: int32 [B, max_pages] (host; numpy or CPU tensor), -1 = no page."""
+        if not self.paged:
+            raise LtError(ERR_STATE, "lt_set_block_table (context is not paged)")
+        max_pages = -(-int(self.cfg.max_tokens) // self.paged[0])
+        t = np.ascontiguousarray(np.asarray(table, dtype=np.int32))
+        if t.shape != (self.cfg.batch, max_pages):
+            raise LtError(ERR_SHAPE, "lt_set_block_table (table must be [B, ceil(max_tokens / page_tokens)])")
+        _check(load().lt_set_block_table(self._h, t.ctypes.data, _stream_ptr(stream)), "lt_set_block_table")
+
+    def reset_sequence(self, sequence: int):
+        _check(load().lt_reset_sequence(self._h, int(sequence)), "lt_reset_sequence")
 
     def truncate_layer(self, layer: int, stream=None):
         _check(load().lt_truncate_layer(self._h, int(layer), _stream_ptr(stream)), "lt_truncate_layer")
@@ -391,9 +427,12 @@ class Context:
                 "is_lazy": bool(lazy.value)}
 
     def layer_tensors(self, layer: int):
-        """Views of a layer's K and V blocks inside the slab: bf16 [B, Hkv, capacity, 128]."""
+        """Views of a layer's K and V blocks inside the slab: bf16 [B, Hkv, capacity, 128]; for a full layer
+        of a paged context its pools, bf16 [n_pages, Hkv, page_tokens, 128]."""
         view = self.layer_view(layer)
         shape = (self.cfg.batch, self.cfg.n_kv_heads, view["capacity"], self.cfg.head_dim)
+        if self.paged and not view["is_lazy"]:
+            shape = (self.paged[1], self.cfg.n_kv_heads, self.paged[0], self.cfg.head_dim)
         count = int(np.prod(shape))
         base = self.kv_slab.data_ptr()
         out = []

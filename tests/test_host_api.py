@@ -317,3 +317,65 @@ def test_online_context_sizes_and_slot_accounting():
     h = make_ctx(c, [0, 1, 0, 1])
     assert lib.lt_truncate_layer(h, 0, None) == lt.ERR_STATE
     lib.lt_destroy(h)
+
+
+def test_paged_context_sizes_and_argument_validation():
+    """Everything checked here happens on the host before any launch or copy."""
+    lib, c, mask = lt.load(), cfg(), [0, 1, 0, 1]
+    m = np.asarray(mask, np.uint8)
+    page, n_pages = 64, 40
+    max_pages = -(-1000 // page)
+    pool = n_pages * 2 * page * 128 * 2                              # bf16 [n_pages][Hkv][page][128]
+    ring = 2 * 2 * 64 * 128 * 2                                      # bf16 [B][Hkv][w_sink + w_recent][128]
+    table = -(-(2 * max_pages * 4) // 256) * 256
+    assert lt.kv_bytes_paged(c, mask, page, n_pages) == table + 2 * 2 * pool + 2 * 2 * ring
+    for bad_page in (0, 32, 96, 1 << 21):
+        assert lt.kv_bytes_paged(c, mask, bad_page, n_pages) == 0
+    assert lt.kv_bytes_paged(c, mask, page, 0) == 0
+    assert lt.kv_bytes_paged(cfg(batch=65), mask, page, n_pages) == 0
+
+    def create(conf, pg, npg, kvb=None):
+        handle = ctypes.c_void_p()
+        kvb = lt.kv_bytes_paged(conf, mask, pg, npg) if kvb is None else kvb
+        st = lib.lt_create_paged(ctypes.byref(conf), m.ctypes.data, pg, npg, FAKE_DEV, kvb, FAKE_DEV + (1 << 34),
+                                 lt.workspace_bytes(conf), ctypes.byref(handle))
+        return st, handle
+
+    assert create(c, 96, n_pages, 1 << 30)[0] == lt.ERR_SHAPE
+    assert create(c, -1, n_pages, 1 << 30)[0] == lt.ERR_INVALID_ARG
+    assert create(c, page, n_pages, lt.kv_bytes_paged(c, mask, page, n_pages) - 1)[0] == lt.ERR_CAPACITY
+    # 512 ranges of at most 255 pages of 64 tokens: longer contexts need larger pages
+    long_c = cfg(max_tokens=512 * 255 * 64 + 1)
+    assert create(long_c, 64, n_pages, 1 << 40)[0] == lt.ERR_SHAPE
+    assert create(long_c, 128, n_pages)[0] == lt.OK
+    st, h = create(c, page, n_pages)
+    assert st == lt.OK
+    k, v = ctypes.c_void_p(), ctypes.c_void_p()
+    sb, sh, cap, lazy = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int32()
+    assert lib.lt_layer_view(h, 0, ctypes.byref(k), ctypes.byref(v), ctypes.byref(sb), ctypes.byref(sh), ctypes.byref(cap),
+                             ctypes.byref(lazy)) == lt.OK
+    assert (sb.value, sh.value, cap.value, lazy.value) == (2 * page * 128, page * 128, max_pages * page, 0)
+    assert (k.value, v.value) == (FAKE_DEV + table, FAKE_DEV + table + pool)   # the pools follow the table
+    # no page, no append; entries outside the pool are refused; both before anything is enqueued
+    assert lib.lt_append_kv(h, 0, FAKE_DEV, FAKE_DEV, 5, None) == lt.ERR_STATE
+    assert lib.lt_append_kv(h, 1, FAKE_DEV, FAKE_DEV, 2000, None) != lt.ERR_STATE    # a lazy layer needs no pages
+    bad = np.full((2, max_pages), -1, np.int32)
+    bad[1, 3] = n_pages
+    assert lib.lt_set_block_table(h, bad.ctypes.data, None) == lt.ERR_INVALID_ARG
+    bad[1, 3] = -2
+    assert lib.lt_set_block_table(h, bad.ctypes.data, None) == lt.ERR_INVALID_ARG
+    assert lib.lt_set_block_table(h, None, None) == lt.ERR_INVALID_ARG
+    assert lib.lt_truncate_layer(h, 0, None) == lt.ERR_STATE
+    assert lib.lt_reset_sequence(h, 2) == lt.ERR_INVALID_ARG
+    assert lib.lt_reset_sequence(h, 1) == lt.OK
+    lib.lt_destroy(h)
+    plain = make_ctx(c, mask)
+    ok = np.zeros((2, max_pages), np.int32)
+    assert lib.lt_set_block_table(plain, ok.ctypes.data, None) == lt.ERR_STATE
+    assert lib.lt_reset_sequence(plain, 0) == lt.OK                  # also works on a contiguous context
+    lib.lt_destroy(plain)
+    online = ctypes.c_void_p()
+    assert lib.lt_create_online(ctypes.byref(c), 2, FAKE_DEV, lt.kv_bytes_online(c, 2), FAKE_DEV + (1 << 34),
+                                lt.workspace_bytes(c), ctypes.byref(online)) == lt.OK
+    assert lib.lt_reset_sequence(online, 0) == lt.ERR_STATE
+    lib.lt_destroy(online)
