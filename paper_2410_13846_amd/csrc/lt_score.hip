@@ -27,6 +27,9 @@ struct LaneState {
 };
 
 // Uniform description of a 32-key sub-tile relative to the masks.
+// s_waitcnt immediate for gfx9: vmcnt = 0 (bits 3:0 and 15:14), expcnt and lgkmcnt left at their maxima
+constexpr int kWaitVmcnt0 = 0x0F70;
+
 struct TileClass {
     bool fast;      // every (key, query) pair is causal and the kept/dropped decision is the same for all pairs
     bool kept;      // on the fast path: all pairs are kept
@@ -65,6 +68,25 @@ __device__ __forceinline__ void update_fast(const floatx16_t &c, LaneState &st, 
     st.sum_causal = st.sum_causal * alpha + sum;
     st.sum_kept = st.sum_kept * alpha + (kept ? sum : 0.f);
     st.m = m_new;
+}
+
+// The same without looking for the maximum: the exponentials are formed against the lane's current
+// reference and the sub-tile is taken only if their sum stays within 2^12 in every lane (16 terms of at most
+// 2^8).  A larger sum, or a NaN while there is no reference yet, sends the whole wavefront through
+// update_fast, which moves the reference.  Any reference gives the same quotient of the two sums; the two
+// half-wavefronts and the key ranges are merged later by their references.
+constexpr float kQuickSumLimit = 4096.f;
+__device__ __forceinline__ void update_quick(const floatx16_t &c, LaneState &st, float scale_log2e, bool kept)
+{
+    float sum = 0.f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) sum += fast_exp2(fmaf(c[i], scale_log2e, -st.m));
+    if (__all(sum <= kQuickSumLimit)) {
+        st.sum_causal += sum;
+        st.sum_kept += kept ? sum : 0.f;
+    } else {
+        update_fast(c, st, scale_log2e, kept);
+    }
 }
 
 __device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st, float scale_log2e, int j_base,
@@ -170,6 +192,11 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
         }
     }
 
+    // The query fragments must have arrived on every path into the tile loop: otherwise the compiler, which
+    // cannot tell how many newer loads may be outstanding, makes the first matrix instruction of EVERY tile wait
+    // for all outstanding loads, the K prefetch issued just before it included.
+    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+
     LaneState st[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { st[nt].m = -INFINITY; st[nt].sum_causal = 0.f; st[nt].sum_kept = 0.f; }
@@ -193,7 +220,7 @@ __global__ __launch_bounds__(64 * G, 2) void lt_lazy_ratio_partial_kernel(ScoreA
         const TileClass cls = classify(j0, n, a.w_last, w_sink, w_recent, a.fixed_mode);
         if (cls.fast) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) update_fast(c[nt], st[nt], a.scale_log2e, cls.kept);
+            for (int nt = 0; nt < NT; ++nt) update_quick(c[nt], st[nt], a.scale_log2e, cls.kept);
         } else {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) {
