@@ -157,3 +157,44 @@ def test_bf16_output_is_the_rounded_fp32_output(group, lazy):
         outs[dtype] = out
         ctx.close()
     assert torch.equal(outs[torch.float32].to(torch.bfloat16), outs[torch.bfloat16])       # same bits: round to nearest even
+
+
+def test_reset_sequence_frees_a_slot_for_a_new_prompt():
+    """A contiguous context: one sequence ends, its slot takes a new prompt (shorter than the ring, then growing
+    past it) while the others go on; every sequence is checked against the oracle over its own history."""
+    B, Hq, Hkv, ws, wr = 3, 8, 2, 4, 28
+    cfg = lt.make_config(2, B, Hq, Hkv, 128, ws, wr, 400)
+    is_lazy = [0, 1]
+    ctx = lt.Context(cfg, is_lazy, DEV)
+    hists = [oracle.History(2, is_lazy, ws, wr) for _ in range(B)]
+
+    def append(counts, seed):
+        n_max = max(max(counts), 1)
+        for layer in range(2):
+            k = randn_bf16((B, Hkv, n_max, 128), seed + 10 * layer)
+            v = randn_bf16((B, Hkv, n_max, 128), seed + 10 * layer + 1)
+            ctx.append_kv_ragged(layer, k, v, counts)
+            for b in range(B):
+                if counts[b] > 0:
+                    hists[b].append(layer, bits(k[b:b + 1, :, :counts[b]]), bits(v[b:b + 1, :, :counts[b]]))
+
+    def check(seed):
+        for layer in range(2):
+            q = randn_bf16((B, Hq, 128), seed + layer)
+            out, lse = ctx.decode_attn(layer, q, want_lse=True)
+            for b in range(B):
+                ref, ref_lse = hists[b].decode(layer, bits(q[b:b + 1]))
+                assert np.abs(f64(out[b:b + 1]) - ref).max() <= TOL_OUT
+                assert np.abs(f64(lse[b:b + 1]) - ref_lse).max() <= TOL_LSE
+
+    append([120, 75, 33], 8700)
+    check(8710)
+    ctx.reset_sequence(1)
+    assert ctx.seq_len(0, 1) == (0, 0) and ctx.seq_len(1, 1) == (0, 0) and ctx.seq_len(0, 0) == (120, 120)
+    hists[1] = oracle.History(2, is_lazy, ws, wr)
+    append([0, 9, 0], 8720)                                    # shorter than the ring: old ring entries must not show
+    check(8730)
+    append([1, 40, 1], 8740)                                   # the new sequence wraps its ring; the others step on
+    check(8750)
+    assert ctx.seq_len(1, 1) == (49, ws + wr) and ctx.layer_len(0)[0] == 121
+    ctx.close()
