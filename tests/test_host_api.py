@@ -379,3 +379,30 @@ def test_paged_context_sizes_and_argument_validation():
                                 lt.workspace_bytes(c), ctypes.byref(online)) == lt.OK
     assert lib.lt_reset_sequence(online, 0) == lt.ERR_STATE
     lib.lt_destroy(online)
+
+
+def test_product_path_has_no_oracle_and_no_fallback(tmp_path, monkeypatch):
+    """The package never touches oracle/ (nor does the input generator or the oracle the package), and a missing
+    library with no compiler is an error, not a silent CPU path."""
+    import subprocess
+    import sys
+
+    uses_oracle = re.compile(r"^\s*(import|from)\s+oracle\b|lt_oracle|liblto", re.M)
+    pkg = os.path.join(ROOT, "paper_2410_13846_amd")
+    for folder, _, files in os.walk(pkg):
+        for name in files:
+            if name.endswith((".py", ".cpp", ".hip", ".h")):
+                assert not uses_oracle.search(open(os.path.join(folder, name)).read()), name
+    assert not uses_oracle.search(open(os.path.join(ROOT, "lt_workloads.py")).read())
+    for name in os.listdir(os.path.join(ROOT, "oracle")):
+        if name.endswith((".py", ".c", ".h")):
+            assert "paper_2410_13846_amd" not in open(os.path.join(ROOT, "oracle", name)).read(), name
+    probe = ("import sys; sys.path.insert(0, %r)\n"
+             "import paper_2410_13846_amd.build as b\n"
+             "b.LIB_PATH = %r\n"
+             "from paper_2410_13846_amd import lt\n"
+             "try:\n    lt.load()\nexcept Exception as e:\n    print('raised', type(e).__name__)\nelse:\n    print('loaded')\n"
+             ) % (ROOT, str(tmp_path / "absent" / "liblt_hip.so"))
+    env = dict(os.environ, HIPCC=str(tmp_path / "no_such_hipcc"))
+    out = subprocess.run([sys.executable, "-c", probe], env=env, capture_output=True, text=True, timeout=120)
+    assert out.stdout.strip().startswith("raised"), out.stdout + out.stderr
