@@ -357,9 +357,17 @@ def prefill_bench(args, lt, W, wl, dev):
         rows.append(row)
         del q, k, v, out, lse, res
         torch.cuda.empty_cache()
-    return {"metric": "prefill attention and lazy ratio from its log-sum-exp, per layer", "n_gpus": 1, "data": "synthetic",
+    mean_ms = float(np.mean([r["causal_ms"] for r in rows]))
+    flops = 4.0 * wl.batch * wl.n_q_heads * wl.head_dim * n * (n + 1) / 2.0
+    achieved = flops / mean_ms / 1e9
+    return {"metric": "prefill attention and lazy ratio from its log-sum-exp, per layer", "value": mean_ms, "unit": "ms per layer (causal prefill attention)",
+            "higher_is_better": False, "n_gpus": 1, "data": "synthetic",
             "dtype": "bf16 operands, fp32 accumulate", "config": {"workload": wl.name, "batch": wl.batch, "q_heads": wl.n_q_heads,
-            "kv_heads": wl.n_kv_heads, "context": n, "w_sink": wl.w_sink, "w_recent": wl.w_recent, "w_last": w}, "layers": rows}
+            "kv_heads": wl.n_kv_heads, "context": n, "w_sink": wl.w_sink, "w_recent": wl.w_recent, "w_last": w},
+            "roofline": {"bound": "mfma", "kernel": "lt_prefill_attn_kernel<%d, *> (causal mask)" % wl.group, "achieved": achieved,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": achieved / MFMA_BF16_PEAK_TFLOPS, "traffic": None,
+                         "flops_per_launch": flops, "avg_launch_us": mean_ms * 1e3},
+            "layers": rows}
 
 
 def paged_bench(args, lt, W, wl, dev):
