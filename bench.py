@@ -240,6 +240,8 @@ def growth_curve(args, lt, W, wl, dev):
     is_lazy = [1 if l in W.planted_lazy_layers(wl) else 0 for l in range(wl.n_layers)]
     cfg = lt.make_config(wl.n_layers, wl.batch, wl.n_q_heads, wl.n_kv_heads, wl.head_dim, wl.w_sink, wl.w_recent, final)
     ctx = lt.Context(cfg, is_lazy, dev)
+    if args.keys_full or args.keys_lazy:
+        ctx.set_split(args.keys_full, args.keys_lazy)
     lib, h = lt.load(), ctx._h
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     K = args.steps
