@@ -78,12 +78,18 @@ def history_of(wl, layer, b, steps_done):
     return np.concatenate(ks, axis=2), np.concatenate(vs, axis=2)
 
 
-def run_sampled(wl, layers, is_lazy, samples, steps, score_samples=()):
+def run_sampled(wl, layers, is_lazy, samples, steps, score_samples=(), page_tokens=0):
     """Fill the stack for `layers` (indices into the workload's recipe), decode `steps` tokens with the
-    fused step, and check the sampled (position in `layers`, sequence) pairs at the last step."""
+    fused step, and check the sampled (position in `layers`, sequence) pairs at the last step.
+    With page_tokens the full layers are paged behind a shuffled block table, as bench.py --paged runs them."""
     sub = wl.scaled(n_layers=len(layers), decode_steps=steps)
     cfg = make_cfg(sub)
-    ctx = lt.Context(cfg, is_lazy, DEV)
+    if page_tokens:
+        max_pages = -(-int(cfg.max_tokens) // page_tokens)
+        ctx = lt.Context(cfg, is_lazy, DEV, paged=(page_tokens, wl.batch * max_pages))
+        ctx.set_block_table(np.random.default_rng(7).permutation(wl.batch * max_pages).astype(np.int32).reshape(wl.batch, max_pages))
+    else:
+        ctx = lt.Context(cfg, is_lazy, DEV)
     for i, layer in enumerate(layers):
         say(wl.name, "prefill layer", layer)
         k, v = W.prefill_kv(wl, layer, DEV)
@@ -138,6 +144,20 @@ def test_llama3_8b_32k_shapes_sampled():
     layers = [full_layers[0], lazy_layers[0], full_layers[-1], lazy_layers[-1]]
     run_sampled(wl, layers, [0, 1, 0, 1], samples=[(0, 0), (1, 3), (2, 7), (3, 5)], steps=3,
                 score_samples=[(0, 2, 1), (1, 6, 7)])
+
+
+def test_llama3_8b_32k_paged_shapes_sampled():
+    """The same shape with the full layers in pages of 256 tokens handed out in a random order (bench.py --paged 256)."""
+    wl = W.WORKLOADS["llama3_8b_32k"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layers = [l for l in range(wl.n_layers) if l not in lazy_layers]
+    run_sampled(wl, [full_layers[1], lazy_layers[1]], [0, 1], samples=[(0, 2), (0, 7), (1, 4)], steps=3, page_tokens=256)
+
+
+def test_mistral_7b_16k_paged_shapes_sampled():
+    """Batch 32, context 16384, pages of 64 tokens: one workgroup's key range spans all four page registers."""
+    wl = W.WORKLOADS["mistral_7b_16k"]
+    run_sampled(wl, [5], [0], samples=[(0, 0), (0, 29)], steps=2, page_tokens=64)
 
 
 def test_mistral_7b_16k_shapes_sampled():
