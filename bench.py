@@ -54,6 +54,9 @@ def parse_args():
                     help="long-generation curve: fixed lazy mask, decode from the prompt length up to the workload's "
                          "final length, timing --steps decode steps at each doubling of the history (the tokens in "
                          "between are bulk-appended); reports tokens/s against generated length")
+    ap.add_argument("--whole-run", action="store_true",
+                    help="with --growth: decode every step of the generation (prompt to final length) instead of sampling "
+                         "the curve; decode inputs cycle through a pool of --steps pre-generated steps")
     ap.add_argument("--paged", type=int, default=0, metavar="PAGE_TOKENS",
                     help="compare the stack with its full layers stored in pages of this many tokens (shuffled block table) "
                          "against the contiguous stack; prints its own JSON line")
@@ -268,6 +271,48 @@ def growth_curve(args, lt, W, wl, dev):
                                         out[layer].data_ptr(), None, stream)
                 if st != 0:
                     raise lt.LtError(st, "lt_decode_step")
+
+    if args.whole_run:
+        # the whole generation, step by step: every launch sees the history length it would see in a real run
+        grow_to(wl.context)
+        decode(min(K, 4))
+        torch.cuda.synchronize()
+        T_start = ctx.layer_len(0)[0]
+        bins, edges = [], []
+        T = 2048
+        while T < final:
+            edges.append(T)
+            T *= 2
+        edges.append(final)
+        t_begin = time.perf_counter()
+        done, T_now = 0, T_start
+        for edge in edges:
+            n_steps = edge - T_now
+            if n_steps <= 0:
+                continue
+            t0 = time.perf_counter()
+            left = n_steps
+            while left > 0:                            # the input pool is cycled; values do not matter for the timing
+                chunk = min(left, K)
+                decode(chunk)
+                left -= chunk
+            torch.cuda.synchronize()
+            dt = time.perf_counter() - t0
+            bins.append({"history_from": T_now, "history_to": edge, "steps": n_steps, "seconds": dt,
+                         "ms_per_step": dt / n_steps * 1e3, "tokens_per_s": wl.batch * n_steps / dt})
+            log("T %6d..%6d: %6d steps in %.2f s, %.3f ms/step, %.0f tokens/s" % (T_now, edge, n_steps, dt, dt / n_steps * 1e3, wl.batch * n_steps / dt))
+            done += n_steps
+            T_now = edge
+        total = time.perf_counter() - t_begin
+        ctx.close()
+        total_bytes = sum(W.kv_bytes_per_step(wl, is_lazy, t) for t in range(T_start + 1, final + 1, 64)) * 64.0
+        return {"metric": "whole generation at a fixed lazy mask: decode tokens/s", "value": wl.batch * done / total, "unit": "tokens/s",
+                "n_gpus": 1, "steps": done, "seconds": total, "launches": done * wl.n_layers, "higher_is_better": True, "data": "synthetic",
+                "kv_gbs": total_bytes / total / 1e9, "kv_hbm_frac": total_bytes / total / 1e9 / HBM_PEAK_GBS,
+                "config": {"workload": wl.name, "layers": wl.n_layers, "lazy_layers": int(sum(is_lazy)), "batch": wl.batch,
+                           "q_heads": wl.n_q_heads, "kv_heads": wl.n_kv_heads, "w_sink": wl.w_sink, "w_recent": wl.w_recent,
+                           "history_first_step": T_start + 1, "history_last_step": final},
+                "bins": bins}
 
     points, T = [], wl.context
     targets = []
