@@ -369,12 +369,15 @@ lt_status lt_create_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t 
     return LT_OK;
 }
 
-// Pages a sequence needs for `tokens` tokens are all present in the host copy of the block table.
-static bool pages_cover(const lt_ctx *ctx, int32_t sequence, int64_t tokens)
+// The pages that tokens [have, want) of a sequence fall into are present in the host copy of the block table.
+// (The pages of tokens below `have` were checked when those tokens arrived, and lt_set_block_table refuses a
+// table that drops them.)
+static bool pages_cover(const lt_ctx *ctx, int32_t sequence, int64_t have, int64_t want)
 {
-    const int64_t pages = (tokens + ((int64_t)1 << ctx->page_shift) - 1) >> ctx->page_shift;
-    if (pages > ctx->max_pages) return false;
-    for (int64_t p = 0; p < pages; ++p)
+    if (want <= have) return true;
+    const int64_t first = have >> ctx->page_shift, last = (want - 1) >> ctx->page_shift;
+    if (last >= ctx->max_pages) return false;
+    for (int64_t p = first; p <= last; ++p)
         if (ctx->table_host[(size_t)sequence * ctx->max_pages + p] < 0) return false;
     return true;
 }
@@ -741,7 +744,7 @@ static lt_status append_impl(lt_ctx *ctx, int32_t layer, const void *k_new, cons
     if (!l.lazy && longest_after > l.capacity) return LT_ERR_CAPACITY;
     if (ctx->paged && !l.lazy)
         for (int b = 0; b < B; ++b)
-            if (!pages_cover(ctx, b, l.total_b[b] + (n_per_seq != nullptr ? n_per_seq[b] : n_new))) return LT_ERR_STATE;
+            if (!pages_cover(ctx, b, l.total_b[b], l.total_b[b] + (n_per_seq != nullptr ? n_per_seq[b] : n_new))) return LT_ERR_STATE;
     if (ragged && l.total_b.empty()) {
         try {
             l.total_b.assign((size_t)B, l.total);
@@ -844,7 +847,7 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     const bool paged = ctx->paged && !l.lazy;
     if (paged && fused)
         for (int b = 0; b < c.batch; ++b)
-            if (!pages_cover(ctx, b, l.total_b[b] + 1)) return LT_ERR_STATE;   // the new token has no page yet
+            if (!pages_cover(ctx, b, l.total_b[b], l.total_b[b] + 1)) return LT_ERR_STATE;   // the new token has no page yet
 
     ltk::DecodeArgs a{};
     a.k_cache = l.k;
