@@ -210,11 +210,6 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
         }
     }
 
-    // The query fragments must have arrived on every path into the tile loop: otherwise the compiler, which
-    // cannot tell how many newer loads may be outstanding, makes the first matrix instruction of EVERY sub-tile
-    // wait for all outstanding loads, the next tile's prefetch issued just before it included.
-    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0); expcnt and lgkmcnt left at their maxima
-
     floatx16_t acc[4][NT];                     // O^T: [32-dim tile][32-query tile]
 #pragma unroll
     for (int dt = 0; dt < 4; ++dt)
@@ -382,6 +377,11 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     };
 
     prefetch(0);
+    // The query fragments must have arrived on every path into the tile loop: otherwise the compiler, which
+    // cannot tell how many newer loads may be outstanding, makes the first matrix instruction of EVERY sub-tile
+    // wait for all outstanding loads, the next tile's prefetch issued just before it included.  Placed after the
+    // first tile's loads were issued, the wait costs nothing: park(0) needs those loads next anyway.
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0); expcnt and lgkmcnt left at their maxima
     park(0);
     // The accumulator is multiplied only in the outer loop; the inner loop, which runs until some
     // row's maximum outgrows its reference, touches it with matrix instructions alone, so it can
