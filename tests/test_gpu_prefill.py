@@ -189,3 +189,42 @@ def test_chunked_prefill_through_the_cache_chunk_by_chunk(group):
     ref_rho, _, ref_r = oracle.lazy_ratio(bits(q_last), bits(k), ws, wr)
     assert np.abs(f64(rho) - ref_rho).max() <= TOL_RATIO and abs(float(mean.cpu()[0]) - ref_r) <= TOL_RATIO
     ctx.close()
+
+
+# ---- logits that climb or fall steadily: the softmax reference of the fast paths must follow ---------------
+
+def ramp_inputs(B, Hq, Hkv, n, slope, seed):
+    """Keys along one direction u with a coefficient that grows linearly with the position (plus noise), queries
+    along u: the logit of key j is about slope * j / n natural units, so the row maximum keeps growing (slope > 0:
+    the reference has to move again and again, early keys underflow) or the first keys dominate (slope < 0)."""
+    g = torch.Generator(device=DEV).manual_seed(seed)
+    u = torch.randn(128, generator=g, device=DEV)
+    u = u / u.norm()
+    coeff = torch.arange(n, device=DEV, dtype=torch.float32) / n * slope            # q.k * scale = coeff
+    k = coeff[None, None, :, None] * u * (128 ** 0.25) + 0.05 * torch.randn(B, Hkv, n, 128, generator=g, device=DEV)
+    q = (u * (128 ** 0.25)).expand(B, Hq, n, 128) + 0.05 * torch.randn(B, Hq, n, 128, generator=g, device=DEV)
+    v = torch.randn(B, Hkv, n, 128, generator=g, device=DEV)
+    return q.bfloat16().contiguous(), k.bfloat16().contiguous(), v.bfloat16().contiguous()
+
+
+@pytest.mark.parametrize("slope", [400.0, 60.0, -60.0, -400.0])
+@pytest.mark.parametrize("mask", [lt.MASK_CAUSAL, lt.MASK_STREAMING])
+def test_steadily_growing_or_falling_logits(slope, mask):
+    B, Hq, Hkv, n, ws, wr, w = 1, 4, 1, 1500, 4, 252, 64
+    say("ramp case", dict(slope=slope, mask=mask))
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, ws, wr, n)
+    q, k, v = ramp_inputs(B, Hq, Hkv, n, slope, 7300 + int(abs(slope)))
+    out, lse = lt.prefill_attn(cfg, q, k, v, n, mask, out_dtype=torch.float32)
+    mode = oracle.MODE_LAZY if mask == lt.MASK_STREAMING else oracle.MODE_FULL
+    ref, ref_lse, absw = oracle.prefill_attn(bits(q), bits(k), bits(v), mode, ws, wr, return_absw=True)
+    assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+    assert (np.abs(f64(out) - ref) / out_tolerance(absw, ref, torch.float32)).max() <= 1.0
+    assert np.abs(f64(lse) - ref_lse).max() <= TOL_PREFILL_LSE * max(1.0, abs(slope) / 60.0)   # lse itself is of the order of slope
+    if mask == lt.MASK_CAUSAL:                                   # both forms of the lazy ratio on the same prompt
+        q_last = q[:, :, n - w:].contiguous()
+        ref_rho, _, ref_r = oracle.lazy_ratio(bits(q_last), bits(k), ws, wr)
+        mean_d, _, rho_d = lt.lazy_ratio(cfg, q_last, k, n, w, want_rho=True)
+        assert np.abs(f64(rho_d) - ref_rho).max() <= TOL_RATIO and abs(float(mean_d.cpu()[0]) - ref_r) <= TOL_RATIO
+        mean_l, _, rho_l = lt.lazy_ratio_lse(cfg, q_last, k, n, w, lse[:, :, n - w:], want_rho=True)
+        log_rho, _, _ = oracle.lazy_ratio_from_lse(bits(q_last), bits(k), f64(lse[:, :, n - w:]), ws, wr)
+        assert np.abs(f64(rho_l) - np.exp(log_rho)).max() <= TOL_RATIO
