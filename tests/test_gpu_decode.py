@@ -181,3 +181,31 @@ def test_error_paths_on_the_device():
     ctx.reset()
     assert ctx.layer_len(1) == (0, 0)
     ctx.close()
+
+
+@pytest.mark.parametrize("slope", [500.0, -500.0, 40.0])
+def test_steadily_growing_or_falling_logits_across_splits(slope):
+    """Logits that climb (or fall) by hundreds of natural units over the history: whole key ranges carry a weight
+    that underflows against the others in the merge, row maxima move in almost every tile of the climbing case."""
+    B, Hq, Hkv, T, ws, wr = 2, 8, 2, 3000, 4, 252
+    say("decode ramp", slope)
+    g = torch.Generator(device=DEV).manual_seed(6500 + int(abs(slope)))
+    u = torch.randn(128, generator=g, device=DEV)
+    u = u / u.norm()
+    coeff = torch.arange(T, device=DEV, dtype=torch.float32) / T * slope            # q.k * scale = coeff
+    k = (coeff[None, None, :, None] * u * (128 ** 0.25) + 0.05 * torch.randn(B, Hkv, T, 128, generator=g, device=DEV)).bfloat16()
+    v = torch.randn(B, Hkv, T, 128, generator=g, device=DEV).bfloat16()
+    q = ((u * (128 ** 0.25)).expand(B, Hq, 128) + 0.05 * torch.randn(B, Hq, 128, generator=g, device=DEV)).bfloat16().contiguous()
+    cfg = lt.make_config(2, B, Hq, Hkv, 128, ws, wr, T + 4)
+    ctx = lt.Context(cfg, [0, 1], DEV)
+    ctx.set_split(256, 128)                                     # a dozen key ranges per sequence and head
+    hist = oracle.History(2, [0, 1], ws, wr)
+    for layer in range(2):
+        ctx.append_kv(layer, k.contiguous(), v.contiguous())
+        hist.append(layer, bits(k), bits(v))
+        out, lse = ctx.decode_attn(layer, q, want_lse=True)
+        ref, ref_lse = hist.decode(layer, bits(q))
+        assert torch.isfinite(out).all() and torch.isfinite(lse).all()
+        assert np.abs(f64(out) - ref).max() <= TOL_OUT
+        assert np.abs(f64(lse) - ref_lse).max() <= TOL_LSE
+    ctx.close()
