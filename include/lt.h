@@ -319,6 +319,15 @@ lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, void *out, f
 lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
                          float *lse_out, void *stream);
 
+/* lt_decode_step for the sequences that are still generating (serving: others have finished or their
+ * slot is empty).  active_host: host, uint8 [B], non-zero = takes part.  A sequence that sits the step out
+ * gets no token, keeps its length, is not read at all, and its rows of out / lse_out are 0 / -inf.  Turns
+ * the context into the per-sequence mode of lt_append_kv_ragged.  LT_ERR_SHAPE if batch > 64; LT_ERR_STATE on
+ * a context made by lt_create_online, and when no active sequence has anything to attend over;
+ * LT_ERR_CAPACITY / (paged) LT_ERR_STATE look at the active sequences only. */
+lt_status lt_decode_step_active(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                                const uint8_t *active_host, void *out, float *lse_out, void *stream);
+
 /* ---- tuning and measurement ---------------------------------------------------------------- */
 
 /* Keys one workgroup of the split decode kernel handles in full / lazy layers (multiples of 64);

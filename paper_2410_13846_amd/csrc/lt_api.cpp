@@ -831,30 +831,53 @@ static int64_t slot_of(const lt_config &c, const Layer &l, int64_t p)
 
 // One launch: optional on-the-fly append of this step's token, split attention, merge.
 static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
-                               float *lse_out, void *stream)
+                               float *lse_out, const uint8_t *active, void *stream)
 {
     if (ctx == nullptr || q == nullptr || out == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
     if (((uintptr_t)q % 16) != 0 || ((uintptr_t)k_new % 16) != 0 || ((uintptr_t)v_new % 16) != 0) return LT_ERR_INVALID_ARG;
     Layer &l = ctx->layers[layer];
     const lt_config &c = ctx->cfg;
     const bool fused = k_new != nullptr;
-    if (fused && (l.total + 1 > kMaxTokens || (!l.lazy && l.total + 1 > l.capacity))) return LT_ERR_CAPACITY;
-    const int64_t total = l.total + (fused ? 1 : 0);
-    const int64_t stored = std::min(total, l.capacity);
-    if (stored <= 0) return LT_ERR_STATE;
+    if (active != nullptr) {                    // a step that skips some sequences needs a length per sequence
+        if (ctx->online) return LT_ERR_STATE;
+        if (c.batch > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
+        if (l.total_b.empty()) {
+            try {
+                l.total_b.assign((size_t)c.batch, l.total);
+            } catch (const std::bad_alloc &) {
+                return LT_ERR_NOMEM;
+            }
+        }
+    }
     const bool ragged = !l.total_b.empty();
     if (ragged && c.batch > ltk::kMaxRaggedBatch) return LT_ERR_SHAPE;
+    auto takes_part = [&](int b) { return active == nullptr || active[b] != 0; };
+    // the longest history any sequence of this launch attends over, after the step's token
+    int64_t total = l.total + (fused ? 1 : 0);
+    if (ragged) {
+        total = 0;
+        for (int b = 0; b < c.batch; ++b)
+            if (takes_part(b)) total = std::max(total, l.total_b[b] + (fused ? 1 : 0));
+    }
+    if (fused && (total > kMaxTokens || (!l.lazy && total > l.capacity))) return LT_ERR_CAPACITY;
+    const int64_t stored = std::min(total, l.capacity);
+    if (stored <= 0) return LT_ERR_STATE;
     const bool paged = ctx->paged && !l.lazy;
     if (paged && fused)
         for (int b = 0; b < c.batch; ++b)
-            if (!pages_cover(ctx, b, l.total_b[b], l.total_b[b] + 1)) return LT_ERR_STATE;   // the new token has no page yet
+            if (takes_part(b) && !pages_cover(ctx, b, l.total_b[b], l.total_b[b] + 1)) return LT_ERR_STATE;   // the new token has no page yet
 
     ltk::DecodeArgs a{};
     a.k_cache = l.k;
     a.v_cache = l.v;
-    const int64_t slot = fused ? slot_of(c, l, l.total) : -1;
-    a.k_new = slot >= 0 ? static_cast<const uint16_t *>(k_new) : nullptr;     // a dropped token is simply not stored
-    a.v_new = slot >= 0 ? static_cast<const uint16_t *>(v_new) : nullptr;
+    int64_t slot = fused ? slot_of(c, l, l.total) : -1;
+    bool any_stored = slot >= 0;
+    if (ragged && fused) {
+        any_stored = false;
+        for (int b = 0; b < c.batch; ++b) any_stored = any_stored || (takes_part(b) && slot_of(c, l, l.total_b[b]) >= 0);
+    }
+    a.k_new = any_stored ? static_cast<const uint16_t *>(k_new) : nullptr;    // a dropped token is simply not stored
+    a.v_new = any_stored ? static_cast<const uint16_t *>(v_new) : nullptr;
     a.new_slot = (int32_t)slot;
     a.tickets = ctx->tickets;
     a.q = static_cast<const uint16_t *>(q);
@@ -889,8 +912,9 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     if (ragged)
         for (int b = 0; b < c.batch; ++b) {
             const int64_t total_b = l.total_b[b] + (fused ? 1 : 0);
-            per_seq.stored_b[b] = (int32_t)std::min(total_b, l.capacity);
-            per_seq.new_slot_b[b] = fused ? (int32_t)slot_of(c, l, l.total_b[b]) : -1;
+            // a sequence that sits this step out looks empty to the kernel: nothing read, nothing stored, out = 0
+            per_seq.stored_b[b] = takes_part(b) ? (int32_t)std::min(total_b, l.capacity) : 0;
+            per_seq.new_slot_b[b] = fused && takes_part(b) ? (int32_t)slot_of(c, l, l.total_b[b]) : -1;
         }
     hipStream_t s = static_cast<hipStream_t>(stream);
     if (!ctx->tickets_ready) {
@@ -907,22 +931,33 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
         }
         if (ltk::decode(a, ragged && !paged ? &per_seq : nullptr, paged ? &paged_args : nullptr, s) != hipSuccess) return LT_ERR_HIP;
     }
-    l.total = total;
-    if (ragged && fused)
-        for (int b = 0; b < c.batch; ++b) l.total_b[b] += 1;
+    if (ragged) {
+        if (fused)
+            for (int b = 0; b < c.batch; ++b) l.total_b[b] += takes_part(b) ? 1 : 0;
+        l.total = *std::max_element(l.total_b.begin(), l.total_b.end());
+    } else {
+        l.total = total;
+    }
     return LT_OK;
 }
 
 lt_status lt_decode_attn(lt_ctx *ctx, int32_t layer, const void *q, void *out, float *lse_out, void *stream)
 {
-    return launch_decode(ctx, layer, q, nullptr, nullptr, out, lse_out, stream);
+    return launch_decode(ctx, layer, q, nullptr, nullptr, out, lse_out, nullptr, stream);
 }
 
 lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new, void *out,
                          float *lse_out, void *stream)
 {
     if (k_new == nullptr || v_new == nullptr) return LT_ERR_INVALID_ARG;
-    return launch_decode(ctx, layer, q, k_new, v_new, out, lse_out, stream);
+    return launch_decode(ctx, layer, q, k_new, v_new, out, lse_out, nullptr, stream);
+}
+
+lt_status lt_decode_step_active(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
+                                const uint8_t *active_host, void *out, float *lse_out, void *stream)
+{
+    if (k_new == nullptr || v_new == nullptr || active_host == nullptr) return LT_ERR_INVALID_ARG;
+    return launch_decode(ctx, layer, q, k_new, v_new, out, lse_out, active_host, stream);
 }
 
 // ---- online identification during prefill ------------------------------------------------------

@@ -25,7 +25,7 @@ EXPORTS = [
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
     "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
-    "lt_reset_sequence", "lt_kv_bytes_paged", "lt_create_paged", "lt_set_block_table",
+    "lt_reset_sequence", "lt_kv_bytes_paged", "lt_create_paged", "lt_set_block_table", "lt_decode_step_active",
 ]
 
 
@@ -101,6 +101,8 @@ def load() -> ctypes.CDLL:
     lib.lt_decode_attn.restype = ctypes.c_int
     lib.lt_decode_step.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp]
     lib.lt_decode_step.restype = ctypes.c_int
+    lib.lt_decode_step_active.argtypes = [vp, i32, vp, vp, vp, vp, vp, vp, vp]
+    lib.lt_decode_step_active.restype = ctypes.c_int
     lib.lt_set_split.argtypes = [vp, i32, i32]
     lib.lt_set_split.restype = ctypes.c_int
     lib.lt_profile_enable.argtypes = [vp, i32]
@@ -489,8 +491,10 @@ class Context:
         return (out, lse) if (want_lse or lse is not None) else out
 
     def decode_step(self, layer: int, q: torch.Tensor, k_new: torch.Tensor, v_new: torch.Tensor,
-                    out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None, want_lse: bool = False, stream=None):
-        """Fused append of one token + attention.  k_new / v_new: bf16 [B,Hkv,1,128] or [B,Hkv,128]."""
+                    out: Optional[torch.Tensor] = None, lse: Optional[torch.Tensor] = None, want_lse: bool = False, stream=None,
+                    active=None):
+        """Fused append of one token + attention.  k_new / v_new: bf16 [B,Hkv,1,128] or [B,Hkv,128].
+        active: optional B flags (host); sequences with a zero flag sit the step out (lt_decode_step_active)."""
         qp = _dev_ptr(q, torch.bfloat16, "q")
         kp, vp = _dev_ptr(k_new, torch.bfloat16, "k_new"), _dev_ptr(v_new, torch.bfloat16, "v_new")
         if tuple(q.shape) != (self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim):
@@ -501,6 +505,14 @@ class Context:
             out = torch.empty((self.cfg.batch, self.cfg.n_q_heads, self.cfg.head_dim), dtype=self.out_dtype, device=q.device)
         if lse is None and want_lse:
             lse = torch.empty((self.cfg.batch, self.cfg.n_q_heads), dtype=torch.float32, device=q.device)
+        if active is not None:
+            flags = np.ascontiguousarray(np.asarray(active, dtype=np.uint8))
+            if flags.shape != (self.cfg.batch,):
+                raise LtError(ERR_SHAPE, "lt_decode_step_active (one flag per sequence)")
+            st = load().lt_decode_step_active(self._h, int(layer), qp, kp, vp, flags.ctypes.data, _dev_ptr(out, self.out_dtype, "out"),
+                                              _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
+            _check(st, "lt_decode_step_active")
+            return (out, lse) if (want_lse or lse is not None) else out
         st = load().lt_decode_step(self._h, int(layer), qp, kp, vp, _dev_ptr(out, self.out_dtype, "out"),
                                    _dev_ptr(lse, torch.float32, "lse"), _stream_ptr(stream))
         _check(st, "lt_decode_step")

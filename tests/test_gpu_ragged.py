@@ -198,3 +198,54 @@ def test_reset_sequence_frees_a_slot_for_a_new_prompt():
     check(8750)
     assert ctx.seq_len(1, 1) == (49, ws + wr) and ctx.layer_len(0)[0] == 121
     ctx.close()
+
+
+@pytest.mark.parametrize("paged", [False, True])
+def test_decode_step_for_the_sequences_still_generating(paged):
+    """Some sequences sit steps out: they get no token, keep their length, are not read (rows 0 / -inf), and pick up
+    where they left when they are active again; the others are checked against the oracle over their own history."""
+    B, Hq, Hkv, ws, wr, page = 4, 8, 2, 4, 28, 64
+    cfg = lt.make_config(2, B, Hq, Hkv, 128, ws, wr, 300)
+    is_lazy = [0, 1]
+    if paged:
+        ctx = lt.Context(cfg, is_lazy, DEV, paged=(page, 24))
+        ctx.set_block_table(np.random.default_rng(3).permutation(24)[:20].astype(np.int32).reshape(B, 5))
+    else:
+        ctx = lt.Context(cfg, is_lazy, DEV)
+    hists = [oracle.History(2, is_lazy, ws, wr) for _ in range(B)]
+    lengths = [70, 63, 5, 130]
+    for layer in range(2):
+        k = randn_bf16((B, Hkv, max(lengths), 128), 8800 + layer)
+        v = randn_bf16((B, Hkv, max(lengths), 128), 8810 + layer)
+        if paged:
+            ctx.append_kv_ragged(layer, k, v, lengths)
+        elif layer == 0:                                       # contiguous: start from a batch of equal lengths
+            lengths = [70] * B
+        if not paged:
+            ctx.append_kv(layer, k[:, :, :70].contiguous(), v[:, :, :70].contiguous())
+        for b in range(B):
+            hists[b].append(layer, bits(k[b:b + 1, :, :lengths[b]]), bits(v[b:b + 1, :, :lengths[b]]))
+    totals = list(lengths)
+    patterns = [[1, 0, 1, 1], [1, 0, 0, 1], [0, 1, 1, 0], [1, 1, 1, 1], [0, 0, 0, 1]]
+    for step, act in enumerate(patterns):
+        for layer in range(2):
+            q = randn_bf16((B, Hq, 128), 8820 + 7 * step + layer)
+            kn = randn_bf16((B, Hkv, 1, 128), 8830 + 7 * step + layer)
+            vn = randn_bf16((B, Hkv, 1, 128), 8840 + 7 * step + layer)
+            out, lse = ctx.decode_step(layer, q, kn, vn, want_lse=True, active=act)
+            for b in range(B):
+                if act[b]:
+                    hists[b].append(layer, bits(kn[b:b + 1]), bits(vn[b:b + 1]))
+                    ref, ref_lse = hists[b].decode(layer, bits(q[b:b + 1]))
+                    assert np.abs(f64(out[b:b + 1]) - ref).max() <= TOL_OUT
+                    assert np.abs(f64(lse[b:b + 1]) - ref_lse).max() <= TOL_LSE
+                else:
+                    assert (out[b] == 0).all() and torch.isinf(lse[b]).all() and (lse[b] < 0).all()
+        for b in range(B):
+            totals[b] += act[b]
+            assert ctx.seq_len(0, b) == (totals[b], totals[b])
+            assert ctx.seq_len(1, b) == (totals[b], min(totals[b], ws + wr))
+    assert ctx.layer_len(0)[0] == max(totals)
+    with pytest.raises(lt.LtError):
+        ctx.decode_step(0, q, kn, vn, active=[1, 1])           # one flag per sequence
+    ctx.close()

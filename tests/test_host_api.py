@@ -406,3 +406,27 @@ def test_product_path_has_no_oracle_and_no_fallback(tmp_path, monkeypatch):
     env = dict(os.environ, HIPCC=str(tmp_path / "no_such_hipcc"))
     out = subprocess.run([sys.executable, "-c", probe], env=env, capture_output=True, text=True, timeout=120)
     assert out.stdout.strip().startswith("raised"), out.stdout + out.stderr
+
+
+def test_decode_step_active_argument_validation():
+    lib, c = lt.load(), cfg()
+    h = make_ctx(c, [0, 1, 0, 1])
+    flags = (ctypes.c_uint8 * 2)(1, 0)
+    assert lib.lt_decode_step_active(h, 0, FAKE_DEV, FAKE_DEV, FAKE_DEV, None, FAKE_DEV, None, None) == lt.ERR_INVALID_ARG
+    assert lib.lt_decode_step_active(h, 0, FAKE_DEV, None, FAKE_DEV, flags, FAKE_DEV, None, None) == lt.ERR_INVALID_ARG
+    assert lib.lt_decode_step_active(h, 9, FAKE_DEV, FAKE_DEV, FAKE_DEV, flags, FAKE_DEV, None, None) == lt.ERR_INVALID_ARG
+    none = (ctypes.c_uint8 * 2)(0, 0)
+    assert lib.lt_decode_step_active(h, 0, FAKE_DEV, FAKE_DEV, FAKE_DEV, none, FAKE_DEV, None, None) == lt.ERR_STATE   # nobody generates
+    total = ctypes.c_int64(-1)
+    assert lib.lt_seq_len(h, 0, 0, ctypes.byref(total), None) == lt.OK and total.value == 0        # and nothing was counted
+    lib.lt_destroy(h)
+    online = ctypes.c_void_p()
+    assert lib.lt_create_online(ctypes.byref(c), 2, FAKE_DEV, lt.kv_bytes_online(c, 2), FAKE_DEV + (1 << 34),
+                                lt.workspace_bytes(c), ctypes.byref(online)) == lt.OK
+    assert lib.lt_decode_step_active(online, 0, FAKE_DEV, FAKE_DEV, FAKE_DEV, flags, FAKE_DEV, None, None) == lt.ERR_STATE
+    lib.lt_destroy(online)
+    wide = lt.make_config(1, 65, 4, 2, 128, 4, 60, 100)
+    hw = make_ctx(wide, [0])
+    many = (ctypes.c_uint8 * 65)(*([1] * 65))
+    assert lib.lt_decode_step_active(hw, 0, FAKE_DEV, FAKE_DEV, FAKE_DEV, many, FAKE_DEV, None, None) == lt.ERR_SHAPE
+    lib.lt_destroy(hw)
