@@ -119,8 +119,10 @@ __device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Stage<W>::kSlot
 }
 
 // V staging.  Work item (c, kg) = 8 dims x 4 consecutive keys: four 16-byte loads (one per key), an 8 x 4
-// transpose in registers, eight 8-byte LDS writes (one per dim).  The first 256 threads do it; lanes whose
-// dim chunks fall on the same banks take key groups 32 keys apart, so that a write of 32 lanes covers all banks.
+// transpose in registers, eight 8-byte LDS writes (one per dim).  The first 256 threads do it.  The rows of
+// neighbouring dim chunks start on the same bank (8 rows of 144 bytes are a multiple of 128 bytes), so the four
+// lanes that share a key group index take four different groups of four keys, 16 keys apart: any 16 consecutive
+// lanes then write 32 different banks (the bank-conflict counter reads 0; it read 23 % of the LDS cycles before).
 // Slot of key j (0..63) in a V^T row: 16 (j / 16) + {0, 8, 4, 12}[(j % 16) / 4] + j % 4, i.e. within 16 keys the
 // order 0-3, 8-11, 4-7, 12-15: slots 8 h .. 8 h + 7 then hold keys 4 h + {0..3} and 8 + 4 h + {0..3}.
 template <int kSlots>
@@ -138,7 +140,7 @@ template <int kSlots>
 __device__ __forceinline__ void commit_v(const u32x4_t (&pre)[kSlots], uint16_t *sh)
 {
     if (threadIdx.x >= 256) return;
-    const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2);
+    const int c = 4 * (threadIdx.x >> 6) + (threadIdx.x & 3), kg = ((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 3) << 2);
     const int slot = 16 * (kg >> 2) + ((0x0C040800 >> (8 * (kg & 3))) & 0xff);
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
@@ -313,7 +315,7 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     // per-lane byte offsets of the staging loads inside a whole tile (see fetch_tile, fetch_v)
     const uint32_t k_me = threadIdx.x - Stage<W>::kFirst;               // unused by the threads that copy no K
     const uint32_t k_lane_bytes = 2u * ((k_me >> 4) * (uint32_t)a.kv_stride_t + (k_me & 15) * 8);
-    const uint32_t v_lane_bytes = 2u * (4 * (((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 2) << 2)) * (uint32_t)a.kv_stride_t
+    const uint32_t v_lane_bytes = 2u * (4 * (((threadIdx.x >> 2) & 15) ^ ((threadIdx.x & 3) << 2)) * (uint32_t)a.kv_stride_t
                                         + (4 * (threadIdx.x >> 6) + (threadIdx.x & 3)) * 8);
     auto prefetch = [&](int t) {
         if (t < n_tiles) {
