@@ -585,8 +585,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
         sh_merge_l[h][c] = observe(ml + 1);
     }
     __syncthreads();
-    // One thread per (head, dim); further partial accumulators are fetched eight splits at a time
-    // so the loads overlap instead of paying one memory latency per split.
+    // One thread per (head, dim); further partial accumulators are fetched 24 splits at a time, so that up to
+    // 32 splits cost two memory round trips in all instead of one per split.
 #pragma unroll
     for (int r = 0; r < (G * kHeadDim + kThreads - 1) / kThreads; ++r) {
         const int idx = threadIdx.x + r * kThreads;
@@ -597,19 +597,22 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
         float mx = -INFINITY;
         for (int c = 0; c < a.n_splits; ++c) mx = fmaxf(mx, sh_merge_m[h][c]);
         float l = 0.f, o = 0.f;
-        for (int c0 = 0; c0 < a.n_splits; c0 += 8) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u)
-                v[u] = c0 == 0 ? first[r][u] : observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (c0 + u < a.n_splits) {
-                    const float wgt = sh_merge_m[h][c0 + u] == -INFINITY ? 0.f : fast_exp2(sh_merge_m[h][c0 + u] - mx);
-                    l += wgt * sh_merge_l[h][c0 + u];
-                    o += wgt * v[u];
-                }
+        auto weigh = [&](int c, float v) {
+            if (c < a.n_splits) {
+                const float wgt = sh_merge_m[h][c] == -INFINITY ? 0.f : fast_exp2(sh_merge_m[h][c] - mx);
+                l += wgt * sh_merge_l[h][c];
+                o += wgt * v;
             }
+        };
+#pragma unroll
+        for (int u = 0; u < 8; ++u) weigh(u, first[r][u]);
+        constexpr int kBatch = 24;                                  // splits 8.. : this many loads per round trip
+        for (int c0 = 8; c0 < a.n_splits; c0 += kBatch) {
+            float v[kBatch];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) v[u] = observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) weigh(c0 + u, v[u]);
         }
         store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);
         if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
@@ -629,9 +632,13 @@ hipError_t launch_decode_as(const DecodeArgs &a, const typename ModeArgs<kMode>:
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
     // short ranges: eight wavefronts per workgroup; not for groups of eight heads, whose state needs more than
     // the 256 registers a wavefront has when two share a SIMD
-    const bool wide = G < 8 && a.keys_per_block <= kWideBlockKeys;
-    if (wide) hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);
-    else hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, kMode>), grid, dim3(256), 0, stream, a, r);
+    if constexpr (G < 8) {
+        if (a.keys_per_block <= kWideBlockKeys) {
+            hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 4, kMode>), grid, dim3(256), 0, stream, a, r);
     return hipGetLastError();
 }
 
