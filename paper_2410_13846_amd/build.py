@@ -25,18 +25,33 @@ def is_stale() -> bool:
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
-    """Compile the library (always when force=True; otherwise only if missing)."""
+    """Compile the library (always when force=True; otherwise only if missing).  The translation units are
+    compiled side by side, then linked."""
     if not force and os.path.exists(LIB_PATH):
         return LIB_PATH
+    import tempfile
+    from concurrent.futures import ThreadPoolExecutor
+
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    tmp = LIB_PATH + ".tmp.%d" % os.getpid()
-    cmd = [hipcc] + HIPCC_FLAGS + [os.path.join(CSRC, f) for f in SOURCES] + ["-o", tmp]
-    proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    lines = [l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l]
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + "\n".join(lines))
-    if verbose and lines:
-        print("\n".join(lines))
+    compile_flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    messages = []
+
+    def run(cmd):
+        proc = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        lines = [l for l in proc.stdout.splitlines() if "packed-fp32-ops" not in l]
+        if proc.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + "\n".join(lines))
+        messages.extend(lines)
+
+    with tempfile.TemporaryDirectory(prefix="lt_build_") as tmpdir:
+        objects = [os.path.join(tmpdir, os.path.splitext(f)[0] + ".o") for f in SOURCES]
+        with ThreadPoolExecutor(max_workers=min(len(SOURCES), os.cpu_count() or 1)) as pool:
+            list(pool.map(lambda so: run([hipcc] + compile_flags + ["-c", os.path.join(CSRC, so[0]), "-o", so[1]]),
+                          zip(SOURCES, objects)))
+        tmp = LIB_PATH + ".tmp.%d" % os.getpid()
+        run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objects + ["-o", tmp])
+    if verbose and messages:
+        print("\n".join(messages))
     os.replace(tmp, LIB_PATH)
     return LIB_PATH
 
