@@ -553,11 +553,25 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
 
     // The workgroup that takes the last ticket of its (sequence, KV head) merges all splits:
     // softmax over a union of disjoint key sets is the sum of the per-set results weighted by
-    // exp(max_c - max) * l_c.  Partial results travel through device-scope atomic stores and
-    // loads, which are coherent across the chip's L2 slices on their own; what is left to do is
-    // ordering: our stores complete (workgroup release = wait for the store acknowledgements),
-    // then the ticket is taken, and the merge loads are issued only after the last ticket.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    // exp(max_c - max) * l_c.
+    //
+    // Ordering between workgroups, made explicit step by step:
+    //  1. Partial results are written with device-scope atomic stores: they bypass the non-coherent
+    //     levels and complete at the point every compute unit of the device reads from.
+    //  2. Every thread waits until ALL of its own vector-memory operations have been acknowledged
+    //     (vmcnt(0); on this architecture stores count in vmcnt), i.e. its partial results are
+    //     visible device-wide.  A fence at workgroup scope would not promise that.
+    //  3. The barrier makes step 2 of every thread precede the ticket, which one thread takes
+    //     with a device-scope atomic add.
+    //  4. The merge loads (device-scope atomic loads, never served from a non-coherent cache
+    //     line) are issued only by a workgroup that has seen the last ticket value come back:
+    //     they depend on it through LDS and a barrier, and the hardware does not issue loads
+    //     past an unresolved branch.  Every other workgroup of the (sequence, KV head) took its
+    //     ticket after its own step 2, so all partial results are complete by then.
+    // No cache write-back or invalidate is involved (a device-scope release fence here costs a
+    // whole-L2 write-back per workgroup and doubled the kernel time).
+    __builtin_amdgcn_s_waitcnt(0x0F70);                             // vmcnt(0): this thread's publish() stores are acknowledged
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // compiler ordering; the hardware wait is the line above
     __syncthreads();
     unsigned int *ticket = a.tickets + ((int64_t)b * a.n_kv_heads + g) * kTicketStride;
     if (threadIdx.x == 0) {
@@ -566,7 +580,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     }
     __syncthreads();
     if (!sh_is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");          // compiler ordering: no merge load moves above the ticket
     // Every (head, split) pair's running max and sum go to LDS; the first eight partial
     // accumulators of each output element are requested in the same round trip.
     float first[(G * kHeadDim + kThreads - 1) / kThreads][8];

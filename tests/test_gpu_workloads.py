@@ -2,9 +2,10 @@
 times (same batch, heads, context, window, default split choice, fused decode step).
 
 The tiny configuration is compared tensor by tensor.  The large ones keep the real per-layer
-shapes but fewer layers (a layer's launch does not depend on how many layers exist), and compare
-sampled (layer, sequence) slices that the oracle can compute one by one, plus properties that
-hold for every output."""
+shapes but fewer layers (a layer's launch does not depend on how many layers exist).  The
+"whole batch" tests compare every output element of a full and a lazy layer over several
+consecutive steps; the "sampled" ones cover more layers, scoring and paging on sampled
+(layer, sequence) slices plus properties that hold for every output."""
 import numpy as np
 import pytest
 import torch
@@ -181,12 +182,89 @@ def test_llama31_8b_128k_shapes_sampled():
                 score_samples=[(1, 0, 5)])
 
 
-def test_llama31_8b_128k_batch_16_one_full_layer():
-    """The batch-16 128K shape: one full layer holds 8.6 GB of K and V; offsets exceed 2^31 elements."""
+def run_whole_batch(wl, layers, is_lazy, steps):
+    """Every output element of every sequence and head, at every one of `steps` consecutive fused decode steps of
+    the given layers, against the oracle over the whole positional history.  The layers alternate inside a step as
+    they do in a stack, so the split workspace and the tickets are reused by launches of different split counts:
+    a partial result left over from an earlier launch, or one merged before it was complete, shows up here."""
+    sub = wl.scaled(n_layers=len(layers), decode_steps=steps)
+    cfg = make_cfg(sub)
+    ctx = lt.Context(cfg, is_lazy, DEV)
+    n = wl.context
+    hist_k, hist_v = [], []
+    for i, layer in enumerate(layers):
+        say(wl.name, "whole batch: prefill layer", layer)
+        k, v = W.prefill_kv(wl, layer, DEV)
+        ctx.append_kv(i, k, v)
+        K = np.empty((wl.batch, wl.n_kv_heads, n + steps, wl.head_dim), np.uint16)
+        V = np.empty_like(K)
+        K[:, :, :n] = bits(k)
+        V[:, :, :n] = bits(v)
+        hist_k.append(K)
+        hist_v.append(V)
+        del k, v
+    worst = {i: 0.0 for i in range(len(layers))}
+    for step in range(steps):
+        results = []
+        for i, layer in enumerate(layers):
+            q, k, v = W.decode_qkv(wl, layer, step, DEV)
+            out, lse = ctx.decode_step(i, q, k, v, want_lse=True)
+            results.append((q, k, v, out, lse))
+        torch.cuda.synchronize()
+        for i, (q, k, v, out, lse) in enumerate(results):
+            T = n + step + 1
+            hist_k[i][:, :, T - 1] = bits(k)[:, :, 0]
+            hist_v[i][:, :, T - 1] = bits(v)[:, :, 0]
+            K = hist_k[i] if T == n + steps else np.ascontiguousarray(hist_k[i][:, :, :T])
+            V = hist_v[i] if T == n + steps else np.ascontiguousarray(hist_v[i][:, :, :T])
+            mode = oracle.MODE_LAZY if is_lazy[i] else oracle.MODE_FULL
+            ref, ref_lse = oracle.decode_attn(bits(q), K, V, mode, wl.w_sink, wl.w_recent)
+            err = np.abs(f64(out) - ref)
+            err_lse = np.abs(f64(lse) - ref_lse)
+            say(wl.name, "whole batch: step", step, "layer", layers[i], "lazy" if is_lazy[i] else "full", "T", T,
+                "max err", err.max(), "lse", err_lse.max())
+            assert err.max() <= TOL_OUT, np.unravel_index(err.argmax(), err.shape)
+            assert err_lse.max() <= TOL_LSE, np.unravel_index(err_lse.argmax(), err_lse.shape)
+            worst[i] = max(worst[i], err.max())
+    ctx.close()
+    return worst
+
+
+def test_llama3_8b_32k_whole_batch_every_row():
+    """Batch 8, context 32768: all 8 x 32 x 128 outputs of one full and one planted-lazy layer, four steps in a row."""
+    wl = W.WORKLOADS["llama3_8b_32k"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layer = [l for l in range(wl.n_layers) if l not in lazy_layers][2]
+    run_whole_batch(wl, [full_layer, lazy_layers[2]], [0, 1], steps=4)
+
+
+def test_mistral_7b_16k_whole_batch_every_row():
+    """Batch 32, context 16384: 256 key streams, so one key range per (sequence, KV head) and no merge."""
+    wl = W.WORKLOADS["mistral_7b_16k"]
+    run_whole_batch(wl, [7, 21], [0, 1], steps=3)
+
+
+def test_qwq_32b_whole_batch_every_row():
+    """Groups of five query heads, batch 4, a history of 20000 tokens: 64 key ranges per (sequence, KV head)."""
+    wl = W.WORKLOADS["qwq_32b_gen"].scaled(context=20000)
+    run_whole_batch(wl, [1, 33], [0, 1], steps=4)
+
+
+def test_llama31_8b_128k_b1_whole_batch_every_row():
+    """Context 131072, batch 1, 4 + 4092 window: 32 key ranges per KV head merged in one launch."""
+    wl = W.WORKLOADS["llama31_8b_128k_b1"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layer = [l for l in range(wl.n_layers) if l not in lazy_layers][1]
+    run_whole_batch(wl, [full_layer, lazy_layers[1]], [0, 1], steps=3)
+
+
+def test_llama31_8b_128k_batch_16_one_full_layer_every_row():
+    """The batch-16 128K shape: one full layer holds 8.6 GB of K and V; offsets exceed 2^31 elements.  Every
+    output of the launch against the oracle (the host copy of the layer is 8.6 GB)."""
     wl = W.WORKLOADS["llama31_8b_128k_b16"]
     lazy_layers = W.planted_lazy_layers(wl)
     full_layer = [l for l in range(wl.n_layers) if l not in lazy_layers][0]
-    run_sampled(wl, [full_layer], [0], samples=[(0, 15), (0, 8)], steps=1)
+    run_whole_batch(wl, [full_layer], [0], steps=1)
 
 
 def test_llama3_8b_32k_prefill_and_ratio_from_lse_sampled():
