@@ -19,12 +19,20 @@
  *   `stream` (a hipStream_t passed as void*; NULL is the default stream) and the call returns
  *   without waiting for it.  Token counts live on the host, so no call synchronises.
  *   bf16 tensors are raw 16-bit patterns, dense and row-major in the stated shape unless strides
- *   are given; fp32 outputs are dense.  head_dim must be 128.  All sequences of a batch have the
- *   same length in a layer.
- *   Errors: every call validates its arguments before enqueuing anything and returns a status;
- *   on any status other than LT_OK no device work was enqueued and no state changed.  There are
- *   no exceptions, no aborts and no global state; different lt_ctx objects are independent.  One
- *   lt_ctx must not be used from two threads at once.
+ *   are given; fp32 outputs are dense.  head_dim must be 128.  A layer keeps one token count per
+ *   batch while every call adds the same number of tokens to every sequence; lt_append_kv_ragged,
+ *   lt_reset_sequence, lt_decode_step_active and paged contexts switch a layer to one count per
+ *   sequence (batch <= 64 then).
+ *   Errors: every call validates its arguments and the state it needs on the host, before it
+ *   enqueues the work it was asked for, and returns a status; on any status other than LT_OK no
+ *   token was appended, no token count changed and no cache byte was written.  Two things may
+ *   still have happened on an error path and are harmless: the first decode call on a context
+ *   enqueues the one-off zeroing of its counters before its launch, and a call that needs
+ *   per-sequence counts (see above) switches the layer's bookkeeping to them, which changes no
+ *   length.  In an online context (lt_create_online) a layer's first append reserves a full-size
+ *   slot; if that append's launch is then refused by the runtime (LT_ERR_HIP) the slot stays with
+ *   the layer.  There are no exceptions and no aborts; different lt_ctx objects are independent,
+ *   and one lt_ctx must not be used from two threads at once.
  */
 #ifndef LT_H
 #define LT_H
@@ -90,7 +98,8 @@ lt_status lt_create(const lt_config *cfg, const uint8_t *is_lazy, void *kv_slab,
 /* Free the host-side state.  Device memory is untouched.  NULL is allowed. */
 void lt_destroy(lt_ctx *ctx);
 
-/* Forget every token of every layer (host counters only). */
+/* Forget every token of every layer (host counters only).  The next decode call zeroes the split
+ * counters in the workspace again, so a context whose launch failed half-way is usable after this. */
 lt_status lt_reset(lt_ctx *ctx);
 
 /* Tokens appended to a layer so far (total) and entries its cache holds (stored:
@@ -328,30 +337,8 @@ lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *
 lt_status lt_decode_step_active(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,
                                 const uint8_t *active_host, void *out, float *lse_out, void *stream);
 
-/* ---- tuning and measurement ---------------------------------------------------------------- */
-
-/* Keys one workgroup of the split decode kernel handles in full / lazy layers (multiples of 64);
- * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
-lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
-
-/* Measurement aid: one launch that reads `bytes` of `buf_dev` (rounded down to a multiple of
- * 16 KiB, and at least that) once, with the same kind of loads the decode kernel uses, and discards
- * them; timed by the caller, it gives the read rate this device sustains, the practical ceiling of
- * the decode kernels.
- *   buf_dev   device, 16-byte aligned, at least `bytes` long
- *   sink_dev  device, at least 256 bytes; practically never written */
-lt_status lt_probe_read(const void *buf_dev, size_t bytes, void *sink_dev, void *stream);
-
-enum { LT_KERNEL_DECODE_FULL = 0, LT_KERNEL_DECODE_LAZY = 1, LT_KERNEL_APPEND = 2, LT_KERNEL_COUNT = 3 };
-
-/* Bracket every later kernel launch of this context with a pair of HIP events on the launch
- * stream (on != 0), or stop doing so (on == 0).  Enabling discards earlier measurements. */
-lt_status lt_profile_enable(lt_ctx *ctx, int32_t on);
-
-/* Wait for the recorded events and return, for one kernel kind, how many launches were measured
- * and their summed duration in milliseconds.  Launches beyond the internal event pool (65536
- * pairs) are not measured. */
-lt_status lt_profile_read(lt_ctx *ctx, int32_t kernel, int64_t *launches, double *total_ms);
+/* Tuning knobs and measurement aids (split size, event timing, read-rate probe) are declared in
+ * lt_measure.h; the product path does not need them. */
 
 const char *lt_status_str(lt_status status);
 

@@ -1,0 +1,45 @@
+/*
+ * lt_measure.h -- tuning knobs and measurement aids of the LightTransfer library.
+ *
+ * Nothing here is part of the method (Section "LightTransfer-Test" and the decoding stage of
+ * Section "Preliminary" are served by lt.h alone): these calls exist so that a benchmark can time
+ * single launches on the launch stream, force a split size for a sweep, and measure the read rate
+ * the device sustains.  Conventions (pointers, streams, statuses) are those of lt.h.
+ */
+#ifndef LT_MEASURE_H
+#define LT_MEASURE_H
+
+#include "lt.h"
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Keys one workgroup of the split decode kernel handles in full / lazy layers (multiples of 64);
+ * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
+lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
+
+/* Measurement aid: one launch that reads `bytes` of `buf_dev` (rounded down to a multiple of
+ * 16 KiB, and at least that) once, with the same kind of loads the decode kernel uses, and discards
+ * them; timed by the caller, it gives the read rate this device sustains, the practical ceiling of
+ * the decode kernels.
+ *   buf_dev   device, 16-byte aligned, at least `bytes` long
+ *   sink_dev  device, at least 256 bytes; practically never written */
+lt_status lt_probe_read(const void *buf_dev, size_t bytes, void *sink_dev, void *stream);
+
+enum { LT_KERNEL_DECODE_FULL = 0, LT_KERNEL_DECODE_LAZY = 1, LT_KERNEL_APPEND = 2, LT_KERNEL_COUNT = 3 };
+
+/* Bracket every later kernel launch of this context with a pair of HIP events on the launch
+ * stream (on != 0), or stop doing so (on == 0).  Enabling discards earlier measurements.  Events
+ * are created as launches need them and kept for reuse until lt_destroy. */
+lt_status lt_profile_enable(lt_ctx *ctx, int32_t on);
+
+/* Wait for the recorded events and return, for one kernel kind, how many launches were measured
+ * and their summed duration in milliseconds.  Launches beyond the internal event pool (65536
+ * pairs) are not measured. */
+lt_status lt_profile_read(lt_ctx *ctx, int32_t kernel, int64_t *launches, double *total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LT_MEASURE_H */

@@ -8,7 +8,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
 LIB_PATH = os.path.join(_HERE, "liblt_hip.so")
 SOURCES = ["lt_api.cpp", "lt_decode.hip", "lt_score.hip", "lt_prefill.hip"]
-HEADERS = ["lt_kernels.h", os.path.join("..", "..", "include", "lt.h")]
+HEADERS = ["lt_kernels.h", os.path.join("..", "..", "include", "lt.h"), os.path.join("..", "..", "include", "lt_measure.h")]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",

@@ -3,6 +3,7 @@
 // launch plumbing (split heuristics, optional event timing).  All arithmetic of the method runs
 // in the kernels behind lt_kernels.h; this file only decides shapes and addresses.
 #include "../../include/lt.h"
+#include "../../include/lt_measure.h"
 #include "lt_kernels.h"
 
 #include <algorithm>
@@ -169,7 +170,18 @@ struct ScopedEvents {
     EventPair *pair = nullptr;
     ScopedEvents(lt_ctx *c, hipStream_t s, int32_t kernel) : ctx(c), stream(s)
     {
-        if (ctx->profiling && ctx->events_used < ctx->events.size()) {
+        if (!ctx->profiling) return;
+        if (ctx->events_used == ctx->events.size() && ctx->events.size() < (size_t)kMaxEventPairs) {
+            // a new pair, made when a launch needs it (room for it was reserved by lt_profile_enable); kept for reuse
+            EventPair p{};
+            if (hipEventCreate(&p.start) != hipSuccess) return;
+            if (hipEventCreate(&p.stop) != hipSuccess) {
+                (void)hipEventDestroy(p.start);
+                return;
+            }
+            ctx->events.push_back(p);
+        }
+        if (ctx->events_used < ctx->events.size()) {
             pair = &ctx->events[ctx->events_used++];
             pair->kernel = kernel;
             (void)hipEventRecord(pair->start, stream);
@@ -452,6 +464,8 @@ lt_status lt_reset(lt_ctx *ctx)
     }
     std::fill(ctx->full_used.begin(), ctx->full_used.end(), 0);
     std::fill(ctx->ring_used.begin(), ctx->ring_used.end(), 0);
+    // the next decode call zeroes the split counters again: a launch that failed half-way may have left some taken
+    ctx->tickets_ready = false;
     return LT_OK;
 }
 
@@ -498,12 +512,12 @@ size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_
     return align_up(part) + align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
 }
 
-lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
-                        int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, void *workspace, size_t ws_bytes,
-                        float *rho_dev, float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
+// The dense form behind lt_lazy_ratio.
+static lt_status lazy_ratio_dense(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
+                                  int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, void *workspace, size_t ws_bytes,
+                                  float *rho_dev, float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
 {
-    if (!config_ok(cfg) || q_last == nullptr || k == nullptr || workspace == nullptr || ratio_mean_dev == nullptr)
-        return LT_ERR_INVALID_ARG;
+    if (!config_ok(cfg) || q_last == nullptr || k == nullptr || ratio_mean_dev == nullptr) return LT_ERR_INVALID_ARG;
     if (mode != LT_RECENT_PER_QUERY && mode != LT_RECENT_FIXED) return LT_ERR_INVALID_ARG;
     if (n <= 0 || w_last <= 0 || k_stride_b < 0 || k_stride_h < 0 || k_stride_t <= 0) return LT_ERR_INVALID_ARG;
     const lt_status shape = config_shape(cfg);
@@ -540,6 +554,15 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
     a.ratio_seq = ratio_seq_dev;
     a.ratio_mean = ratio_mean_dev;
     return ltk::lazy_ratio(a, static_cast<hipStream_t>(stream)) == hipSuccess ? LT_OK : LT_ERR_HIP;
+}
+
+lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
+                        int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, void *workspace, size_t ws_bytes,
+                        float *rho_dev, float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
+{
+    if (workspace == nullptr) return LT_ERR_INVALID_ARG;
+    return lazy_ratio_dense(cfg, q_last, k, k_stride_b, k_stride_h, k_stride_t, n, w_last, mode, workspace, ws_bytes, rho_dev,
+                            ratio_seq_dev, ratio_mean_dev, stream);
 }
 
 // Key ranges the window-only form touches: the tiles holding the first w_sink keys and the tiles from
@@ -1067,20 +1090,11 @@ lt_status lt_probe_read(const void *buf_dev, size_t bytes, void *sink_dev, void 
 lt_status lt_profile_enable(lt_ctx *ctx, int32_t on)
 {
     if (ctx == nullptr) return LT_ERR_INVALID_ARG;
-    if (on != 0 && ctx->events.empty()) {
+    if (on != 0 && ctx->events.capacity() < (size_t)kMaxEventPairs) {
         try {
-            ctx->events.reserve(kMaxEventPairs);
+            ctx->events.reserve(kMaxEventPairs);       // host memory only; the events themselves are made on demand
         } catch (const std::bad_alloc &) {
             return LT_ERR_NOMEM;
-        }
-        for (int i = 0; i < kMaxEventPairs; ++i) {
-            EventPair p{};
-            if (hipEventCreate(&p.start) != hipSuccess) return LT_ERR_HIP;
-            if (hipEventCreate(&p.stop) != hipSuccess) {
-                (void)hipEventDestroy(p.start);
-                return LT_ERR_HIP;
-            }
-            ctx->events.push_back(p);
         }
     }
     if (on != 0) ctx->events_used = 0;

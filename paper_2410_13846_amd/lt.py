@@ -211,25 +211,48 @@ def preselect_lazy(is_lazy_samples, n_lazy: int):
     return is_lazy, count
 
 
+def _check_score_inputs(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_last: int, what: str) -> None:
+    """The library sees only addresses and strides: the extents of the tensors are checked here, so that a wrong n or
+    a mis-shaped tensor is an error status and never a read past the end of a buffer."""
+    if q_last.dtype != torch.bfloat16 or k.dtype != torch.bfloat16:
+        raise TypeError("q_last and k must be bf16 tensors")
+    if not q_last.is_contiguous() or k.dim() != 4 or k.stride(3) != 1:
+        raise TypeError("q_last must be contiguous and k must have contiguous head_dim")
+    n, w_last = int(n), int(w_last)
+    if tuple(q_last.shape) != (cfg.batch, cfg.n_q_heads, w_last, cfg.head_dim):
+        raise LtError(ERR_SHAPE, "%s: q_last is %s, expected [B=%d, Hq=%d, w_last=%d, %d]" % (
+            what, tuple(q_last.shape), cfg.batch, cfg.n_q_heads, w_last, cfg.head_dim))
+    if tuple(k.shape[:2]) != (cfg.batch, cfg.n_kv_heads) or k.shape[3] != cfg.head_dim or n < 1 or n > k.shape[2]:
+        raise LtError(ERR_SHAPE, "%s: k is %s, expected [B=%d, Hkv=%d, >= n=%d, %d]" % (
+            what, tuple(k.shape), cfg.batch, cfg.n_kv_heads, n, cfg.head_dim))
+    if not q_last.is_cuda or q_last.device != k.device:
+        raise TypeError("q_last and k must be on one GPU")
+
+
+def _check_workspace(workspace: torch.Tensor, need: int, device, what: str) -> None:
+    if not workspace.is_cuda or workspace.device != device or not workspace.is_contiguous():
+        raise TypeError("%s: the workspace must be a contiguous tensor on the inputs' device" % what)
+    if workspace.numel() * workspace.element_size() < need:
+        raise LtError(ERR_CAPACITY, "%s: workspace of %d bytes, %d needed" % (what, workspace.numel() * workspace.element_size(), need))
+
+
 def lazy_ratio(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_last: int, mode: int = RECENT_PER_QUERY,
                workspace: Optional[torch.Tensor] = None, want_rho: bool = False, stream=None):
     """q_last bf16 [B,Hq,w,128]; k bf16 [B,Hkv,>=n,128] (any strides with contiguous dims).
 
     Returns device tensors (ratio_mean [1], ratio_seq [B], rho [B,Hq,w] or None)."""
     lib = load()
-    if q_last.dtype != torch.bfloat16 or k.dtype != torch.bfloat16 or not q_last.is_cuda or not k.is_cuda:
-        raise TypeError("q_last and k must be bf16 device tensors")
-    if not q_last.is_contiguous() or k.dim() != 4 or k.stride(3) != 1:
-        raise TypeError("q_last must be contiguous and k must have contiguous head_dim")
+    _check_score_inputs(cfg, q_last, k, n, w_last, "lt_lazy_ratio")
     need = lazy_ratio_workspace_bytes(cfg, n, w_last)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_last.device)
+    _check_workspace(workspace, need, q_last.device, "lt_lazy_ratio")
     dev = q_last.device
     mean = torch.empty(1, dtype=torch.float32, device=dev)
     seq = torch.empty(cfg.batch, dtype=torch.float32, device=dev)
     rho = torch.empty((cfg.batch, cfg.n_q_heads, w_last), dtype=torch.float32, device=dev) if want_rho else None
     st = lib.lt_lazy_ratio(ctypes.byref(cfg), q_last.data_ptr(), k.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
-                           int(n), int(w_last), int(mode), workspace.data_ptr(), workspace.numel(),
+                           int(n), int(w_last), int(mode), workspace.data_ptr(), workspace.numel() * workspace.element_size(),
                            rho.data_ptr() if rho is not None else None, seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
     _check(st, "lt_lazy_ratio")
     return mean, seq, rho
@@ -244,24 +267,24 @@ def lazy_ratio_lse(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w
     """Lazy ratio from the prefill's log-sum-exp.  lse_rows: fp32 view [B,Hq,w_last] (last dim contiguous) of the rows
     n-w_last..n-1, e.g. ``lse[:, :, n - w_last:]`` of prefill_attn's output.  Returns what lazy_ratio returns."""
     lib = load()
-    if q_last.dtype != torch.bfloat16 or k.dtype != torch.bfloat16 or not q_last.is_cuda or not k.is_cuda:
-        raise TypeError("q_last and k must be bf16 device tensors")
-    if not q_last.is_contiguous() or k.dim() != 4 or k.stride(3) != 1:
-        raise TypeError("q_last must be contiguous and k must have contiguous head_dim")
+    _check_score_inputs(cfg, q_last, k, n, w_last, "lt_lazy_ratio_lse")
     if lse_rows.dtype != torch.float32 or not lse_rows.is_cuda or lse_rows.dim() != 3 or lse_rows.stride(2) != 1 \
             or tuple(lse_rows.shape) != (cfg.batch, cfg.n_q_heads, w_last):
         raise TypeError("lse_rows must be an fp32 device view [B, Hq, w_last] with a contiguous last dim")
+    if lse_rows.device != q_last.device:
+        raise TypeError("lse_rows must be on the inputs' device")
     need = lazy_ratio_lse_workspace_bytes(cfg, n, w_last)
     if workspace is None:
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q_last.device)
+    _check_workspace(workspace, need, q_last.device, "lt_lazy_ratio_lse")
     dev = q_last.device
     mean = torch.empty(1, dtype=torch.float32, device=dev)
     seq = torch.empty(cfg.batch, dtype=torch.float32, device=dev)
     rho = torch.empty((cfg.batch, cfg.n_q_heads, w_last), dtype=torch.float32, device=dev) if want_rho else None
     st = lib.lt_lazy_ratio_lse(ctypes.byref(cfg), q_last.data_ptr(), k.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
                                int(n), int(w_last), int(mode), lse_rows.data_ptr(), lse_rows.stride(0), lse_rows.stride(1),
-                               workspace.data_ptr(), workspace.numel(), rho.data_ptr() if rho is not None else None,
-                               seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
+                               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                               rho.data_ptr() if rho is not None else None, seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
     _check(st, "lt_lazy_ratio_lse")
     return mean, seq, rho
 
@@ -273,13 +296,22 @@ def prefill_attn(cfg: Config, q: torch.Tensor, k: torch.Tensor, v: torch.Tensor,
     Returns (out [B,Hq,n_q,128] in out_dtype, lse fp32 [B,Hq,n_q] or None)."""
     lib = load()
     for t in (q, k, v):
-        if t.dtype != torch.bfloat16 or not t.is_cuda:
-            raise TypeError("q, k, v must be bf16 device tensors")
+        if t.dtype != torch.bfloat16:
+            raise TypeError("q, k, v must be bf16 tensors")
     if not q.is_contiguous() or q.dim() != 4 or k.dim() != 4 or k.stride(3) != 1 or k.stride() != v.stride():
         raise TypeError("q must be contiguous [B,Hq,n_q,128]; k and v need equal strides and contiguous head_dim")
     if out_dtype not in (torch.bfloat16, torch.float32):
         raise TypeError("out_dtype must be bfloat16 or float32")
-    n_q = int(q.shape[2])
+    n_q, n = int(q.shape[2]), int(n)
+    if tuple(q.shape) != (cfg.batch, cfg.n_q_heads, n_q, cfg.head_dim) or n_q < 1:
+        raise LtError(ERR_SHAPE, "lt_prefill_attn: q is %s, expected [B=%d, Hq=%d, n_q, %d]" % (
+            tuple(q.shape), cfg.batch, cfg.n_q_heads, cfg.head_dim))
+    if tuple(k.shape[:2]) != (cfg.batch, cfg.n_kv_heads) or k.shape[3] != cfg.head_dim or tuple(v.shape) != tuple(k.shape) \
+            or n < n_q or n > k.shape[2]:
+        raise LtError(ERR_SHAPE, "lt_prefill_attn: k / v are %s / %s, expected [B=%d, Hkv=%d, >= n=%d, %d] with n >= n_q=%d" % (
+            tuple(k.shape), tuple(v.shape), cfg.batch, cfg.n_kv_heads, n, cfg.head_dim, n_q))
+    if not q.is_cuda or q.device != k.device or q.device != v.device:
+        raise TypeError("q, k and v must be on one GPU")
     out = torch.empty((cfg.batch, cfg.n_q_heads, n_q, cfg.head_dim), dtype=out_dtype, device=q.device)
     lse = torch.empty((cfg.batch, cfg.n_q_heads, n_q), dtype=torch.float32, device=q.device) if want_lse else None
     st = lib.lt_prefill_attn(ctypes.byref(cfg), q.data_ptr(), k.data_ptr(), v.data_ptr(), k.stride(0), k.stride(1), k.stride(2),

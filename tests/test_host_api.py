@@ -22,10 +22,14 @@ def cfg(**kw):
 
 def test_library_exports_every_declared_symbol():
     lib = lt.load()
-    header = open(os.path.join(ROOT, "include", "lt.h")).read()
-    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    declared = set(re.findall(r"\b(lt_[a-z_]+)\s*\(", header))
-    assert declared, "no declarations found in lt.h"
+    declared = set()
+    for name in sorted(os.listdir(os.path.join(ROOT, "include"))):
+        assert name.endswith(".h"), name
+        header = open(os.path.join(ROOT, "include", name)).read()
+        header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+        found = set(re.findall(r"\b(lt_[a-z_]+)\s*\(", header))
+        assert found, "no declarations found in " + name
+        declared |= found
     assert declared == set(lt.EXPORTS)
     for name in declared:
         assert hasattr(lib, name), name
@@ -136,6 +140,45 @@ def test_lazy_ratio_argument_validation():
     assert call(st=64) == lt.ERR_SHAPE                  # rows would overlap
     assert call(sh=500 * 128 + 4) == lt.ERR_SHAPE       # 16-byte alignment of rows
     assert call(ws=need - 1) == lt.ERR_CAPACITY
+
+
+def test_wrappers_check_tensor_extents_before_the_library_sees_addresses():
+    """The C layer gets addresses and strides only, so the binding must refuse tensors whose extents do not cover what
+    the kernels will read (a wrong n, a missing head, a short workspace): ERR_SHAPE / ERR_CAPACITY, never a launch.
+    Host tensors are enough to reach those checks; well-shaped host tensors are then refused for not being on a GPU."""
+    import torch
+
+    c = cfg()                                                       # B 2, Hq 8, Hkv 2, d 128
+    bf = torch.bfloat16
+    q_last = torch.zeros((2, 8, 16, 128), dtype=bf)
+    k = torch.zeros((2, 2, 500, 128), dtype=bf)
+
+    def status_of(fn, *a, **kw):
+        with pytest.raises(lt.LtError) as e:
+            fn(*a, **kw)
+        return e.value.status
+
+    for fn in (lt.lazy_ratio, lambda *a: lt.lazy_ratio_lse(*a, torch.zeros((2, 8, 16)))):
+        assert status_of(fn, c, q_last, k, 501, 16) == lt.ERR_SHAPE                  # n beyond the keys that exist
+        assert status_of(fn, c, q_last, k, 0, 16) == lt.ERR_SHAPE
+        assert status_of(fn, c, q_last, k, 500, 8) == lt.ERR_SHAPE                   # q_last holds 16 queries, not 8
+        assert status_of(fn, c, q_last[:, :4].contiguous(), k, 500, 16) == lt.ERR_SHAPE
+        assert status_of(fn, c, q_last, k[:, :1], 500, 16) == lt.ERR_SHAPE           # a KV head missing
+        assert status_of(fn, c, q_last, k[:1], 500, 16) == lt.ERR_SHAPE              # a sequence missing
+        with pytest.raises(TypeError):
+            fn(c, q_last, k, 500, 16)                                                # fine shapes, but host memory
+    q = torch.zeros((2, 8, 500, 128), dtype=bf)
+    v = torch.zeros_like(k)
+    assert status_of(lt.prefill_attn, c, q, k, v, 501) == lt.ERR_SHAPE
+    assert status_of(lt.prefill_attn, c, q, k, v, 499) == lt.ERR_SHAPE               # fewer positions than queries
+    assert status_of(lt.prefill_attn, c, q[:, :4].contiguous(), k, v, 500) == lt.ERR_SHAPE
+    assert status_of(lt.prefill_attn, c, q, k[:, :1], v[:, :1], 500) == lt.ERR_SHAPE
+    with pytest.raises(TypeError):
+        lt.prefill_attn(c, q, k, v, 500)
+    if torch.cuda.is_available():                                   # workspace extent and device
+        dev = "cuda:0"
+        short = torch.empty(lt.lazy_ratio_workspace_bytes(c, 500, 16) - 1, dtype=torch.uint8, device=dev)
+        assert status_of(lt.lazy_ratio, c, q_last.to(dev), k.to(dev), 500, 16, workspace=short) == lt.ERR_CAPACITY
 
 
 def test_prefill_and_ratio_from_lse_argument_validation():
