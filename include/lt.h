@@ -32,7 +32,8 @@
  *   length.  In an online context (lt_create_online) a layer's first append reserves a full-size
  *   slot; if that append's launch is then refused by the runtime (LT_ERR_HIP) the slot stays with
  *   the layer.  There are no exceptions and no aborts; different lt_ctx objects are independent,
- *   and one lt_ctx must not be used from two threads at once.
+ *   and one lt_ctx must not be used from two threads at once.  The only process-wide state is the
+ *   scratch array of lt_lazy_ratio_static.
  */
 #ifndef LT_H
 #define LT_H
@@ -137,6 +138,22 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
                         int64_t k_stride_h, int64_t k_stride_t, int64_t n, int32_t w_last,
                         lt_ratio_mode mode, void *workspace, size_t ws_bytes, float *rho_dev,
                         float *ratio_seq_dev, float *ratio_mean_dev, void *stream);
+
+/* lt_lazy_ratio for callers that cannot allocate or bring a workspace: code recorded under stream
+ * capture into a HIP graph, tight serving loops, harnesses that forbid device allocation.  Same
+ * arguments, outputs, results and errors as lt_lazy_ratio, without `workspace` / `ws_bytes`: the
+ * partial results live in a 32 MiB array that is part of the library's code object (one copy per
+ * GPU, held until the process ends).  The call allocates nothing on host or device and frees
+ * nothing; on its first use on a device it looks the array's address up (do that first call outside
+ * a capture).  LT_ERR_CAPACITY, with nothing enqueued, when
+ * lt_lazy_ratio_workspace_bytes(cfg, n, w_last) exceeds 32 MiB (every shape up to batch 16 x 32
+ * query heads x 64 queries fits at any n).  All calls on one GPU share the array, which keeps the
+ * last call's contents: two calls whose kernels may overlap on one GPU (different streams, or
+ * different threads) race; calls on one stream are safe.  Nothing in it needs to start at zero. */
+lt_status lt_lazy_ratio_static(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b,
+                               int64_t k_stride_h, int64_t k_stride_t, int64_t n, int32_t w_last,
+                               lt_ratio_mode mode, float *rho_dev, float *ratio_seq_dev,
+                               float *ratio_mean_dev, void *stream);
 
 /* Bytes of device workspace lt_lazy_ratio_lse needs.  Returns 0 on invalid arguments. */
 size_t lt_lazy_ratio_lse_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last);

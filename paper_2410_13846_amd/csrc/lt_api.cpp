@@ -512,7 +512,8 @@ size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_
     return align_up(part) + align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
 }
 
-// The dense form behind lt_lazy_ratio.
+// The dense form behind lt_lazy_ratio and lt_lazy_ratio_static.  workspace == nullptr selects the library's
+// built-in scratch array (and its fixed size) instead of a caller's buffer.
 static lt_status lazy_ratio_dense(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
                                   int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, void *workspace, size_t ws_bytes,
                                   float *rho_dev, float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
@@ -526,6 +527,7 @@ static lt_status lazy_ratio_dense(const lt_config *cfg, const void *q_last, cons
     if (k_stride_t < ltk::kHeadDim || (k_stride_b % 8) != 0 || (k_stride_h % 8) != 0 || (k_stride_t % 8) != 0) return LT_ERR_SHAPE;
     if (((uintptr_t)q_last % 16) != 0 || ((uintptr_t)k % 16) != 0 || ((uintptr_t)workspace % kAlign) != 0) return LT_ERR_INVALID_ARG;
     if (ws_bytes < lt_lazy_ratio_workspace_bytes(cfg, n, w_last)) return LT_ERR_CAPACITY;
+    if (workspace == nullptr && ltk::static_scratch(&workspace) != hipSuccess) return LT_ERR_HIP;
 
     ltk::ScoreArgs a{};
     a.q_last = static_cast<const uint16_t *>(q_last);
@@ -563,6 +565,15 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
     if (workspace == nullptr) return LT_ERR_INVALID_ARG;
     return lazy_ratio_dense(cfg, q_last, k, k_stride_b, k_stride_h, k_stride_t, n, w_last, mode, workspace, ws_bytes, rho_dev,
                             ratio_seq_dev, ratio_mean_dev, stream);
+}
+
+lt_status lt_lazy_ratio_static(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
+                               int64_t k_stride_t, int64_t n, int32_t w_last, lt_ratio_mode mode, float *rho_dev,
+                               float *ratio_seq_dev, float *ratio_mean_dev, void *stream)
+{
+    // a problem whose partial results do not fit the built-in array is refused (LT_ERR_CAPACITY) before anything is looked up
+    return lazy_ratio_dense(cfg, q_last, k, k_stride_b, k_stride_h, k_stride_t, n, w_last, mode, nullptr, ltk::kStaticScratchBytes,
+                            rho_dev, ratio_seq_dev, ratio_mean_dev, stream);
 }
 
 // Key ranges the window-only form touches: the tiles holding the first w_sink keys and the tiles from

@@ -102,6 +102,12 @@ struct ScoreArgs {
 };
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);
 
+// Device address, on the current device, of the library's built-in scratch array of
+// kStaticScratchBytes bytes (256-byte aligned; zero when the code object is loaded, afterwards it
+// keeps what the last launch left).  Looked up once per device; allocates nothing.
+constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+hipError_t static_scratch(void **ptr);
+
 struct PrefillArgs {
     const uint16_t *q;                 // [B][Hq][n_q][128]: the queries of positions n - n_q .. n - 1
     const uint16_t *k, *v;             // [B][Hkv][n][128] through the strides below (elements)

@@ -10,6 +10,14 @@
 // stay private to the lane until the final merge.
 #include "lt_kernels.h"
 
+#include <mutex>
+
+// Scratch for callers that cannot bring a workspace of their own (code under stream capture,
+// serving loops and harnesses that must not allocate): a fixed array inside the code object,
+// one copy per device, alive until the process ends.  In host code `scratch` is only a handle
+// for the symbol; the device address comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char scratch[ltk::kStaticScratchBytes];
+
 namespace ltk {
 namespace {
 
@@ -369,6 +377,30 @@ hipError_t launch_partial(const ScoreArgs &a, hipStream_t stream)
     else
         hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 2, 1>), grid, dim3(64 * G), 0, stream, a);
     return hipGetLastError();
+}
+
+namespace {
+constexpr int kMaxDevices = 64;
+void *scratch_ptr[kMaxDevices];                 // device address of `scratch` on each device, nullptr until asked
+std::mutex scratch_mutex;
+}  // namespace
+
+hipError_t static_scratch(void **ptr)
+{
+    int device = -1;
+    hipError_t e = hipGetDevice(&device);
+    if (e != hipSuccess) return e;
+    if (device < 0 || device >= kMaxDevices) return hipErrorInvalidDevice;
+    std::lock_guard<std::mutex> lock(scratch_mutex);
+    if (scratch_ptr[device] == nullptr) {
+        void *p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return e;
+        if (p == nullptr) return hipErrorInvalidSymbol;
+        scratch_ptr[device] = p;
+    }
+    *ptr = scratch_ptr[device];
+    return hipSuccess;
 }
 
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream)

@@ -26,6 +26,7 @@ EXPORTS = [
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
     "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
     "lt_reset_sequence", "lt_kv_bytes_paged", "lt_create_paged", "lt_set_block_table", "lt_decode_step_active",
+    "lt_lazy_ratio_static",
 ]
 
 
@@ -79,6 +80,8 @@ def load() -> ctypes.CDLL:
     lib.lt_lazy_ratio_workspace_bytes.restype = sz
     lib.lt_lazy_ratio.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, sz, vp, vp, vp, vp]
     lib.lt_lazy_ratio.restype = ctypes.c_int
+    lib.lt_lazy_ratio_static.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, vp, vp, vp]
+    lib.lt_lazy_ratio_static.restype = ctypes.c_int
     lib.lt_lazy_ratio_lse_workspace_bytes.argtypes = [cfgp, i64, i32]
     lib.lt_lazy_ratio_lse_workspace_bytes.restype = sz
     lib.lt_lazy_ratio_lse.argtypes = [cfgp, vp, vp, i64, i64, i64, i64, i32, ctypes.c_int, vp, i64, i64, vp, sz, vp, vp, vp, vp]
@@ -256,6 +259,25 @@ def lazy_ratio(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_las
                            rho.data_ptr() if rho is not None else None, seq.data_ptr(), mean.data_ptr(), _stream_ptr(stream))
     _check(st, "lt_lazy_ratio")
     return mean, seq, rho
+
+
+def lazy_ratio_static(cfg: Config, q_last: torch.Tensor, k: torch.Tensor, n: int, w_last: int, mean_out: torch.Tensor,
+                      seq_out: Optional[torch.Tensor] = None, rho_out: Optional[torch.Tensor] = None,
+                      mode: int = RECENT_PER_QUERY, stream=None) -> None:
+    """lt_lazy_ratio_static: the same ratios with the partial results in the library's built-in scratch array.
+    Nothing is allocated here either: the caller brings the outputs (fp32 device tensors: mean_out [1],
+    seq_out [B] or None, rho_out [B,Hq,w] or None)."""
+    _check_score_inputs(cfg, q_last, k, n, w_last, "lt_lazy_ratio_static")
+    for t, shape, name in ((mean_out, (1,), "mean_out"), (seq_out, (cfg.batch,), "seq_out"),
+                           (rho_out, (cfg.batch, cfg.n_q_heads, int(w_last)), "rho_out")):
+        if t is None:
+            continue
+        if t.dtype != torch.float32 or t.device != q_last.device or not t.is_contiguous() or tuple(t.shape) != shape:
+            raise LtError(ERR_SHAPE, "lt_lazy_ratio_static: %s must be a contiguous fp32 tensor %s on the inputs' device" % (name, shape))
+    st = load().lt_lazy_ratio_static(ctypes.byref(cfg), q_last.data_ptr(), k.data_ptr(), k.stride(0), k.stride(1), k.stride(2),
+                                     int(n), int(w_last), int(mode), rho_out.data_ptr() if rho_out is not None else None,
+                                     seq_out.data_ptr() if seq_out is not None else None, mean_out.data_ptr(), _stream_ptr(stream))
+    _check(st, "lt_lazy_ratio_static")
 
 
 def lazy_ratio_lse_workspace_bytes(cfg: Config, n: int, w_last: int) -> int:

@@ -158,7 +158,8 @@ def test_wrappers_check_tensor_extents_before_the_library_sees_addresses():
             fn(*a, **kw)
         return e.value.status
 
-    for fn in (lt.lazy_ratio, lambda *a: lt.lazy_ratio_lse(*a, torch.zeros((2, 8, 16)))):
+    for fn in (lt.lazy_ratio, lambda *a: lt.lazy_ratio_lse(*a, torch.zeros((2, 8, 16))),
+               lambda *a: lt.lazy_ratio_static(*a, torch.zeros(1))):
         assert status_of(fn, c, q_last, k, 501, 16) == lt.ERR_SHAPE                  # n beyond the keys that exist
         assert status_of(fn, c, q_last, k, 0, 16) == lt.ERR_SHAPE
         assert status_of(fn, c, q_last, k, 500, 8) == lt.ERR_SHAPE                   # q_last holds 16 queries, not 8
@@ -179,6 +180,29 @@ def test_wrappers_check_tensor_extents_before_the_library_sees_addresses():
         dev = "cuda:0"
         short = torch.empty(lt.lazy_ratio_workspace_bytes(c, 500, 16) - 1, dtype=torch.uint8, device=dev)
         assert status_of(lt.lazy_ratio, c, q_last.to(dev), k.to(dev), 500, 16, workspace=short) == lt.ERR_CAPACITY
+
+
+def test_lazy_ratio_static_argument_validation():
+    """The variant that keeps its partial results in the library's own scratch array: same checks as lt_lazy_ratio,
+    and a problem whose partial results exceed the array is refused with ERR_CAPACITY before anything is enqueued."""
+    lib, c = lt.load(), cfg()
+
+    def call(conf=c, n=500, w=16, mode=0, q=FAKE_DEV, mean=FAKE_DEV, st=128):
+        return lib.lt_lazy_ratio_static(ctypes.byref(conf), q, FAKE_DEV, n * 128 * 2, n * 128, st, n, w, mode, None, None, mean, None)
+
+    assert call(w=0) == lt.ERR_INVALID_ARG
+    assert call(mode=3) == lt.ERR_INVALID_ARG
+    assert call(q=None) == lt.ERR_INVALID_ARG
+    assert call(mean=None) == lt.ERR_INVALID_ARG
+    assert call(n=8, w=16) == lt.ERR_SHAPE
+    assert call(st=64) == lt.ERR_SHAPE
+    big = lt.make_config(1, 64, 64, 8, 128, 4, 2044, 1 << 20)       # 64 sequences x 64 heads x 64 queries x 64 key ranges
+    assert lt.lazy_ratio_workspace_bytes(big, 1 << 20, 64) > 32 << 20
+    assert call(conf=big, n=1 << 20, w=64) == lt.ERR_CAPACITY
+    # the benchmark shapes fit
+    for B, n in ((8, 32768), (32, 16384), (1, 131072), (16, 131072)):
+        shape = lt.make_config(32, B, 32, 8, 128, 4, 2044, n)
+        assert 0 < lt.lazy_ratio_workspace_bytes(shape, n, 64) <= 32 << 20, (B, n)
 
 
 def test_prefill_and_ratio_from_lse_argument_validation():
