@@ -6,7 +6,9 @@ import subprocess
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(_HERE, "csrc")
-LIB_PATH = os.path.join(_HERE, "liblt_hip.so")
+# LT_HIP_LIBRARY names another build of the same C ABI to load instead (the CPU-only sanitizer build of the host layer
+# that the test-suite makes); it is never built or rebuilt from here.
+LIB_PATH = os.environ.get("LT_HIP_LIBRARY") or os.path.join(_HERE, "liblt_hip.so")
 SOURCES = ["lt_api.cpp", "lt_decode.hip", "lt_score.hip", "lt_prefill.hip"]
 HEADERS = ["lt_kernels.h", os.path.join("..", "..", "include", "lt.h"), os.path.join("..", "..", "include", "lt_measure.h")]
 
@@ -27,6 +29,8 @@ def is_stale() -> bool:
 def build(force: bool = True, verbose: bool = False) -> str:
     """Compile the library (always when force=True; otherwise only if missing).  The translation units are
     compiled side by side, then linked."""
+    if os.environ.get("LT_HIP_LIBRARY"):
+        return LIB_PATH                         # somebody else's build: used as it is (loading fails if it is absent)
     if not force and os.path.exists(LIB_PATH):
         return LIB_PATH
     import tempfile

@@ -456,9 +456,12 @@ class Context:
         _check(load().lt_truncate_layer(self._h, int(layer), _stream_ptr(stream)), "lt_truncate_layer")
 
     def close(self):
+        """Destroys the host-side context and lets go of the slab and the workspace (views handed out by
+        layer_tensors keep the memory alive for as long as they live)."""
         if getattr(self, "_h", None):
             load().lt_destroy(self._h)
             self._h = None
+            self._slab_all = self._ws_all = self.kv_slab = self.workspace = None
 
     def __del__(self):
         try:
