@@ -117,7 +117,8 @@ lt_status lt_layer_view(const lt_ctx *ctx, int32_t layer, void **k_dev, void **v
 /* ---- lazy-layer identification ------------------------------------------------------------ */
 
 /* Bytes of device workspace lt_lazy_ratio needs for a prompt of n tokens scored over its last
- * w_last queries.  Returns 0 on invalid arguments. */
+ * w_last queries (partial sums of the key ranges, per-head sums, counters of finished ranges; the
+ * call clears the counters itself).  Returns 0 on invalid arguments. */
 size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last);
 
 /* Lazy ratio of one layer (Eq. 1): for each of the last w_last prompt positions p = n-w_last..n-1
@@ -142,14 +143,16 @@ lt_status lt_lazy_ratio(const lt_config *cfg, const void *q_last, const void *k,
 /* lt_lazy_ratio for callers that cannot allocate or bring a workspace: code recorded under stream
  * capture into a HIP graph, tight serving loops, harnesses that forbid device allocation.  Same
  * arguments, outputs, results and errors as lt_lazy_ratio, without `workspace` / `ws_bytes`: the
- * partial results live in a 32 MiB array that is part of the library's code object (one copy per
- * GPU, held until the process ends).  The call allocates nothing on host or device and frees
- * nothing; on its first use on a device it looks the array's address up (do that first call outside
- * a capture).  LT_ERR_CAPACITY, with nothing enqueued, when
- * lt_lazy_ratio_workspace_bytes(cfg, n, w_last) exceeds 32 MiB (every shape up to batch 16 x 32
- * query heads x 64 queries fits at any n).  All calls on one GPU share the array, which keeps the
- * last call's contents: two calls whose kernels may overlap on one GPU (different streams, or
- * different threads) race; calls on one stream are safe.  Nothing in it needs to start at zero. */
+ * partial sums and counters live in an 8 MiB array that is part of the library's code object (one
+ * copy per GPU, held until the process ends).  The call allocates nothing on host or device and
+ * frees nothing; on its first use on a device it looks the array's address up (do that first call
+ * outside a capture).  LT_ERR_CAPACITY, with nothing enqueued, when
+ * lt_lazy_ratio_workspace_bytes(cfg, n, w_last) exceeds 8 MiB (about 10 000 (sequence, query head)
+ * pairs at w_last = 64; every configuration of the benchmark needs less than 1 MiB).  All calls on
+ * one GPU share the array, which keeps the last call's contents: the counters in it are cleared by
+ * a small fill launch at the start of every call, nothing else needs to start at zero; two calls
+ * whose kernels may overlap on one GPU (different streams, or different threads) race; calls on one
+ * stream are safe. */
 lt_status lt_lazy_ratio_static(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b,
                                int64_t k_stride_h, int64_t k_stride_t, int64_t n, int32_t w_last,
                                lt_ratio_mode mode, float *rho_dev, float *ratio_seq_dev,

@@ -495,21 +495,47 @@ lt_status lt_layer_view(const lt_ctx *ctx, int32_t layer, void **k_dev, void **v
 
 // ---- lazy-layer identification ---------------------------------------------------------------
 
-static int score_keys_per_block(const lt_config *cfg, int64_t n)
+// Keys per workgroup of the scoring kernel for `keys` keys per (sequence, KV head) in all.  A compute unit holds two
+// workgroups of the kernel (one when a wavefront owns more than two query tiles), so the B * Hkv key streams are cut
+// into about 512 (256) ranges of equal length, multiples of kScoreTileKeys; more streams than that: one range each.
+static int score_keys_per_block(const lt_config *cfg, int64_t keys, int32_t w_last)
 {
-    // Enough workgroups to fill 256 compute units a few times; ranges are multiples of the LDS tile.
     const int64_t streams = (int64_t)cfg->batch * cfg->n_kv_heads;
-    int64_t keys = ceil_div(n * streams, 256 * 4);
-    keys = ceil_div(keys, ltk::kScoreTileKeys) * ltk::kScoreTileKeys;
-    return (int)std::min<int64_t>(std::max<int64_t>(keys, 256), 4096);
+    const int query_tiles = (cfg->n_q_heads / cfg->n_kv_heads) * ((w_last + 31) / 32);
+    const int64_t resident = ltk::score_tiles_per_wave(query_tiles) <= 2 ? 512 : 256;
+    const int64_t ranges = std::max<int64_t>(resident / streams, 1);
+    const int64_t per = ceil_div(ceil_div(keys, ranges), ltk::kScoreTileKeys) * ltk::kScoreTileKeys;
+    return (int)std::max<int64_t>(per, ltk::kScoreTileKeys);
+}
+
+// Workspace of a scoring call with `chunks` key ranges: partial sums, per-head sums of rho, counters.
+struct ScoreWorkspace {
+    size_t part_bytes, head_bytes, ticket_bytes;
+    size_t total() const { return part_bytes + head_bytes + ticket_bytes; }
+};
+
+static ScoreWorkspace score_workspace(const lt_config *cfg, int64_t chunks, int32_t w_last)
+{
+    ScoreWorkspace w;
+    w.part_bytes = align_up((size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)chunks * 3 * sizeof(float));
+    w.head_bytes = align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
+    w.ticket_bytes = align_up(((size_t)cfg->batch * cfg->n_kv_heads + 1) * sizeof(unsigned int));
+    return w;
+}
+
+static void bind_score_workspace(ltk::ScoreArgs &a, const lt_config *cfg, void *workspace)
+{
+    const ScoreWorkspace w = score_workspace(cfg, a.n_chunks, a.w_last);
+    uint8_t *base = static_cast<uint8_t *>(workspace);
+    a.part = reinterpret_cast<float *>(base);
+    a.head_scratch = reinterpret_cast<float *>(base + w.part_bytes);
+    a.tickets = reinterpret_cast<unsigned int *>(base + w.part_bytes + w.head_bytes);
 }
 
 size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last)
 {
     if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n <= 0 || w_last <= 0 || w_last > 64) return 0;
-    const int64_t chunks = ceil_div(n, score_keys_per_block(cfg, n));
-    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * chunks) * 3 * sizeof(float);
-    return align_up(part) + align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
+    return score_workspace(cfg, ceil_div(n, score_keys_per_block(cfg, n, w_last)), w_last).total();
 }
 
 // The dense form behind lt_lazy_ratio and lt_lazy_ratio_static.  workspace == nullptr selects the library's
@@ -543,15 +569,13 @@ static lt_status lazy_ratio_dense(const lt_config *cfg, const void *q_last, cons
     a.w_sink = cfg->w_sink;
     a.w_recent = cfg->w_recent;
     a.fixed_mode = mode == LT_RECENT_FIXED ? 1 : 0;
-    a.keys_per_block = score_keys_per_block(cfg, n);
+    a.keys_per_block = score_keys_per_block(cfg, n, w_last);
     a.n_chunks = (int32_t)ceil_div(n, a.keys_per_block);
     a.range_a_end = n;
     a.range_b_begin = n;
     a.n_chunks_a = a.n_chunks;
     a.scale_log2e = effective_scale(cfg) * kLog2e;
-    a.part = static_cast<float *>(workspace);
-    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * a.n_chunks) * 3 * sizeof(float);
-    a.head_scratch = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(part));
+    bind_score_workspace(a, cfg, workspace);
     a.rho = rho_dev;
     a.ratio_seq = ratio_seq_dev;
     a.ratio_mean = ratio_mean_dev;
@@ -591,7 +615,7 @@ static WindowPlan window_plan(const lt_config *cfg, int64_t n, int32_t w_last, l
     int64_t first_recent = mode == LT_RECENT_FIXED ? n - cfg->w_recent : n - w_last - (int64_t)cfg->w_recent + 1;
     first_recent = std::min<int64_t>(std::max<int64_t>(first_recent, 0), n);
     p.b_begin = std::max<int64_t>(p.a_end, first_recent / tile * tile);
-    p.keys_per_block = score_keys_per_block(cfg, p.a_end + (n - p.b_begin));
+    p.keys_per_block = score_keys_per_block(cfg, p.a_end + (n - p.b_begin), w_last);
     p.chunks_a = (int32_t)ceil_div(p.a_end, p.keys_per_block);
     p.chunks_b = (int32_t)ceil_div(n - p.b_begin, p.keys_per_block);
     return p;
@@ -602,8 +626,7 @@ size_t lt_lazy_ratio_lse_workspace_bytes(const lt_config *cfg, int64_t n, int32_
     if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n <= 0 || w_last <= 0 || w_last > 64 || w_last > n) return 0;
     const WindowPlan p = window_plan(cfg, n, w_last, LT_RECENT_PER_QUERY), f = window_plan(cfg, n, w_last, LT_RECENT_FIXED);
     const int64_t chunks = std::max(p.chunks_a + p.chunks_b, f.chunks_a + f.chunks_b);       // either reading fits
-    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * chunks) * 3 * sizeof(float);
-    return align_up(part) + align_up((size_t)cfg->batch * cfg->n_q_heads * sizeof(float));
+    return score_workspace(cfg, chunks, w_last).total();
 }
 
 lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void *k, int64_t k_stride_b, int64_t k_stride_h,
@@ -650,9 +673,7 @@ lt_status lt_lazy_ratio_lse(const lt_config *cfg, const void *q_last, const void
     a.lse_stride_b = lse_stride_b;
     a.lse_stride_h = lse_stride_h;
     a.scale_log2e = effective_scale(cfg) * kLog2e;
-    a.part = static_cast<float *>(workspace);
-    const size_t part = (size_t)cfg->batch * cfg->n_q_heads * (size_t)w_last * (size_t)(2 * a.n_chunks) * 3 * sizeof(float);
-    a.head_scratch = reinterpret_cast<float *>(static_cast<uint8_t *>(workspace) + align_up(part));
+    bind_score_workspace(a, cfg, workspace);
     a.rho = rho_dev;
     a.ratio_seq = ratio_seq_dev;
     a.ratio_mean = ratio_mean_dev;

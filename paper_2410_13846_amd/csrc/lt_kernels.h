@@ -15,7 +15,10 @@ constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
 constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head) is split into
 constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels
 constexpr int kMaxRaggedBatch = 64;    // sequences a launch can give their own lengths (the lengths travel as kernel arguments)
-constexpr int kScoreTileKeys = 64;     // keys staged in LDS per step of the scoring kernel
+constexpr int kScoreTileKeys = 128;    // key ranges of the scoring kernel are multiples of this
+// 32-query tiles each of the scoring kernel's four wavefronts owns, for QT = (Hq / Hkv) * ceil(w_last / 32) tiles in all;
+// up to two, two workgroups share a compute unit
+constexpr int score_tiles_per_wave(int QT) { return (QT + 3) / 4; }
 
 struct AppendArgs {
     const uint16_t *k_new, *v_new;     // [B][Hkv][n_new][128]
@@ -96,8 +99,9 @@ struct ScoreArgs {
     const float *lse_rows;             // natural-log LSE of the causal rows n-w..n-1, or nullptr: computed here
     int64_t lse_stride_b, lse_stride_h;
     float scale_log2e;
-    float *part;                       // [B][Hq][n_chunks][2][3][w]: max (log2 units), causal sum, kept sum
+    float *part;                       // [B][Hq][n_chunks][3][w]: max (log2 units), causal sum, kept sum
     float *head_scratch;               // [B][Hq] sum of rho over the queries of a head
+    unsigned int *tickets;             // [B * Hkv + 1] counters of finished key ranges / finished (sequence, KV head) pairs
     float *rho, *ratio_seq, *ratio_mean;
 };
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);
@@ -105,7 +109,7 @@ hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream);
 // Device address, on the current device, of the library's built-in scratch array of
 // kStaticScratchBytes bytes (256-byte aligned; zero when the code object is loaded, afterwards it
 // keeps what the last launch left).  Looked up once per device; allocates nothing.
-constexpr size_t kStaticScratchBytes = (size_t)32 << 20;
+constexpr size_t kStaticScratchBytes = (size_t)8 << 20;
 hipError_t static_scratch(void **ptr);
 
 struct PrefillArgs {

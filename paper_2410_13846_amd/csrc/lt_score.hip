@@ -3,11 +3,18 @@
 // on the fly to two sums per query -- the softmax denominator over the causal set and the part
 // of it that falls on the initial + recent keys.  No attention matrix and no V are touched.
 //
-// One workgroup = one (sequence, KV head, range of keys); wavefront i of the workgroup owns
-// query head g*G + i, so the G heads that share the KV head read each key tile from LDS once.
+// One launch.  One workgroup (four wavefronts, one per SIMD, the whole register file) = one
+// (sequence, KV head, range of keys).  K tiles travel from global memory straight into LDS
+// (global_load_lds_dwordx4, three stages, two tiles in flight), laid out with an XOR swizzle of
+// the 16-byte pieces of a row so that the matrix-operand reads are free of bank conflicts.
 // S^T = K Q^T is formed with v_mfma_f32_32x32x16_bf16: keys are the rows, queries the columns,
 // so each lane keeps 16 key logits of ONE query per instruction and the running max / sums
-// stay private to the lane until the final merge.
+// stay private to the lane until the final merge.  A wavefront owns up to four 32-query tiles
+// (of one or two heads of the group): every K fragment read from LDS feeds that many matrix
+// instructions.  The matrix instructions of one 32-key sub-tile are issued in the same
+// instruction stream as the exponentials of the previous sub-tile (two accumulator sets).
+// The workgroup that finishes last for a (sequence, KV head) merges the key ranges, and the one
+// that finishes last overall forms the means: the order of every sum is fixed.
 #include "lt_kernels.h"
 
 #include <mutex>
@@ -97,15 +104,16 @@ __device__ __forceinline__ void update_quick(const floatx16_t &c, LaneState &st,
     }
 }
 
+// j_end: keys from j_end on belong to another workgroup's range (or lie past the prompt) and are left out.
 __device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st, float scale_log2e, int j_base,
-                                              int p, int n, int w_sink, int w_recent, int fixed_mode)
+                                              int p, int n, int w_sink, int w_recent, int fixed_mode, int j_end)
 {
     // key row of accumulator register i in this lane: j_base + 8*(i/4) + (i%4)
     float tmax = -INFINITY;
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int j = j_base + 8 * (i >> 2) + (i & 3);
-        if (j <= p) tmax = fmaxf(tmax, c[i]);
+        if (j <= p && j < j_end) tmax = fmaxf(tmax, c[i]);
     }
     const float m_new = fmaxf(st.m, tmax * scale_log2e);
     if (m_new == -INFINITY) return;                           // nothing causal seen so far
@@ -114,7 +122,7 @@ __device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
         const int j = j_base + 8 * (i >> 2) + (i & 3);
-        const bool causal = j <= p;
+        const bool causal = j <= p && j < j_end;
         const bool recent = fixed_mode ? (j >= n - w_recent) : (j > p - w_recent);
         const float e = causal ? fast_exp2(fmaf(c[i], scale_log2e, -m_new)) : 0.f;
         sum += e;
@@ -125,55 +133,87 @@ __device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st
     st.m = m_new;
 }
 
-// A 64-key tile is 1024 16-byte pieces (coalesced rows of 256 B) spread over the workgroup.
-// fetch_tile() starts the global loads into registers, commit_tile() parks them in LDS; the MFMA
-// work of the current tile runs between the two so the load latency is covered.
-template <int G>
-struct Staging {
-    static constexpr int kThreads = 64 * G;
-    static constexpr int kTotal = kScoreTileKeys * 16;
-    static constexpr int kPieces = (kTotal + kThreads - 1) / kThreads;
-};
 
-template <int G>
-__device__ __forceinline__ void fetch_tile(u32x4_t (&pre)[Staging<G>::kPieces], const uint16_t *kb, int64_t stride_t, int j0, int n)
+// ---------------------------------------------------------------------------------------------
+// Staging: a tile of TK keys is TK rows of 256 bytes.  Piece c (16 bytes) of row r lives at byte
+// r * 256 + ((c ^ (r & 15)) << 4) of its stage.  A wavefront's global_load_lds instruction writes
+// 1 KB = four whole rows, lane l to byte 16 * l after the (uniform) destination, so lane l
+// fetches piece (l & 15) ^ (row & 15) of row (l >> 4): still one coalesced kilobyte of memory.
+// ---------------------------------------------------------------------------------------------
+constexpr int kScoreStages = 4;                              // LDS stages of a workgroup: three tiles under way
+constexpr int kScoreThreads = 256;
+
+// One global -> LDS load of 16 bytes per lane: lane l's bytes land at LDS byte address lds_base + 16 * l (lds_base is
+// uniform and travels in M0).  Written as inline assembly on purpose: for the compiler's own form of this load the
+// wait-count insertion makes every later LDS read wait for ALL loads of this kind that are still under way, the
+// prefetched tiles included, which would serialise the pipeline.  Here the waits are explicit (wait_vmcnt below; these
+// loads count in vmcnt like any other).  No other instruction of these kernels uses M0.
+__device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_base)
 {
-#pragma unroll
-    for (int i = 0; i < Staging<G>::kPieces; ++i) {
-        int idx = threadIdx.x + i * Staging<G>::kThreads;
-        idx = idx < Staging<G>::kTotal ? idx : Staging<G>::kTotal - 1;   // surplus threads re-read the last piece
-        int j = j0 + (idx >> 4);
-        j = j < n ? j : n - 1;                                          // clamp; such keys are masked as non-causal
-        pre[i] = *reinterpret_cast<const u32x4_t *>(kb + (int64_t)j * stride_t + (idx & 15) * 8);
-    }
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_base) : "memory");
+}
+__device__ __forceinline__ uint32_t lds_address(const void *p)
+{
+    return (uint32_t)(uintptr_t)(const __attribute__((address_space(3))) char *)p;
 }
 
-template <int G>
-__device__ __forceinline__ void commit_tile(const u32x4_t (&pre)[Staging<G>::kPieces], uint16_t *sh)
+// Workgroup barrier without a fence: the waits that order LDS traffic around it are written out by hand
+// (a fence would wait for ALL outstanding global-to-LDS loads, the prefetched tiles included).
+__device__ __forceinline__ void barrier_no_fence()
 {
-#pragma unroll
-    for (int i = 0; i < Staging<G>::kPieces; ++i) {
-        const int idx = threadIdx.x + i * Staging<G>::kThreads;
-        if (idx < Staging<G>::kTotal) *reinterpret_cast<u32x4_t *>(&sh[(idx >> 4) * kRowElems + (idx & 15) * 8]) = pre[i];
-    }
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
 }
 
-// G: query heads per KV head.  QH: wavefronts per head, each with its own 32 * NT queries (G * QH wavefronts
-// per workgroup).  NT: 32-query column tiles per wavefront.  w <= 32: <G, 1, 1>; w <= 64: <G, 1, 2> for groups of
-// up to four heads (more, lighter wavefronts per SIMD), <G, 2, 1> otherwise.
-template <int G, int NT, int QH>
-__global__ __launch_bounds__(64 * G * QH, 2) void lt_lazy_ratio_partial_kernel(ScoreArgs a)
+// s_waitcnt vmcnt(N) for gfx9 (bits 3:0 and 15:14), the other counters left at their maxima
+template <int N>
+__device__ __forceinline__ void wait_vmcnt()
 {
-    constexpr int W = G * QH;
-    __shared__ __attribute__((aligned(16))) uint16_t sh_k[2][kScoreTileKeys * kRowElems];
+    static_assert(N >= 0 && N < 64, "vmcnt has six bits");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
 
-    constexpr int kPieces = Staging<W>::kPieces;
+__device__ __forceinline__ void publish(float *p, float v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+__device__ __forceinline__ float observe(const float *p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
+
+// Merge (m2, c2, k2) into (m, c, k): two partial softmax sums with their references (log2 units).
+__device__ __forceinline__ void merge_state(float &m, float &c, float &k, float m2, float c2, float k2)
+{
+    if (m2 == -INFINITY) return;
+    const float m_new = fmaxf(m, m2);
+    const float keep = fast_exp2(m - m_new), add = fast_exp2(m2 - m_new);      // keep = 0 while m = -inf
+    c = c * keep + add * c2;
+    k = k * keep + add * k2;
+    m = m_new;
+}
+
+// NT: 32-query tiles per wavefront (1..4): the query tiles of a KV head's group are dealt to the four wavefronts, and
+// every wavefront contracts every key (both 32-key sub-tiles of each 64-key LDS tile).  Up to two query tiles per
+// wavefront leave room for two workgroups per compute unit (two wavefronts per SIMD, each filling the other's stalls);
+// more tiles need the whole register file.
+template <int NT>
+__global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_kernel(ScoreArgs a)
+{
+    constexpr int TK = 64;                                      // keys per tile
+    constexpr int kStageBytes = TK * 256;
+    constexpr int kLoads = TK * 16 / kScoreThreads;             // global_load_lds per wavefront and tile (4)
+    constexpr int kGroups = 4, KW = 1;
+    // The only LDS object of the kernel, so it starts at LDS address 0 and every tile load lands below 64 KB.
+    // After the tile loop the same memory carries the lane states, the ratios and a flag.
+    __shared__ __attribute__((aligned(1024))) char sh_all[kScoreStages * kStageBytes];
+    static_assert(kScoreStages * kStageBytes <= 65536, "tile loads address LDS through a 16-bit offset");
+    static_assert(kScoreStages * kStageBytes >= 32768, "the lane states, the ratios and the flag live in the first 32 KB");
+    int *sh_flag = reinterpret_cast<int *>(sh_all + 32768 - 64);            // past the states (12 KB)
+
     const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it stays in scalar registers
     const int col = lane & 31, half = lane >> 5;
-    const int h = g * G + wave % G;
-    const int q_off = (wave / G) * 32 * NT;                              // first query of this wavefront among the w_last
+    const int tg = wave;                                        // tile group of this wavefront
+    const int G = a.n_q_heads / a.n_kv_heads;
+    const int QH = (a.w_last + 31) >> 5;                        // 32-query tiles per head
+    const int QT = G * QH;                                      // query tiles of this KV head's group
 
     const int n = (int)a.n;
     const int w_sink = min(a.w_sink, n), w_recent = min(a.w_recent, n);   // a window longer than the prompt is the prompt
@@ -185,199 +225,331 @@ __global__ __launch_bounds__(64 * G * QH, 2) void lt_lazy_ratio_partial_kernel(S
         begin_key = (int)a.range_b_begin + (chunk - a.n_chunks_a) * a.keys_per_block;
         end_key = min(n, begin_key + a.keys_per_block);
     }
-    const int n_tiles = (end_key - begin_key + kScoreTileKeys - 1) / kScoreTileKeys;
+    const int n_tiles = (end_key - begin_key + TK - 1) / TK;
     const uint16_t *kb = a.k + (int64_t)b * a.k_stride_b + (int64_t)g * a.k_stride_h;
+    const uint16_t *hot = a.q_last + ((int64_t)b * a.n_q_heads + g * G) * a.w_last * kHeadDim;   // a line that is in cache anyway
 
-    // Q^T fragments (B operand): lane holds, for its query column, the 8 dims 16*s + 8*half .. +7
+    // ---- tile loads ---------------------------------------------------------------------------------------
+    // this lane's row inside a 16-row block and the piece it fetches (see the layout above)
+    const int my_row = wave * 4 + (lane >> 4);
+    const int my_piece = (lane & 15) ^ (my_row & 15);
+    int next_issue = 0;
+    const uint32_t lds_base = lds_address(sh_all);              // 0
+    // source of this lane's first load of the next tile; the tile's other loads are 16 rows apart each
+    const uint16_t *next_src = kb + (int64_t)(begin_key + my_row) * a.k_stride_t + my_piece * 8;
+    const int64_t rows16 = 16 * a.k_stride_t;
+    auto issue = [&]() __attribute__((always_inline)) {        // tile `next_issue` -> stage next_issue % 4; past the last tile: dummy loads
+        const int j0 = begin_key + next_issue * TK;
+        const uint32_t stage_base = lds_base + (next_issue & (kScoreStages - 1)) * kStageBytes;
+        if (next_issue < n_tiles && j0 + TK <= n) {             // the common case: every row exists
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) load_to_lds(next_src + i * rows16, stage_base + (i * 16 + wave * 4) * 256);
+        } else {
+#pragma unroll
+            for (int i = 0; i < kLoads; ++i) {
+                int j = j0 + i * 16 + my_row;
+                j = j < n ? j : n - 1;                          // rows past the prompt repeat its last key; they are masked
+                const uint16_t *src = next_issue < n_tiles ? kb + (int64_t)j * a.k_stride_t + my_piece * 8 : hot + (lane & 15) * 8;
+                load_to_lds(src, stage_base + (i * 16 + wave * 4) * 256);
+            }
+        }
+        next_src += TK * a.k_stride_t;
+        ++next_issue;
+    };
+
+    // ---- Q^T fragments (B operand): lane holds, for its query column, the 8 dims 16*s + 8*half .. +7 ---------
     bf16x8_t qf[NT][8];
+    int q_pos[NT];                                              // prompt position of this lane's query column per tile
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) {
-        const int t = q_off + nt * 32 + col;
+        const int qt = tg * NT + nt;
+        const int h = g * G + qt / QH;
+        const int t = (qt % QH) * 32 + col;
+        const bool live = qt < QT && t < a.w_last;
+        q_pos[nt] = n - a.w_last + t;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
             uint4 u = make_uint4(0u, 0u, 0u, 0u);
-            if (t < a.w_last)
+            if (live)
                 u = *reinterpret_cast<const uint4 *>(a.q_last + (((int64_t)b * a.n_q_heads + h) * a.w_last + t) * kHeadDim +
                                                      16 * s + 8 * half);
             qf[nt][s] = __builtin_bit_cast(bf16x8_t, u);
         }
     }
-
-    // The query fragments must have arrived on every path into the tile loop: otherwise the compiler, which
-    // cannot tell how many newer loads may be outstanding, makes the first matrix instruction of EVERY tile wait
-    // for all outstanding loads, the K prefetch issued just before it included.
-    __builtin_amdgcn_s_waitcnt(kWaitVmcnt0);
+    // the fragments have arrived before any tile load is counted
+    wait_vmcnt<0>();
 
     LaneState st[NT];
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { st[nt].m = -INFINITY; st[nt].sum_causal = 0.f; st[nt].sum_kept = 0.f; }
 
-    // S^T for one 32-key sub-tile: 8 k-steps of 16 dims, NT column tiles of 32 queries.
-    auto contract = [&](floatx16_t (&c)[NT], const uint16_t *tile, int kt) {
+    // LDS byte offset of this lane's K fragment for k-step s of sub-tile `sub`: row 32 * sub + col, piece 2s + half
+    const int frag_x = (half ^ (col & 15)) << 4;
+    auto k_fragment = [&](const char *stage, int s) __attribute__((always_inline)) {     // `stage` points at the sub-tile
+        const int byte = col * 256 + (frag_x ^ (s << 5));
+        return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(stage + byte));
+    };
+
+    // Fold one sub-tile's logits (masked form): per-element predicates of Eq. 1, and keys outside this workgroup's range out
+    auto fold_masked = [&](const floatx16_t (&c)[NT], int j0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+            update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, q_pos[nt], n, w_sink, w_recent, a.fixed_mode, end_key);
+    };
+    // Is the whole sub-tile on the mask-free path?
+    auto fast_class = [&](int j0, bool &kept) __attribute__((always_inline)) {
+        const TileClass cls = classify(j0, n, a.w_last, w_sink, w_recent, a.fixed_mode);
+        kept = cls.kept;
+        return cls.fast && j0 + 32 <= end_key;
+    };
+
+    // Contract this wavefront's sub-tile of `stage` into `next` while folding `prev` (the logits of the sub-tile that began at key
+    // j_prev; j_prev < 0: nothing to fold).  On the mask-free path the exponentials of `prev` are issued between the
+    // matrix instructions of `next`, two accumulator registers per tile and k-step, against each lane's current
+    // reference; the sums are taken only if they stay within 2^12 in every lane, else `prev` is folded again the
+    // long way, which moves the reference (any reference gives the same quotient of the two sums).
+    auto step = [&](floatx16_t (&next)[NT], const char *stage, const floatx16_t (&prev)[NT], int j_prev) __attribute__((always_inline)) {
+        bool kept = false;
+        const bool quick = j_prev >= 0 && fast_class(j_prev, kept);
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-            for (int i = 0; i < 16; ++i) c[nt][i] = 0.f;
+            for (int i = 0; i < 16; ++i) next[nt][i] = 0.f;
+        if (quick) {
+            float sum[NT];
 #pragma unroll
-        for (int s = 0; s < 8; ++s) {
-            const u32x4_t u = *reinterpret_cast<const u32x4_t *>(&tile[(32 * kt + col) * kRowElems + 16 * s + 8 * half]);
-            const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, u);
+            for (int nt = 0; nt < NT; ++nt) sum[nt] = 0.f;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) c[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], c[nt], 0, 0, 0);
-        }
-    };
-    // Fold one sub-tile's logits into the running max and the two sums of every query column.
-    auto fold = [&](const floatx16_t (&c)[NT], int j0) {
-        const TileClass cls = classify(j0, n, a.w_last, w_sink, w_recent, a.fixed_mode);
-        if (cls.fast) {
+            for (int s = 0; s < 8; ++s) {
+                const bf16x8_t kf = k_fragment(stage, s);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) update_quick(c[nt], st[nt], a.scale_log2e, cls.kept);
-        } else {
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const int p = n - a.w_last + q_off + nt * 32 + col;     // query position of this lane's column
-                update_masked(c[nt], st[nt], a.scale_log2e, j0 + 4 * half, p, n, w_sink, w_recent, a.fixed_mode);
-            }
-        }
-    };
-
-    // Two wavefronts per SIMD (from two workgroups) overlap one's matrix-core work with the
-    // other's exponentials.  The K tiles are prefetched two tiles ahead in two register sets, so
-    // a global load has two tiles of compute (about 2.5 us) to arrive before it is parked in LDS.
-    auto compute = [&](const uint16_t *tile, int j0) {
-#pragma unroll
-        for (int kt = 0; kt < kScoreTileKeys / 32; ++kt) {
-            if (j0 + 32 * kt >= end_key) break;
-            floatx16_t c[NT];
-            contract(c, tile, kt);
-            fold(c, j0 + 32 * kt);
-        }
-    };
-    auto tile_key = [&](int tile) { return begin_key + tile * kScoreTileKeys; };
-
-    u32x4_t pre_even[kPieces], pre_odd[kPieces];
-    if (n_tiles > 0) {
-        fetch_tile<W>(pre_even, kb, a.k_stride_t, tile_key(0), n);
-        commit_tile<W>(pre_even, sh_k[0]);
-    }
-    __syncthreads();
-    if (n_tiles > 1) fetch_tile<W>(pre_odd, kb, a.k_stride_t, tile_key(1), n);
-    for (int tile = 0; tile < n_tiles; tile += 2) {
-        if (tile + 2 < n_tiles) fetch_tile<W>(pre_even, kb, a.k_stride_t, tile_key(tile + 2), n);
-        compute(sh_k[0], tile_key(tile));
-        if (tile + 1 < n_tiles) {
-            commit_tile<W>(pre_odd, sh_k[1]);
-            __syncthreads();
-            if (tile + 3 < n_tiles) fetch_tile<W>(pre_odd, kb, a.k_stride_t, tile_key(tile + 3), n);
-            compute(sh_k[1], tile_key(tile + 1));
-            if (tile + 2 < n_tiles) {
-                commit_tile<W>(pre_even, sh_k[0]);
-                __syncthreads();
-            }
-        }
-    }
-
-    // partial layout [B][Hq][chunk][half][field][w]: each store below is contiguous over the query columns
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int t = q_off + nt * 32 + col;
-        if (t < a.w_last) {
-            float *dst = a.part + ((((int64_t)b * a.n_q_heads + h) * a.n_chunks + chunk) * 2 + half) * 3 * a.w_last + t;
-            dst[0] = st[nt].m;
-            dst[a.w_last] = st[nt].sum_causal;
-            dst[2 * a.w_last] = st[nt].sum_kept;
-        }
-    }
-}
-
-// rho per (sequence, head, query): one workgroup per (sequence, head), one thread per query,
-// merging the chunk partials by their running maxima; the head's sum of rho goes to scratch.
-// Fixed-order reductions: the result does not depend on scheduling.
-__global__ __launch_bounds__(64) void lt_lazy_ratio_finish_kernel(ScoreArgs a)
-{
-    __shared__ float sh_sum[64];
-    const int h = blockIdx.x, b = blockIdx.y, t = threadIdx.x;
-    const int n_part = 2 * a.n_chunks;
-    float rho = 0.f;
-    if (t < a.w_last) {
-        const float *src = a.part + ((int64_t)b * a.n_q_heads + h) * n_part * 3 * a.w_last + t;
-        float mx = -INFINITY, causal = 0.f, kept = 0.f;
-        for (int c0 = 0; c0 < n_part; c0 += 8) {              // eight partials per round trip
-            float m[8], f[8], k[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float *pc = src + (int64_t)min(c0 + u, n_part - 1) * 3 * a.w_last;
-                m[u] = pc[0];
-                f[u] = pc[a.w_last];
-                k[u] = pc[2 * a.w_last];
-            }
-#pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                if (c0 + u < n_part && m[u] != -INFINITY) {
-                    const float m_new = fmaxf(mx, m[u]);
-                    const float keep = fast_exp2(mx - m_new), add = fast_exp2(m[u] - m_new);
-                    causal = causal * keep + add * f[u];
-                    kept = kept * keep + add * k[u];
-                    mx = m_new;
+                for (int nt = 0; nt < NT; ++nt) {
+                    next[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], next[nt], 0, 0, 0);
+                    sum[nt] += fast_exp2(fmaf(prev[nt][2 * s], a.scale_log2e, -st[nt].m));
+                    sum[nt] += fast_exp2(fmaf(prev[nt][2 * s + 1], a.scale_log2e, -st[nt].m));
                 }
             }
-        }
-        if (a.lse_rows != nullptr) {
-            // Table 1: the chunks covered only the initial and recent keys; the whole row's
-            // denominator comes from the prefill attention's log-sum-exp
-            const float lse = a.lse_rows[(int64_t)b * a.lse_stride_b + (int64_t)h * a.lse_stride_h + t];
-            rho = mx == -INFINITY ? 0.f : kept * fast_exp2(mx - lse * 1.44269504088896340736f);
+            bool ok = true;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) ok = ok && sum[nt] <= kQuickSumLimit;
+            if (__all(ok)) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    st[nt].sum_causal += sum[nt];
+                    st[nt].sum_kept += kept ? sum[nt] : 0.f;
+                }
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) update_fast(prev[nt], st[nt], a.scale_log2e, kept);
+            }
         } else {
-            rho = kept / causal;
+#pragma unroll
+            for (int s = 0; s < 8; ++s) {
+                const bf16x8_t kf = k_fragment(stage, s);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) next[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], next[nt], 0, 0, 0);
+            }
+            if (j_prev >= 0 && j_prev < end_key) fold_masked(prev, j_prev);
         }
-        if (a.rho != nullptr) a.rho[((int64_t)b * a.n_q_heads + h) * a.w_last + t] = rho;
+    };
+
+    // ---- main loop: tile t sits in stage t % 4; tiles t + 1 .. t + 3 are on their way -------------------------------------
+    constexpr int kAhead = kScoreStages - 1;
+    floatx16_t acc_a[NT], acc_b[NT];
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) issue();
+    wait_vmcnt<(kAhead - 1) * kLoads>();                        // this wavefront's part of tile 0 has landed
+    barrier_no_fence();                                         // ... and everybody else's
+    int j_pending = -1;                                         // first key of the sub-tile whose logits wait (in acc_b) to be folded
+    for (int tile = 0; tile < n_tiles; ++tile) {
+        issue();                                                // tile + 3 -> the stage tile - 1 was read from (all past the last barrier)
+        const char *stage = sh_all + (tile & (kScoreStages - 1)) * kStageBytes;
+        const int j0 = begin_key + tile * TK;
+        step(acc_a, stage, acc_b, j_pending);                   // first 32 keys, while the previous tile's second half is folded
+        step(acc_b, stage + 32 * 256, acc_a, j0);               // second 32 keys, while the first half is folded
+        j_pending = j0 + 32;
+        wait_vmcnt<(kAhead - 1) * kLoads>();                    // tile + 1 has landed (the two after it may still be under way)
+        barrier_no_fence();                                     // everybody is done reading tile `tile`, and tile + 1 is complete
     }
-    sh_sum[t] = rho;
+    wait_vmcnt<0>();                                            // the dummy loads past the last tile
+    if (j_pending >= 0 && j_pending < end_key) {
+        bool kept = false;
+        if (fast_class(j_pending, kept)) {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) update_quick(acc_b[nt], st[nt], a.scale_log2e, kept);
+        } else {
+            fold_masked(acc_b, j_pending);
+        }
+    }
+    barrier_no_fence();                                         // the stages are free: they carry the lane states next
+
+    // ---- merge the lanes and wavefronts that saw different keys of the same query ----------------------------------------------
+    float *sh_state = reinterpret_cast<float *>(sh_all);  // [wave][nt][3][64]
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        float *dst = sh_state + ((wave * NT + nt) * 3) * 64 + lane;
+        dst[0] = st[nt].m;
+        dst[64] = st[nt].sum_causal;
+        dst[128] = st[nt].sum_kept;
+    }
     __syncthreads();
-    for (int step = 32; step > 0; step >>= 1) {
-        if (t < step) sh_sum[t] += sh_sum[t + step];
+    // entry e = (query tile qt, column): at most 16 * 32 = 512 of them, two rounds of the 256 threads
+    constexpr int kRounds = 2;
+    float fin_m[kRounds], fin_c[kRounds], fin_k[kRounds];
+    const bool single = a.n_chunks == 1;
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int e = threadIdx.x + r * kScoreThreads;
+        const int qt = e >> 5, c = e & 31;
+        fin_m[r] = -INFINITY; fin_c[r] = 0.f; fin_k[r] = 0.f;
+        const int t = (qt % QH) * 32 + c;
+        if (qt >= QT || t >= a.w_last) continue;
+        const int src_tg = qt / NT, src_nt = qt % NT;
+#pragma unroll
+        for (int way = 0; way < KW; ++way)
+#pragma unroll
+            for (int hf = 0; hf < 2; ++hf) {
+                const float *src = sh_state + (((way * kGroups + src_tg) * NT + src_nt) * 3) * 64 + hf * 32 + c;
+                merge_state(fin_m[r], fin_c[r], fin_k[r], src[0], src[64], src[128]);
+            }
+        if (!single) {
+            const int h = g * G + qt / QH;
+            float *dst = a.part + (((int64_t)b * a.n_q_heads + h) * a.n_chunks + chunk) * 3 * a.w_last + t;
+            publish(dst, fin_m[r]);
+            publish(dst + a.w_last, fin_c[r]);
+            publish(dst + 2 * a.w_last, fin_k[r]);
+        }
+    }
+
+    // ---- the last workgroup of a (sequence, KV head) merges the key ranges ------------------------------------------------
+    // Ordering: device-scope stores complete (vmcnt 0) in every thread, barrier, then one thread takes the ticket
+    // with a device-scope atomic; the workgroup that sees the last ticket issues its device-scope loads only after.
+    if (!single) {
+        wait_vmcnt<0>();
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            const unsigned int mine = __hip_atomic_fetch_add(a.tickets + (int64_t)b * a.n_kv_heads + g, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            *sh_flag = mine == (unsigned int)(a.n_chunks - 1);
+        }
+        __syncthreads();
+        if (!*sh_flag) return;
+#pragma unroll
+        for (int r = 0; r < kRounds; ++r) {
+            const int e = threadIdx.x + r * kScoreThreads;
+            const int qt = e >> 5, c = e & 31;
+            const int t = (qt % QH) * 32 + c;
+            fin_m[r] = -INFINITY; fin_c[r] = 0.f; fin_k[r] = 0.f;
+            if (qt >= QT || t >= a.w_last) continue;
+            const int h = g * G + qt / QH;
+            const float *src = a.part + ((int64_t)b * a.n_q_heads + h) * a.n_chunks * 3 * a.w_last + t;
+            constexpr int kBatch = 16;                              // key ranges per round trip (48 loads), merged in range order
+            for (int c0 = 0; c0 < a.n_chunks; c0 += kBatch) {
+                float m[kBatch], f[kBatch], k[kBatch];
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u) {
+                    const float *pc = src + (int64_t)min(c0 + u, a.n_chunks - 1) * 3 * a.w_last;
+                    m[u] = observe(pc);
+                    f[u] = observe(pc + a.w_last);
+                    k[u] = observe(pc + 2 * a.w_last);
+                }
+#pragma unroll
+                for (int u = 0; u < kBatch; ++u)
+                    if (c0 + u < a.n_chunks) merge_state(fin_m[r], fin_c[r], fin_k[r], m[u], f[u], k[u]);
+            }
+        }
+    }
+
+    // ---- rho of every (head, query) of the group, and the heads' sums -----------------------------------------------------------
+    float *sh_rho = sh_state;                                   // [QT * 32]; the states in there have been consumed
+    __syncthreads();
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int e = threadIdx.x + r * kScoreThreads;
+        const int qt = e >> 5, c = e & 31;
+        const int t = (qt % QH) * 32 + c;
+        float rho = 0.f;
+        if (qt < QT && t < a.w_last) {
+            const int h = g * G + qt / QH;
+            if (a.lse_rows != nullptr) {
+                // Table 1: the key ranges covered only the initial and recent keys; the whole row's denominator
+                // comes from the prefill attention's log-sum-exp
+                const float lse = a.lse_rows[(int64_t)b * a.lse_stride_b + (int64_t)h * a.lse_stride_h + t];
+                rho = fin_m[r] == -INFINITY ? 0.f : fin_k[r] * fast_exp2(fin_m[r] - lse * 1.44269504088896340736f);
+            } else {
+                rho = fin_k[r] / fin_c[r];
+            }
+            if (a.rho != nullptr) a.rho[((int64_t)b * a.n_q_heads + h) * a.w_last + t] = rho;
+        }
+        if (e < 16 * 32) sh_rho[e] = rho;
+    }
+    __syncthreads();
+    // a head's sum of rho: wavefront w takes heads w, w + 4, ...; lane t holds query t, then a butterfly over the 64 lanes
+    // (a fixed order of additions)
+    for (int hh = wave; hh < G; hh += 4) {
+        float v = lane < a.w_last ? sh_rho[(hh * QH + (lane >> 5)) * 32 + (lane & 31)] : 0.f;
+#pragma unroll
+        for (int mask = 32; mask > 0; mask >>= 1) v += __shfl_xor(v, mask, 64);
+        if (lane == 0) publish(a.head_scratch + (int64_t)b * a.n_q_heads + g * G + hh, v);
+    }
+
+    // ---- the last (sequence, KV head) to get here forms the means -------------------------------------------------------------
+    wait_vmcnt<0>();
+    __syncthreads();
+    const int n_groups_total = a.batch * a.n_kv_heads;
+    unsigned int *done = a.tickets + n_groups_total;
+    if (threadIdx.x == 0) {
+        const unsigned int mine = __hip_atomic_fetch_add(done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        *sh_flag = mine == (unsigned int)(n_groups_total - 1);
+    }
+    __syncthreads();
+    if (!*sh_flag) return;
+    // The heads' sums of several sequences at a time come into LDS with one load per thread and round trip; one
+    // thread per sequence then adds its heads in order.
+    constexpr int kHeadSlots = 4096;                            // floats of LDS for the heads' sums (16 KB)
+    float *sh_heads = sh_state;
+    float *sh_sum = sh_state + kHeadSlots;                      // [256]
+    const int seqs_per_pass = max(1, min(kScoreThreads, kHeadSlots / a.n_q_heads));
+    float mine = 0.f;
+    for (int b0 = 0; b0 < a.batch; b0 += seqs_per_pass) {
+        const int n_seq = min(seqs_per_pass, a.batch - b0);
+        float rseq = 0.f;
+        if (a.n_q_heads <= kHeadSlots) {
+            __syncthreads();                                    // the previous pass has been read
+            for (int i = threadIdx.x; i < n_seq * a.n_q_heads; i += kScoreThreads)
+                sh_heads[i] = observe(a.head_scratch + (int64_t)b0 * a.n_q_heads + i);
+            __syncthreads();
+            if ((int)threadIdx.x < n_seq) {
+                float sum = 0.f;
+                for (int h = 0; h < a.n_q_heads; ++h) sum += sh_heads[threadIdx.x * a.n_q_heads + h];
+                rseq = sum / (float)(a.n_q_heads * a.w_last);
+            }
+        } else if (threadIdx.x == 0) {                          // more heads than the buffer holds: one sequence per pass, read directly
+            float sum = 0.f;
+            for (int h = 0; h < a.n_q_heads; ++h) sum += observe(a.head_scratch + (int64_t)b0 * a.n_q_heads + h);
+            rseq = sum / (float)(a.n_q_heads * a.w_last);
+        }
+        if ((int)threadIdx.x < n_seq) {
+            if (a.ratio_seq != nullptr) a.ratio_seq[b0 + threadIdx.x] = rseq;
+            mine += rseq;
+        }
+    }
+    __syncthreads();
+    sh_sum[threadIdx.x] = mine;
+    __syncthreads();
+    for (int stride = kScoreThreads / 2; stride > 0; stride >>= 1) {
+        if ((int)threadIdx.x < stride) sh_sum[threadIdx.x] += sh_sum[threadIdx.x + stride];
         __syncthreads();
     }
-    if (t == 0) a.head_scratch[(int64_t)b * a.n_q_heads + h] = sh_sum[0];
+    if (threadIdx.x == 0) a.ratio_mean[0] = sh_sum[0] / (float)a.batch;
 }
 
-// Per-sequence mean over heads and queries, then the batch mean (one workgroup, fixed order).
-__global__ __launch_bounds__(64) void lt_lazy_ratio_mean_kernel(ScoreArgs a)
+__global__ void lt_score_zero_tickets_kernel(unsigned int *tickets, int n)
 {
-    __shared__ float sh_seq[64];
-    float total = 0.f;
-    for (int b0 = 0; b0 < a.batch; b0 += 64) {
-        const int b = b0 + threadIdx.x;
-        float r = 0.f;
-        if (b < a.batch) {
-            float sum = 0.f;
-            for (int h = 0; h < a.n_q_heads; ++h) sum += a.head_scratch[(int64_t)b * a.n_q_heads + h];
-            r = sum / (float)(a.n_q_heads * a.w_last);
-            if (a.ratio_seq != nullptr) a.ratio_seq[b] = r;
-        }
-        sh_seq[threadIdx.x] = r;
-        __syncthreads();
-        if (threadIdx.x == 0)
-            for (int i = 0; i < 64 && b0 + i < a.batch; ++i) total += sh_seq[i];
-        __syncthreads();
-    }
-    if (threadIdx.x == 0) a.ratio_mean[0] = total / (float)a.batch;
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) tickets[i] = 0u;
 }
 
 }  // namespace
-
-template <int G>
-hipError_t launch_partial(const ScoreArgs &a, hipStream_t stream)
-{
-    const dim3 grid(a.n_chunks, a.n_kv_heads, a.batch);
-    if (a.w_last <= 32)
-        hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 1, 1>), grid, dim3(64 * G), 0, stream, a);
-    else if constexpr (G <= 4)                       // measured 3 % faster than one wavefront of 64 queries per head
-        hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 1, 2>), grid, dim3(128 * G), 0, stream, a);
-    else
-        hipLaunchKernelGGL((lt_lazy_ratio_partial_kernel<G, 2, 1>), grid, dim3(64 * G), 0, stream, a);
-    return hipGetLastError();
-}
 
 namespace {
 constexpr int kMaxDevices = 64;
@@ -405,23 +577,21 @@ hipError_t static_scratch(void **ptr)
 
 hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream)
 {
-    hipError_t e;
-    switch (a.n_q_heads / a.n_kv_heads) {
-    case 1: e = launch_partial<1>(a, stream); break;
-    case 2: e = launch_partial<2>(a, stream); break;
-    case 3: e = launch_partial<3>(a, stream); break;
-    case 4: e = launch_partial<4>(a, stream); break;
-    case 5: e = launch_partial<5>(a, stream); break;
-    case 6: e = launch_partial<6>(a, stream); break;
-    case 7: e = launch_partial<7>(a, stream); break;
-    case 8: e = launch_partial<8>(a, stream); break;
-    default: e = hipErrorInvalidValue; break;
+    // the counters must start at zero whatever the last launch on this workspace left behind
+    const int n_tickets = a.batch * a.n_kv_heads + 1;
+    hipLaunchKernelGGL(lt_score_zero_tickets_kernel, dim3((n_tickets + 255) / 256), dim3(256), 0, stream, a.tickets, n_tickets);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    // query tiles of a KV head's group, dealt to the four wavefronts
+    const int QT = (a.n_q_heads / a.n_kv_heads) * ((a.w_last + 31) / 32);
+    const dim3 grid(a.n_chunks, a.n_kv_heads, a.batch), block(kScoreThreads);
+    switch (score_tiles_per_wave(QT)) {
+    case 1: hipLaunchKernelGGL((lt_lazy_ratio_kernel<1>), grid, block, 0, stream, a); break;
+    case 2: hipLaunchKernelGGL((lt_lazy_ratio_kernel<2>), grid, block, 0, stream, a); break;
+    case 3: hipLaunchKernelGGL((lt_lazy_ratio_kernel<3>), grid, block, 0, stream, a); break;
+    case 4: hipLaunchKernelGGL((lt_lazy_ratio_kernel<4>), grid, block, 0, stream, a); break;
+    default: return hipErrorInvalidValue;
     }
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(lt_lazy_ratio_finish_kernel, dim3(a.n_q_heads, a.batch), dim3(64), 0, stream, a);
-    e = hipGetLastError();
-    if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(lt_lazy_ratio_mean_kernel, dim3(1), dim3(64), 0, stream, a);
     return hipGetLastError();
 }
 

@@ -52,7 +52,7 @@ def test_static_scratch_matches_the_workspace_form_on_two_calls_in_a_row():
 
 def test_static_scratch_refuses_what_does_not_fit_and_allocates_nothing():
     lib = lt.load()
-    big = lt.make_config(1, 64, 64, 8, 128, 4, 2044, 1 << 20)
+    big = lt.make_config(1, 512, 64, 8, 128, 4, 2044, 1 << 20)
     dummy = torch.zeros(4096, dtype=torch.bfloat16, device=DEV)
     out = torch.zeros(1, dtype=torch.float32, device=DEV)
     st = lib.lt_lazy_ratio_static(ctypes.byref(big), dummy.data_ptr(), dummy.data_ptr(), (1 << 20) * 128 * 8, (1 << 20) * 128, 128,
