@@ -495,15 +495,13 @@ lt_status lt_layer_view(const lt_ctx *ctx, int32_t layer, void **k_dev, void **v
 
 // ---- lazy-layer identification ---------------------------------------------------------------
 
-// Keys per workgroup of the scoring kernel for `keys` keys per (sequence, KV head) in all.  A compute unit holds two
-// workgroups of the kernel (one when a wavefront owns more than two query tiles), so the B * Hkv key streams are cut
-// into about 512 (256) ranges of equal length, multiples of kScoreTileKeys; more streams than that: one range each.
-static int score_keys_per_block(const lt_config *cfg, int64_t keys, int32_t w_last)
+// Keys per workgroup of the scoring kernel for `keys` keys per (sequence, KV head) in all.  One workgroup (eight
+// wavefronts) fills a compute unit, so the B * Hkv key streams are cut into about 256 ranges of equal length, multiples
+// of kScoreTileKeys; more streams than compute units: one range each.
+static int score_keys_per_block(const lt_config *cfg, int64_t keys)
 {
     const int64_t streams = (int64_t)cfg->batch * cfg->n_kv_heads;
-    const int query_tiles = (cfg->n_q_heads / cfg->n_kv_heads) * ((w_last + 31) / 32);
-    const int64_t resident = ltk::score_tiles_per_wave(query_tiles) <= 2 ? 512 : 256;
-    const int64_t ranges = std::max<int64_t>(resident / streams, 1);
+    const int64_t ranges = std::max<int64_t>(256 / streams, 1);
     const int64_t per = ceil_div(ceil_div(keys, ranges), ltk::kScoreTileKeys) * ltk::kScoreTileKeys;
     return (int)std::max<int64_t>(per, ltk::kScoreTileKeys);
 }
@@ -535,7 +533,7 @@ static void bind_score_workspace(ltk::ScoreArgs &a, const lt_config *cfg, void *
 size_t lt_lazy_ratio_workspace_bytes(const lt_config *cfg, int64_t n, int32_t w_last)
 {
     if (!config_ok(cfg) || config_shape(cfg) != LT_OK || n <= 0 || w_last <= 0 || w_last > 64) return 0;
-    return score_workspace(cfg, ceil_div(n, score_keys_per_block(cfg, n, w_last)), w_last).total();
+    return score_workspace(cfg, ceil_div(n, score_keys_per_block(cfg, n)), w_last).total();
 }
 
 // The dense form behind lt_lazy_ratio and lt_lazy_ratio_static.  workspace == nullptr selects the library's
@@ -569,7 +567,7 @@ static lt_status lazy_ratio_dense(const lt_config *cfg, const void *q_last, cons
     a.w_sink = cfg->w_sink;
     a.w_recent = cfg->w_recent;
     a.fixed_mode = mode == LT_RECENT_FIXED ? 1 : 0;
-    a.keys_per_block = score_keys_per_block(cfg, n, w_last);
+    a.keys_per_block = score_keys_per_block(cfg, n);
     a.n_chunks = (int32_t)ceil_div(n, a.keys_per_block);
     a.range_a_end = n;
     a.range_b_begin = n;
@@ -615,7 +613,7 @@ static WindowPlan window_plan(const lt_config *cfg, int64_t n, int32_t w_last, l
     int64_t first_recent = mode == LT_RECENT_FIXED ? n - cfg->w_recent : n - w_last - (int64_t)cfg->w_recent + 1;
     first_recent = std::min<int64_t>(std::max<int64_t>(first_recent, 0), n);
     p.b_begin = std::max<int64_t>(p.a_end, first_recent / tile * tile);
-    p.keys_per_block = score_keys_per_block(cfg, p.a_end + (n - p.b_begin), w_last);
+    p.keys_per_block = score_keys_per_block(cfg, p.a_end + (n - p.b_begin));
     p.chunks_a = (int32_t)ceil_div(p.a_end, p.keys_per_block);
     p.chunks_b = (int32_t)ceil_div(n - p.b_begin, p.keys_per_block);
     return p;

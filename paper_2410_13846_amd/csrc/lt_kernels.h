@@ -16,9 +16,6 @@ constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head
 constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels
 constexpr int kMaxRaggedBatch = 64;    // sequences a launch can give their own lengths (the lengths travel as kernel arguments)
 constexpr int kScoreTileKeys = 128;    // key ranges of the scoring kernel are multiples of this
-// 32-query tiles each of the scoring kernel's four wavefronts owns, for QT = (Hq / Hkv) * ceil(w_last / 32) tiles in all;
-// up to two, two workgroups share a compute unit
-constexpr int score_tiles_per_wave(int QT) { return (QT + 3) / 4; }
 
 struct AppendArgs {
     const uint16_t *k_new, *v_new;     // [B][Hkv][n_new][128]

@@ -3,16 +3,19 @@
 // on the fly to two sums per query -- the softmax denominator over the causal set and the part
 // of it that falls on the initial + recent keys.  No attention matrix and no V are touched.
 //
-// One launch.  One workgroup (four wavefronts, one per SIMD, the whole register file) = one
+// One launch.  One workgroup of eight wavefronts (two per SIMD, which fill each other's stalls; the
+// barrier of every tile keeps them in step, so no wavefront is left to run alone at the end) = one
 // (sequence, KV head, range of keys).  K tiles travel from global memory straight into LDS
-// (global_load_lds_dwordx4, three stages, two tiles in flight), laid out with an XOR swizzle of
-// the 16-byte pieces of a row so that the matrix-operand reads are free of bank conflicts.
-// S^T = K Q^T is formed with v_mfma_f32_32x32x16_bf16: keys are the rows, queries the columns,
-// so each lane keeps 16 key logits of ONE query per instruction and the running max / sums
-// stay private to the lane until the final merge.  A wavefront owns up to four 32-query tiles
-// (of one or two heads of the group): every K fragment read from LDS feeds that many matrix
-// instructions.  The matrix instructions of one 32-key sub-tile are issued in the same
-// instruction stream as the exponentials of the previous sub-tile (two accumulator sets).
+// (global_load_lds_dwordx4, the next tile(s) under way while one is contracted), laid out with an
+// XOR swizzle of the 16-byte pieces of a row so that the matrix-operand reads are free of bank
+// conflicts.  S^T = K Q^T is formed with v_mfma_f32_32x32x16_bf16: keys are the rows, queries the
+// columns, so each lane keeps 16 key logits of ONE query per instruction and the running max /
+// sums stay private to the lane until the final merge.  A wavefront owns one or two 32-query
+// tiles: every K fragment read from LDS feeds that many matrix instructions.  The matrix
+// instructions of one 32-key sub-tile are issued in the same instruction stream as the
+// exponentials of the previous sub-tile (two accumulator sets).  On this hardware a SIMD does
+// not run vector and matrix instructions at the same time, so the kernel's floor is the sum of
+// the two (about equal here), not the larger.
 // The workgroup that finishes last for a (sequence, KV head) merges the key ranges, and the one
 // that finishes last overall forms the means: the order of every sum is fixed.
 #include "lt_kernels.h"
@@ -140,8 +143,8 @@ __device__ __forceinline__ void update_masked(const floatx16_t &c, LaneState &st
 // 1 KB = four whole rows, lane l to byte 16 * l after the (uniform) destination, so lane l
 // fetches piece (l & 15) ^ (row & 15) of row (l >> 4): still one coalesced kilobyte of memory.
 // ---------------------------------------------------------------------------------------------
-constexpr int kScoreStages = 4;                              // LDS stages of a workgroup: three tiles under way
-constexpr int kScoreThreads = 256;
+constexpr int kScoreThreads = 512;
+constexpr int kScoreWaves = kScoreThreads / 64;
 
 // One global -> LDS load of 16 bytes per lane: lane l's bytes land at LDS byte address lds_base + 16 * l (lds_base is
 // uniform and travels in M0).  Written as inline assembly on purpose: for the compiler's own form of this load the
@@ -188,29 +191,29 @@ __device__ __forceinline__ void merge_state(float &m, float &c, float &k, float 
     m = m_new;
 }
 
-// NT: 32-query tiles per wavefront (1..4): the query tiles of a KV head's group are dealt to the four wavefronts, and
-// every wavefront contracts every key (both 32-key sub-tiles of each 64-key LDS tile).  Up to two query tiles per
-// wavefront leave room for two workgroups per compute unit (two wavefronts per SIMD, each filling the other's stalls);
-// more tiles need the whole register file.
-template <int NT>
-__global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_kernel(ScoreArgs a)
+// NT: 32-query tiles per wavefront (1 or 2).  KW: wavefronts that own the same query tiles and share the keys between
+// them (1 or 2): the eight wavefronts are 8 / KW tile groups x KW key ways.  An LDS tile holds 64 * KW keys, and every
+// wavefront contracts two 32-key sub-tiles of it (sub-tiles kw and kw + KW).
+template <int NT, int KW>
+__global__ __launch_bounds__(kScoreThreads, 1) void lt_lazy_ratio_kernel(ScoreArgs a)
 {
-    constexpr int TK = 64;                                      // keys per tile
+    constexpr int TK = 64 * KW;                                 // keys per tile
     constexpr int kStageBytes = TK * 256;
-    constexpr int kLoads = TK * 16 / kScoreThreads;             // global_load_lds per wavefront and tile (4)
-    constexpr int kGroups = 4, KW = 1;
+    constexpr int kScoreStages = 65536 / kStageBytes;           // 2 stages of 32 KB or 4 of 16 KB
+    constexpr int kLoads = TK * 16 / kScoreThreads;             // global_load_lds per wavefront and tile
+    constexpr int kRowsPerRound = kScoreThreads / 16;           // rows one round of loads of the whole workgroup covers (32)
+    constexpr int kGroups = kScoreWaves / KW;
     // The only LDS object of the kernel, so it starts at LDS address 0 and every tile load lands below 64 KB.
     // After the tile loop the same memory carries the lane states, the ratios and a flag.
     __shared__ __attribute__((aligned(1024))) char sh_all[kScoreStages * kStageBytes];
     static_assert(kScoreStages * kStageBytes <= 65536, "tile loads address LDS through a 16-bit offset");
-    static_assert(kScoreStages * kStageBytes >= 32768, "the lane states, the ratios and the flag live in the first 32 KB");
-    int *sh_flag = reinterpret_cast<int *>(sh_all + 32768 - 64);            // past the states (12 KB)
+    int *sh_flag = reinterpret_cast<int *>(sh_all + 65536 - 64);            // far past the states, sums and ratios
 
     const int chunk = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // scalar: what depends on it stays in scalar registers
     const int col = lane & 31, half = lane >> 5;
-    const int tg = wave;                                        // tile group of this wavefront
+    const int tg = wave % kGroups, kw = wave / kGroups;         // tile group and key way of this wavefront
     const int G = a.n_q_heads / a.n_kv_heads;
     const int QH = (a.w_last + 31) >> 5;                        // 32-query tiles per head
     const int QT = G * QH;                                      // query tiles of this KV head's group
@@ -230,27 +233,27 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
     const uint16_t *hot = a.q_last + ((int64_t)b * a.n_q_heads + g * G) * a.w_last * kHeadDim;   // a line that is in cache anyway
 
     // ---- tile loads ---------------------------------------------------------------------------------------
-    // this lane's row inside a 16-row block and the piece it fetches (see the layout above)
+    // this lane's row inside a round of loads (32 rows) and the piece it fetches (see the layout above)
     const int my_row = wave * 4 + (lane >> 4);
     const int my_piece = (lane & 15) ^ (my_row & 15);
     int next_issue = 0;
     const uint32_t lds_base = lds_address(sh_all);              // 0
-    // source of this lane's first load of the next tile; the tile's other loads are 16 rows apart each
+    // source of this lane's first load of the next tile; the tile's other loads are 32 rows apart each
     const uint16_t *next_src = kb + (int64_t)(begin_key + my_row) * a.k_stride_t + my_piece * 8;
-    const int64_t rows16 = 16 * a.k_stride_t;
-    auto issue = [&]() __attribute__((always_inline)) {        // tile `next_issue` -> stage next_issue % 4; past the last tile: dummy loads
+    const int64_t rows_round = kRowsPerRound * a.k_stride_t;
+    auto issue = [&]() __attribute__((always_inline)) {        // tile `next_issue` -> its stage; past the last tile: dummy loads
         const int j0 = begin_key + next_issue * TK;
         const uint32_t stage_base = lds_base + (next_issue & (kScoreStages - 1)) * kStageBytes;
         if (next_issue < n_tiles && j0 + TK <= n) {             // the common case: every row exists
 #pragma unroll
-            for (int i = 0; i < kLoads; ++i) load_to_lds(next_src + i * rows16, stage_base + (i * 16 + wave * 4) * 256);
+            for (int i = 0; i < kLoads; ++i) load_to_lds(next_src + i * rows_round, stage_base + (i * kRowsPerRound + wave * 4) * 256);
         } else {
 #pragma unroll
             for (int i = 0; i < kLoads; ++i) {
-                int j = j0 + i * 16 + my_row;
+                int j = j0 + i * kRowsPerRound + my_row;
                 j = j < n ? j : n - 1;                          // rows past the prompt repeat its last key; they are masked
                 const uint16_t *src = next_issue < n_tiles ? kb + (int64_t)j * a.k_stride_t + my_piece * 8 : hot + (lane & 15) * 8;
-                load_to_lds(src, stage_base + (i * 16 + wave * 4) * 256);
+                load_to_lds(src, stage_base + (i * kRowsPerRound + wave * 4) * 256);
             }
         }
         next_src += TK * a.k_stride_t;
@@ -267,13 +270,12 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
         const int t = (qt % QH) * 32 + col;
         const bool live = qt < QT && t < a.w_last;
         q_pos[nt] = n - a.w_last + t;
+        // dead columns read the group's first query (in bounds) and are zeroed: no branch around the loads
+        const uint16_t *src = a.q_last + (((int64_t)b * a.n_q_heads + (live ? h : g * G)) * a.w_last + (live ? t : 0)) * kHeadDim + 8 * half;
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            uint4 u = make_uint4(0u, 0u, 0u, 0u);
-            if (live)
-                u = *reinterpret_cast<const uint4 *>(a.q_last + (((int64_t)b * a.n_q_heads + h) * a.w_last + t) * kHeadDim +
-                                                     16 * s + 8 * half);
-            qf[nt][s] = __builtin_bit_cast(bf16x8_t, u);
+            const uint4 u = *reinterpret_cast<const uint4 *>(src + 16 * s);
+            qf[nt][s] = __builtin_bit_cast(bf16x8_t, live ? u : make_uint4(0u, 0u, 0u, 0u));
         }
     }
     // the fragments have arrived before any tile load is counted
@@ -283,11 +285,14 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
 #pragma unroll
     for (int nt = 0; nt < NT; ++nt) { st[nt].m = -INFINITY; st[nt].sum_causal = 0.f; st[nt].sum_kept = 0.f; }
 
-    // LDS byte offset of this lane's K fragment for k-step s of sub-tile `sub`: row 32 * sub + col, piece 2s + half
-    const int frag_x = (half ^ (col & 15)) << 4;
-    auto k_fragment = [&](const char *stage, int s) __attribute__((always_inline)) {     // `stage` points at the sub-tile
-        const int byte = col * 256 + (frag_x ^ (s << 5));
-        return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(stage + byte));
+    // LDS byte offset of this lane's K fragment for k-step s of this wavefront's first sub-tile of stage 0: row
+    // 32 * kw + col, piece 2s + half, swizzled.  The stage and the second sub-tile add compile-time constants, which
+    // travel in the offset field of the LDS read: no address arithmetic in the loop.
+    int frag_off[8];
+#pragma unroll
+    for (int s = 0; s < 8; ++s) frag_off[s] = (32 * kw + col) * 256 + (((half ^ (col & 15)) << 4) ^ (s << 5));
+    auto k_fragment = [&](int const_bytes, int s) __attribute__((always_inline)) {
+        return __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(sh_all + frag_off[s] + const_bytes));
     };
 
     // Fold one sub-tile's logits (masked form): per-element predicates of Eq. 1, and keys outside this workgroup's range out
@@ -303,12 +308,12 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
         return cls.fast && j0 + 32 <= end_key;
     };
 
-    // Contract this wavefront's sub-tile of `stage` into `next` while folding `prev` (the logits of the sub-tile that began at key
+    // Contract the sub-tile at constant byte offset `stage` (from this wavefront's first sub-tile of stage 0) into `next` while folding `prev` (the logits of the sub-tile that began at key
     // j_prev; j_prev < 0: nothing to fold).  On the mask-free path the exponentials of `prev` are issued between the
     // matrix instructions of `next`, two accumulator registers per tile and k-step, against each lane's current
     // reference; the sums are taken only if they stay within 2^12 in every lane, else `prev` is folded again the
     // long way, which moves the reference (any reference gives the same quotient of the two sums).
-    auto step = [&](floatx16_t (&next)[NT], const char *stage, const floatx16_t (&prev)[NT], int j_prev) __attribute__((always_inline)) {
+    auto step = [&](floatx16_t (&next)[NT], int stage, const floatx16_t (&prev)[NT], int j_prev) __attribute__((always_inline)) {
         bool kept = false;
         const bool quick = j_prev >= 0 && fast_class(j_prev, kept);
 #pragma unroll
@@ -319,15 +324,21 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
             float sum[NT];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) sum[nt] = 0.f;
+            // The order is pinned: one matrix instruction, then the six vector instructions of two logits, and so on,
+            // with the K fragment of the next k-step requested one step ahead.  A matrix instruction leaves part of its
+            // issue time open to vector instructions of the same wavefront, but only if they sit right behind it.
+            bf16x8_t kf = k_fragment(stage, 0);
 #pragma unroll
             for (int s = 0; s < 8; ++s) {
-                const bf16x8_t kf = k_fragment(stage, s);
+                const bf16x8_t kf_next = k_fragment(stage, s < 7 ? s + 1 : 7);
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     next[nt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[nt][s], next[nt], 0, 0, 0);
                     sum[nt] += fast_exp2(fmaf(prev[nt][2 * s], a.scale_log2e, -st[nt].m));
                     sum[nt] += fast_exp2(fmaf(prev[nt][2 * s + 1], a.scale_log2e, -st[nt].m));
+                    __builtin_amdgcn_sched_barrier(0);
                 }
+                kf = kf_next;
             }
             bool ok = true;
 #pragma unroll
@@ -353,7 +364,7 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
         }
     };
 
-    // ---- main loop: tile t sits in stage t % 4; tiles t + 1 .. t + 3 are on their way -------------------------------------
+    // ---- main loop: tile t sits in stage t % kScoreStages; the following kScoreStages - 1 tiles are on their way ---------
     constexpr int kAhead = kScoreStages - 1;
     floatx16_t acc_a[NT], acc_b[NT];
 #pragma unroll
@@ -361,15 +372,19 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
     wait_vmcnt<(kAhead - 1) * kLoads>();                        // this wavefront's part of tile 0 has landed
     barrier_no_fence();                                         // ... and everybody else's
     int j_pending = -1;                                         // first key of the sub-tile whose logits wait (in acc_b) to be folded
-    for (int tile = 0; tile < n_tiles; ++tile) {
-        issue();                                                // tile + 3 -> the stage tile - 1 was read from (all past the last barrier)
-        const char *stage = sh_all + (tile & (kScoreStages - 1)) * kStageBytes;
-        const int j0 = begin_key + tile * TK;
-        step(acc_a, stage, acc_b, j_pending);                   // first 32 keys, while the previous tile's second half is folded
-        step(acc_b, stage + 32 * 256, acc_a, j0);               // second 32 keys, while the first half is folded
-        j_pending = j0 + 32;
-        wait_vmcnt<(kAhead - 1) * kLoads>();                    // tile + 1 has landed (the two after it may still be under way)
-        barrier_no_fence();                                     // everybody is done reading tile `tile`, and tile + 1 is complete
+    for (int tile0 = 0; tile0 < n_tiles; tile0 += kScoreStages) {
+#pragma unroll
+        for (int u = 0; u < kScoreStages; ++u) {                // the stage of tile tile0 + u is u: a constant in the unrolled body
+            const int tile = tile0 + u;
+            if (tile >= n_tiles) break;
+            issue();                                            // into the stage tile - 1 was read from (all past the last barrier)
+            const int j0 = begin_key + tile * TK;
+            step(acc_a, u * kStageBytes, acc_b, j_pending);                        // sub-tile kw, while the previous tile's second one is folded
+            step(acc_b, u * kStageBytes + 32 * KW * 256, acc_a, j0 + 32 * kw);     // sub-tile kw + KW, while the first is folded
+            j_pending = j0 + 32 * (kw + KW);
+            wait_vmcnt<(kAhead - 1) * kLoads>();                // tile + 1 has landed (later ones may still be under way)
+            barrier_no_fence();                                 // everybody is done reading tile `tile`, and tile + 1 is complete
+        }
     }
     wait_vmcnt<0>();                                            // the dummy loads past the last tile
     if (j_pending >= 0 && j_pending < end_key) {
@@ -393,8 +408,8 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
         dst[128] = st[nt].sum_kept;
     }
     __syncthreads();
-    // entry e = (query tile qt, column): at most 16 * 32 = 512 of them, two rounds of the 256 threads
-    constexpr int kRounds = 2;
+    // entry e = (query tile qt, column): at most 16 * 32 = 512 of them, one per thread
+    constexpr int kRounds = 1;
     float fin_m[kRounds], fin_c[kRounds], fin_k[kRounds];
     const bool single = a.n_chunks == 1;
 #pragma unroll
@@ -483,9 +498,9 @@ __global__ __launch_bounds__(kScoreThreads, NT <= 2 ? 2 : 1) void lt_lazy_ratio_
         if (e < 16 * 32) sh_rho[e] = rho;
     }
     __syncthreads();
-    // a head's sum of rho: wavefront w takes heads w, w + 4, ...; lane t holds query t, then a butterfly over the 64 lanes
+    // a head's sum of rho: wavefront w takes head w; lane t holds query t, then a butterfly over the 64 lanes
     // (a fixed order of additions)
-    for (int hh = wave; hh < G; hh += 4) {
+    for (int hh = wave; hh < G; hh += kScoreWaves) {
         float v = lane < a.w_last ? sh_rho[(hh * QH + (lane >> 5)) * 32 + (lane & 31)] : 0.f;
 #pragma unroll
         for (int mask = 32; mask > 0; mask >>= 1) v += __shfl_xor(v, mask, 64);
@@ -582,16 +597,14 @@ hipError_t lazy_ratio(const ScoreArgs &a, hipStream_t stream)
     hipLaunchKernelGGL(lt_score_zero_tickets_kernel, dim3((n_tickets + 255) / 256), dim3(256), 0, stream, a.tickets, n_tickets);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    // query tiles of a KV head's group, dealt to the four wavefronts
+    // query tiles of a KV head's group, dealt to the eight wavefronts: up to eight tiles, four tile groups x two key
+    // ways; more, eight tile groups that each see every key
     const int QT = (a.n_q_heads / a.n_kv_heads) * ((a.w_last + 31) / 32);
     const dim3 grid(a.n_chunks, a.n_kv_heads, a.batch), block(kScoreThreads);
-    switch (score_tiles_per_wave(QT)) {
-    case 1: hipLaunchKernelGGL((lt_lazy_ratio_kernel<1>), grid, block, 0, stream, a); break;
-    case 2: hipLaunchKernelGGL((lt_lazy_ratio_kernel<2>), grid, block, 0, stream, a); break;
-    case 3: hipLaunchKernelGGL((lt_lazy_ratio_kernel<3>), grid, block, 0, stream, a); break;
-    case 4: hipLaunchKernelGGL((lt_lazy_ratio_kernel<4>), grid, block, 0, stream, a); break;
-    default: return hipErrorInvalidValue;
-    }
+    if (QT <= 4) hipLaunchKernelGGL((lt_lazy_ratio_kernel<1, 2>), grid, block, 0, stream, a);
+    else if (QT <= 8) hipLaunchKernelGGL((lt_lazy_ratio_kernel<2, 2>), grid, block, 0, stream, a);
+    else if (QT <= 16) hipLaunchKernelGGL((lt_lazy_ratio_kernel<2, 1>), grid, block, 0, stream, a);
+    else return hipErrorInvalidValue;
     return hipGetLastError();
 }
 
