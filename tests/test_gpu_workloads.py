@@ -267,6 +267,49 @@ def test_llama31_8b_128k_batch_16_one_full_layer_every_row():
     run_whole_batch(wl, [full_layer], [0], steps=1)
 
 
+def run_whole_batch_ratio(wl, layer, static=False):
+    """Every rho of every (sequence, head, query) of one layer's scoring call at the workload's real shape, the
+    per-sequence ratios and the layer's ratio, against the oracle's Eq. 1."""
+    cfg = make_cfg(wl)
+    k, _ = W.prefill_kv(wl, layer, DEV)
+    q_last = W.last_queries(wl, layer, DEV)
+    say(wl.name, "whole batch: scoring layer", layer, "static scratch" if static else "workspace")
+    if static:
+        mean = torch.empty(1, dtype=torch.float32, device=DEV)
+        seq = torch.empty(wl.batch, dtype=torch.float32, device=DEV)
+        rho = torch.empty((wl.batch, wl.n_q_heads, wl.w_last), dtype=torch.float32, device=DEV)
+        lt.lazy_ratio_static(cfg, q_last, k, wl.context, wl.w_last, mean, seq, rho)
+    else:
+        mean, seq, rho = lt.lazy_ratio(cfg, q_last, k, wl.context, wl.w_last, want_rho=True)
+    torch.cuda.synchronize()
+    ref_rho, ref_seq, ref_r = oracle.lazy_ratio(bits(q_last), bits(k), wl.w_sink, wl.w_recent)
+    err = np.abs(f64(rho) - ref_rho)
+    say(wl.name, "whole batch: scoring layer", layer, "max |rho - oracle|", err.max(), "r", ref_r, "err", abs(float(mean.cpu()[0]) - ref_r))
+    assert err.max() <= TOL_RATIO, np.unravel_index(err.argmax(), err.shape)
+    assert np.abs(f64(seq) - ref_seq).max() <= TOL_RATIO
+    assert abs(float(mean.cpu()[0]) - ref_r) <= TOL_RATIO
+
+
+def test_llama3_8b_32k_scoring_every_ratio():
+    """Batch 8, n = 32768, w_last = 64: all 8 x 32 x 64 ratios of a planted-lazy and of a plain layer."""
+    wl = W.WORKLOADS["llama3_8b_32k"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    run_whole_batch_ratio(wl, lazy_layers[3])
+    run_whole_batch_ratio(wl, [l for l in range(wl.n_layers) if l not in lazy_layers][3], static=True)
+
+
+def test_llama31_8b_128k_b1_scoring_every_ratio():
+    """n = 131072, batch 1: 32 key ranges per KV head merged by the last workgroup."""
+    wl = W.WORKLOADS["llama31_8b_128k_b1"]
+    run_whole_batch_ratio(wl, W.planted_lazy_layers(wl)[2])
+
+
+def test_qwq_32b_scoring_every_ratio():
+    """Groups of five query heads (ten query tiles dealt to eight wavefronts), batch 4, a prompt of 20000 tokens."""
+    wl = W.WORKLOADS["qwq_32b_gen"].scaled(context=20000, bias="planted", n_lazy=32)
+    run_whole_batch_ratio(wl, 7)
+
+
 def test_llama3_8b_32k_prefill_and_ratio_from_lse_sampled():
     """Prefill attention of one planted-lazy layer at batch 8, 32/8 heads, n = 32768 in the launch configuration
     bench.py --prefill times: sampled rows against the oracle's decode of the truncated history (prefill row p ==
