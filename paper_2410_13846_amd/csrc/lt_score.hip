@@ -260,6 +260,11 @@ __global__ __launch_bounds__(kScoreThreads, 1) void lt_lazy_ratio_kernel(ScoreAr
         ++next_issue;
     };
 
+    // the first tile(s) are requested before anything else, so that they travel while the query fragments are fetched
+    constexpr int kAhead = kScoreStages - 1;
+#pragma unroll
+    for (int i = 0; i < kAhead; ++i) issue();
+
     // ---- Q^T fragments (B operand): lane holds, for its query column, the 8 dims 16*s + 8*half .. +7 ---------
     bf16x8_t qf[NT][8];
     int q_pos[NT];                                              // prompt position of this lane's query column per tile
@@ -278,7 +283,7 @@ __global__ __launch_bounds__(kScoreThreads, 1) void lt_lazy_ratio_kernel(ScoreAr
             qf[nt][s] = __builtin_bit_cast(bf16x8_t, live ? u : make_uint4(0u, 0u, 0u, 0u));
         }
     }
-    // the fragments have arrived before any tile load is counted
+    // the fragments and this wavefront's part of the first tile(s) have arrived
     wait_vmcnt<0>();
 
     LaneState st[NT];
@@ -365,12 +370,8 @@ __global__ __launch_bounds__(kScoreThreads, 1) void lt_lazy_ratio_kernel(ScoreAr
     };
 
     // ---- main loop: tile t sits in stage t % kScoreStages; the following kScoreStages - 1 tiles are on their way ---------
-    constexpr int kAhead = kScoreStages - 1;
     floatx16_t acc_a[NT], acc_b[NT];
-#pragma unroll
-    for (int i = 0; i < kAhead; ++i) issue();
-    wait_vmcnt<(kAhead - 1) * kLoads>();                        // this wavefront's part of tile 0 has landed
-    barrier_no_fence();                                         // ... and everybody else's
+    barrier_no_fence();                                         // everybody's part of tile 0 has landed (each waited above)
     int j_pending = -1;                                         // first key of the sub-tile whose logits wait (in acc_b) to be folded
     for (int tile0 = 0; tile0 < n_tiles; tile0 += kScoreStages) {
 #pragma unroll
