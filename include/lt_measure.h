@@ -19,6 +19,16 @@ extern "C" {
  * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
 lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
 
+/* Decode launches whose workgroups each stream 8192 keys or more leave the last eighth of every
+ * (sequence, KV head) to whichever wavefronts finish their own range first (on by default): the
+ * compute units do not all read memory equally fast, and a launch ends with its slowest
+ * workgroup.  Which wavefront gets which keys of that part is decided at run time, so the
+ * floating-point sums are taken in an order that varies from launch to launch and outputs can
+ * differ in their last bits between two runs on the same inputs.  on = 0 gives every key a fixed
+ * place (as a forced split, paged layers and shorter ranges always have): bit-identical outputs
+ * for identical inputs, at 1.5-3.5 % more time on long contexts. */
+lt_status lt_set_shared_tail(lt_ctx *ctx, int32_t on);
+
 /* Measurement aid: one launch that reads `bytes` of `buf_dev` (rounded down to a multiple of
  * 16 KiB, and at least that) once, with the same kind of loads the decode kernel uses, and discards
  * them; timed by the caller, it gives the read rate this device sustains, the practical ceiling of

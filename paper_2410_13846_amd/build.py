@@ -16,6 +16,9 @@ HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-Wall", "-Wextra",
     # packed fp32 VALU forms are kept out of the generated code on purpose
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # an atomic issued by one lane stays one instruction whose result is waited for where it is used (the
+    # wave-level rewrite of atomics reads the result back on the spot, which stalls a software pipeline)
+    "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
 ]
 
 

@@ -9,6 +9,7 @@
 #include <algorithm>
 #include <cmath>
 #include <cstring>
+#include <climits>
 #include <new>
 #include <vector>
 
@@ -18,6 +19,7 @@ constexpr size_t kAlign = 256;
 constexpr int64_t kMaxTokens = (int64_t)1 << 30;        // per-sequence positions are 32-bit inside the decode kernel
 constexpr int kMinKeysFull = 256;                       // smallest split the decode workspace is sized for (full layers)
 constexpr int kMinKeysLazy = 64;                        // same, lazy layers
+constexpr int kMinKeysSharedTail = 8192;                // key ranges at least this long leave a shared tail
 constexpr int kMaxEventPairs = 65536;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -98,6 +100,7 @@ struct lt_ctx {
     int64_t splits_cap = 0;
     int32_t keys_full = 0, keys_lazy = 0;      // 0 = heuristic
     bool out_bf16 = false;                     // decode outputs are bf16 instead of fp32
+    bool shared_tail = true;                   // long key ranges end in a part the wavefronts share (lt_set_shared_tail)
     bool profiling = false;
     std::vector<EventPair> events;             // pool, created on first enable
     size_t events_used = 0;
@@ -155,9 +158,9 @@ lt_status assign_full_slot(lt_ctx *ctx, Layer &l)
 // units means one range per stream.  Short ranges are not cut below `lo` keys.
 int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t splits_cap)
 {
-    constexpr int64_t kComputeUnits = 256;
+    constexpr int64_t workgroups = 256;                        // one per compute unit
     const int64_t lo = lazy ? 128 : 256;
-    const int64_t splits = std::max<int64_t>(kComputeUnits / streams, 1);
+    const int64_t splits = std::max<int64_t>(workgroups / streams, 1);
     int64_t keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
     keys = std::max(keys, lo);
     keys = std::max(keys, ceil_div(ceil_div(stored, splits_cap), ltk::kKeyGranule) * ltk::kKeyGranule);
@@ -951,6 +954,20 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
         a.keys_per_block = (int32_t)std::min<int64_t>(a.keys_per_block, most);
     }
     a.n_splits = (int32_t)ceil_div(stored, a.keys_per_block);
+    a.tail_begin = INT32_MAX;
+    // Long ranges leave their last eighth to the shared tail (see DecodeArgs::tail_begin): it evens out the
+    // workgroups' different speeds.  Below kMinKeysSharedTail keys per workgroup a wavefront's two pieces in
+    // flight are too large a share of its work for that to pay (measured), and a forced split stays as given.
+    if (ctx->shared_tail && forced <= 0 && !paged && a.n_splits > 1 && a.keys_per_block >= kMinKeysSharedTail) {
+        const int64_t streams = (int64_t)c.batch * c.n_kv_heads;
+        const int64_t begin = (stored - stored / 8) / ltk::kKeyGranule * ltk::kKeyGranule;
+        const int32_t keys = choose_keys_per_block(begin, streams, l.lazy, ctx->splits_cap);
+        if (ceil_div(begin, keys) > 1) {
+            a.tail_begin = (int32_t)begin;
+            a.keys_per_block = keys;
+            a.n_splits = (int32_t)ceil_div(begin, keys);
+        }
+    }
     if (a.n_splits > ctx->splits_cap) return LT_ERR_CAPACITY;
     a.scale_log2e = c.softmax_scale * kLog2e;
     a.lazy_tag = l.lazy ? 1 : 0;
@@ -1106,6 +1123,13 @@ lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_pe
         return LT_ERR_CAPACITY;
     ctx->keys_full = keys_per_block_full;
     ctx->keys_lazy = keys_per_block_lazy;
+    return LT_OK;
+}
+
+lt_status lt_set_shared_tail(lt_ctx *ctx, int32_t on)
+{
+    if (ctx == nullptr) return LT_ERR_INVALID_ARG;
+    ctx->shared_tail = on != 0;
     return LT_OK;
 }
 

@@ -359,7 +359,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     int stored = a.stored;
     if constexpr (kRagged) stored = lengths_of(r).stored_b[b];
     const int begin_key = split * a.keys_per_block;
-    const int end_key = min(stored, begin_key + a.keys_per_block);
+    const int end_key = min(min(stored, a.tail_begin), begin_key + a.keys_per_block);
     const int n_tiles = max((end_key - begin_key + 15) >> 4, 0);
     const int wrap = max(n_tiles, 1);
     uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
@@ -401,24 +401,25 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
         return shift;
     };
     if constexpr (kPaged) { kb = a.k_cache; vb = a.v_cache; }
-    auto fetch = [&](Tile &t, int key0) {
+    // `limit` is the end of the keys a tile may hold: the end of the workgroup's range, or `stored` in the shared tail
+    auto fetch = [&](Tile &t, int key0, int limit) __attribute__((always_inline)) {
         if constexpr (kPaged) {
             const int64_t shift = tile_shift(key0);
-            load_tile(t, kb + shift, vb + shift, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new, hot);
+            load_tile(t, kb + shift, vb + shift, key0, sub, chunk, limit - 1, new_slot, k_new, v_new, hot);
         } else {
-            load_tile(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot, k_new, v_new, hot);
+            load_tile(t, kb, vb, key0, sub, chunk, limit - 1, new_slot, k_new, v_new, hot);
         }
     };
-    auto consume = [&](const Tile &t, int key0, RowState<G> &st, const uint32_t (&qf)[G][4]) {
+    auto consume = [&](const Tile &t, int key0, int limit, RowState<G> &st, const uint32_t (&qf)[G][4]) __attribute__((always_inline)) {
         if constexpr (kPaged) {
             if (new_slot >= key0 && new_slot < key0 + 16) {         // wave-uniform, true for one tile of one workgroup
                 const int64_t shift = tile_shift(key0);
-                store_new_token(t, kb + shift, vb + shift, key0, sub, chunk, end_key - 1, new_slot);
+                store_new_token(t, kb + shift, vb + shift, key0, sub, chunk, limit - 1, new_slot);
             }
         } else {
-            store_new_token(t, kb, vb, key0, sub, chunk, end_key - 1, new_slot);
+            store_new_token(t, kb, vb, key0, sub, chunk, limit - 1, new_slot);
         }
-        process_tile<G>(t, qf, st, key0, sub, chunk, end_key, a.scale_log2e);
+        process_tile<G>(t, qf, st, key0, sub, chunk, limit, a.scale_log2e);
     };
 
     uint32_t qf[G][4];
@@ -477,16 +478,71 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
         while (next_tile >= wrap) next_tile -= wrap;
         return fetched++ < my_tiles ? begin_key + 16 * cur : -1;
     };
+    // The shared tail (described below): its first two pieces are claimed while the wavefront's last own tiles
+    // are on their way, so that the claims have come back when those tiles are done.
+    const int n_pieces = !kPaged && stored > a.tail_begin ? (stored - a.tail_begin + kTailKeys - 1) / kTailKeys : 0;
+    unsigned int *counter = a.tickets + ((int64_t)b * a.n_kv_heads + g) * kTicketStride + 1;
+    // a claim is one atomic add by lane 0; its result is read (readfirstlane) only when the piece is needed
+    auto claim = [&]() __attribute__((always_inline)) {
+        unsigned int c = 0;
+        if (lane == 0) c = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return c;
+    };
+    unsigned int claim_first = 0, claim_next = 0;
+    if (n_pieces > 0 && my_tiles <= 2) { claim_first = claim(); claim_next = claim(); }
+
     Tile t0, t1;
     int key0 = advance();
-    fetch(t0, key0);
+    fetch(t0, key0, end_key);
     for (int k = 0; k < my_tiles; k += 2) {
+        if (n_pieces > 0 && k > 0 && k + 2 >= my_tiles) { claim_first = claim(); claim_next = claim(); }   // the last round
         const int key1 = advance();
-        fetch(t1, key1);
-        consume(t0, key0, st, qf);
+        fetch(t1, key1, end_key);
+        consume(t0, key0, end_key, st, qf);
         key0 = advance();
-        fetch(t0, key0);
-        if (k + 1 < my_tiles) consume(t1, key1, st, qf);
+        fetch(t0, key0, end_key);
+        if (k + 1 < my_tiles) consume(t1, key1, end_key, st, qf);
+    }
+
+    // The shared tail.  Workgroups do not get through equal ranges in equal times: measured with a timestamp per
+    // workgroup, those of some of the device's eight XCDs take 5-10 % longer over the same number of keys (which
+    // XCDs differs from device to device), and a launch ends with its slowest workgroup.  So the last part of
+    // every (sequence, KV head) belongs to no range: a wavefront that has finished its own tiles takes the next
+    // piece of kTailKeys keys from a counter of the (sequence, KV head).  The order in which keys reach a
+    // wavefront's running softmax does not matter to the result (up to rounding).  Every claim moves the counter
+    // forward, so a wavefront leaves the loop after at most n_pieces claims of all wavefronts together; the
+    // workgroup that merges the splits puts the counter back to zero.
+    if (n_pieces > 0) {                                             // uniform over the workgroup
+        // The (sequence, KV head) pairs hand out their pieces at about the same pace, and their tails sit a fixed
+        // stride apart: as with the start tiles above, each pair starts at a piece of its own, chosen by absolute
+        // address, and wraps around, so that the pairs' reading positions stay spread over the memory channels.
+        unsigned int window = 1;
+        while (2 * window <= (unsigned int)n_pieces && window < 512) window *= 2;
+        const unsigned int n_pairs = gridDim.y * gridDim.z, pair = blockIdx.z * gridDim.y + blockIdx.y;
+        const unsigned int tail_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)a.tail_begin * kHeadDim)) / (kTailKeys * kHeadDim * 2));
+        const int turn = (int)(((pair * window / n_pairs - tail_addr) & (window - 1)) % (unsigned int)n_pieces);
+        auto first_key = [&](int piece) __attribute__((always_inline)) {
+            int at = piece + turn;
+            at = at >= n_pieces ? at - n_pieces : at;
+            return piece < n_pieces ? a.tail_begin + at * kTailKeys : -1;
+        };
+        auto second_key = [&](int key_a) __attribute__((always_inline)) { return key_a >= 0 && key_a + 16 < stored ? key_a + 16 : -1; };
+        // Pieces are claimed two ahead, so a claim has the time of a whole piece to come back, and the tiles of
+        // the next piece are requested as the buffers of the current one are consumed: the loads never pause.
+        int key_a = first_key((int)__builtin_amdgcn_readfirstlane(claim_first)), key_b = second_key(key_a);
+        fetch(t0, key_a, stored);
+        fetch(t1, key_b, stored);
+        while (key_a >= 0) {
+            const unsigned int claim_after = claim();
+            const int next_a = first_key((int)__builtin_amdgcn_readfirstlane(claim_next)), next_b = second_key(next_a);
+            consume(t0, key_a, stored, st, qf);
+            fetch(t0, next_a, stored);
+            if (key_b >= 0) consume(t1, key_b, stored, st, qf);
+            fetch(t1, next_b, stored);
+            claim_next = claim_after;
+            key_a = next_a;
+            key_b = next_b;
+        }
     }
 
     // Merge the four rows of the wavefront with the cross-row swap instructions of gfx950 (vector
@@ -549,7 +605,11 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
             if (dim == 0) { publish(&a.part_ml[row * 2], mx); publish(&a.part_ml[row * 2 + 1], l); }
         }
     }
-    if (single) return;
+    if (single) {
+        // all wavefronts have left the shared tail (the barrier above): its counter is ready for the next launch
+        if (n_pieces > 0 && threadIdx.x == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
 
     // The workgroup that takes the last ticket of its (sequence, KV head) merges all splits:
     // softmax over a union of disjoint key sets is the sum of the per-set results weighted by
@@ -631,7 +691,10 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
         store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);
         if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
     }
-    if (threadIdx.x == 0) __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // ready for the next launch
+    if (threadIdx.x == 0) {                                         // ready for the next launch
+        __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(ticket + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
 }
 
 __global__ void lt_zero_tickets_kernel(unsigned int *tickets, int n)

@@ -13,7 +13,9 @@ constexpr int kMaxGroup = 8;           // query heads per KV head
 constexpr int kWideBlockKeys = 2048;    // decode workgroups with at most this many keys run eight wavefronts, else four
 constexpr int kKeyGranule = 64;        // keys_per_block is a multiple of this
 constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head) is split into
-constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels
+constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels;
+                                       // slot 1 after a ticket counts the pieces handed out of the shared tail
+constexpr int kTailKeys = 32;          // keys per piece of the shared tail (two tiles)
 constexpr int kMaxRaggedBatch = 64;    // sequences a launch can give their own lengths (the lengths travel as kernel arguments)
 constexpr int kScoreTileKeys = 128;    // key ranges of the scoring kernel are multiples of this
 
@@ -61,6 +63,10 @@ struct DecodeArgs {
     int32_t lazy_tag;                  // selects the kernel instantiation (name) only
     int32_t out_bf16;                  // out holds bf16 instead of fp32
     uint32_t spread_tiles;             // window (4 KB tiles, a power of two) the workgroups' start addresses are spread over; 0: pseudo-random starts
+    // Keys from tail_begin on (a multiple of kKeyGranule) belong to no workgroup's range: the wavefronts of the
+    // (sequence, KV head) take them in pieces of kTailKeys, first come first served, once their own tiles are done.
+    // The n_splits ranges of keys_per_block keys then cover [0, tail_begin).  INT32_MAX: no shared tail.
+    int32_t tail_begin;
 };
 // ragged batches: per-sequence stored entries (<= stored, which sizes the grid) and new-token slots (-1: dropped);
 // a separate argument block, so that launches for equal-length batches do not carry it

@@ -21,7 +21,7 @@ OUT_BF16, OUT_F32 = 0, 1
 EXPORTS = [
     "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
     "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
-    "lt_set_split", "lt_profile_enable", "lt_profile_read", "lt_status_str",
+    "lt_set_split", "lt_set_shared_tail", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
     "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
@@ -108,6 +108,8 @@ def load() -> ctypes.CDLL:
     lib.lt_decode_step_active.restype = ctypes.c_int
     lib.lt_set_split.argtypes = [vp, i32, i32]
     lib.lt_set_split.restype = ctypes.c_int
+    lib.lt_set_shared_tail.argtypes = [vp, i32]
+    lib.lt_set_shared_tail.restype = ctypes.c_int
     lib.lt_profile_enable.argtypes = [vp, i32]
     lib.lt_profile_enable.restype = ctypes.c_int
     lib.lt_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
@@ -577,6 +579,9 @@ class Context:
 
     def set_split(self, keys_full: int = 0, keys_lazy: int = 0):
         _check(load().lt_set_split(self._h, int(keys_full), int(keys_lazy)), "lt_set_split")
+
+    def set_shared_tail(self, on: bool = True):
+        _check(load().lt_set_shared_tail(self._h, 1 if on else 0), "lt_set_shared_tail")
 
     def profile_enable(self, on: bool = True):
         _check(load().lt_profile_enable(self._h, 1 if on else 0), "lt_profile_enable")

@@ -84,13 +84,14 @@ void lt_stub_counts(int32_t *out8)
     const int v[8] = {g_log.append, g_log.truncate, g_log.decode, g_log.zero_tickets, g_log.probe, g_log.score, g_log.prefill, g_log.memcpy};
     for (int i = 0; i < 8; ++i) out8[i] = v[i];
 }
-void lt_stub_last_decode(int64_t *out12)
+void lt_stub_last_decode(int64_t *out13)
 {
     const ltk::DecodeArgs &a = g_log.last_decode;
-    const int64_t v[12] = {a.stored, a.keys_per_block, a.n_splits, a.new_slot, a.spread_tiles, a.k_new != nullptr, a.lazy_tag, a.out_bf16,
+    const int64_t v[13] = {a.stored, a.keys_per_block, a.n_splits, a.new_slot, a.spread_tiles, a.k_new != nullptr, a.lazy_tag, a.out_bf16,
                            a.stride_b, a.stride_h, g_log.last_decode_mode,
-                           (int64_t)(reinterpret_cast<const unsigned char *>(a.v_cache) - reinterpret_cast<const unsigned char *>(a.k_cache))};
-    for (int i = 0; i < 12; ++i) out12[i] = v[i];
+                           (int64_t)(reinterpret_cast<const unsigned char *>(a.v_cache) - reinterpret_cast<const unsigned char *>(a.k_cache)),
+                           a.tail_begin};
+    for (int i = 0; i < 13; ++i) out13[i] = v[i];
 }
 void lt_stub_last_lengths(int32_t *stored_b, int32_t *new_slot_b, int32_t n)
 {

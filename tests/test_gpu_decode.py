@@ -80,6 +80,31 @@ def test_many_splits_merge_in_one_launch():
     run_case(B=2, Hq=8, Hkv=2, n_prefill=20000, steps=4, w_sink=4, w_recent=1020, seed=450, split=(256, 64), fused=True)
 
 
+@pytest.mark.parametrize("fused", [False, True])
+def test_long_ranges_share_their_tail(fused):
+    # 128 (sequence, KV head) pairs of 16K keys: two workgroups per pair with ranges above 8192 keys, so the last
+    # eighth of every pair is handed out piece by piece to whichever wavefront is free, the new token's tile included
+    run_case(B=16, Hq=16, Hkv=8, n_prefill=16390, steps=3, w_sink=4, w_recent=1020, seed=470, fused=fused)
+
+
+def test_shared_tail_switched_off_gives_the_same_bits_every_time():
+    B, Hq, Hkv, n = 16, 32, 8, 16500
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, 4, 1020, n)
+    ctx = lt.Context(cfg, [0], DEV)
+    ctx.append_kv(0, randn_bf16((B, Hkv, n, 128), 481), randn_bf16((B, Hkv, n, 128), 482))
+    q = randn_bf16((B, Hq, 128), 483, scale=1.5)
+    say("shared tail on / off, n", n)
+    shared = [ctx.decode_attn(0, q).clone() for _ in range(3)]
+    ctx.set_shared_tail(False)
+    fixed = [ctx.decode_attn(0, q).clone() for _ in range(3)]
+    assert torch.equal(fixed[0], fixed[1]) and torch.equal(fixed[0], fixed[2])
+    for out in shared:                                        # the same keys in another order: rounding only
+        assert (out - fixed[0]).abs().max().item() <= 2e-6
+    ctx.set_shared_tail(True)
+    assert (ctx.decode_attn(0, q) - fixed[0]).abs().max().item() <= 2e-6
+    ctx.close()
+
+
 @pytest.mark.parametrize("split", [(256, 64), (512, 128), (2048, 2048)])
 def test_result_does_not_depend_on_the_split(split):
     run_case(B=1, Hq=8, Hkv=2, n_prefill=3000, steps=2, w_sink=4, w_recent=1020, seed=500, split=split)

@@ -108,6 +108,13 @@ def test_ragged_batch_of_sixteen_groups_of_five():
     run_ragged(lengths, Hq=5, Hkv=1, ws=4, wr=124, steps=2, seed=8400)
 
 
+def test_ragged_batch_with_a_shared_tail():
+    # two workgroups per (sequence, KV head) with ranges above 8192 keys: the launch leaves keys 14336.. to a shared
+    # tail; sequences that end before it, inside it and at its first keys all take part in the same launch
+    lengths = [16390, 9000, 14337, 14336, 14400, 16000, 1, 15000, 16390, 12000, 14350, 16389, 8192, 8193, 16200, 14335]
+    run_ragged(lengths, Hq=16, Hkv=8, ws=4, wr=1020, steps=3, seed=77)
+
+
 def test_sequence_without_tokens_gives_zero():
     cfg = lt.make_config(1, 2, 4, 1, 128, 4, 28, 64)
     ctx = lt.Context(cfg, [0], DEV)

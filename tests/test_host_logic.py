@@ -30,11 +30,14 @@ def counts(lib):
     return dict(zip(("append", "truncate", "decode", "zero_tickets", "probe", "score", "prefill", "memcpy"), out))
 
 
+NO_TAIL = 2 ** 31 - 1                                          # DecodeArgs::tail_begin of a launch without a shared tail
+
+
 def last_decode(lib):
-    out = (ctypes.c_int64 * 12)()
+    out = (ctypes.c_int64 * 13)()
     lib.lt_stub_last_decode(out)
     return dict(zip(("stored", "keys_per_block", "n_splits", "new_slot", "spread_tiles", "fused", "lazy_tag", "out_bf16", "stride_b",
-                     "stride_h", "mode", "v_minus_k"), out))
+                     "stride_h", "mode", "v_minus_k", "tail_begin"), out))
 
 
 def last_lengths(lib, n):
@@ -157,7 +160,15 @@ def test_split_choice_covers_the_keys_and_fills_the_device(B, Hkv, G, n, ws, wr)
         assert c.step(layer) == lt.OK
         d = last_decode(lib)
         assert d["stored"] == stored and d["keys_per_block"] % 64 == 0
-        assert (d["n_splits"] - 1) * d["keys_per_block"] < stored <= d["n_splits"] * d["keys_per_block"]
+        # the ranges tile the stored entries, or, when the ranges are long, all but a shared tail of about an eighth
+        ranged = stored
+        if d["tail_begin"] != NO_TAIL:
+            ranged = d["tail_begin"]
+            assert d["keys_per_block"] >= 4096 and d["n_splits"] > 1 and ranged % 64 == 0
+            assert stored // 8 <= stored - ranged < stored // 8 + 64
+        else:
+            assert d["keys_per_block"] < 8192 + 64 or d["n_splits"] == 1
+        assert (d["n_splits"] - 1) * d["keys_per_block"] < ranged <= d["n_splits"] * d["keys_per_block"]
         assert 1 <= d["n_splits"] <= 512
         groups = d["n_splits"] * B * Hkv
         if stored >= 256 * 256:
@@ -171,6 +182,7 @@ def test_split_choice_covers_the_keys_and_fills_the_device(B, Hkv, G, n, ws, wr)
     keys = 256 * ((n + 8 + 256 * 512 - 1) // (256 * 512))
     assert lib.lt_set_split(c.h, keys, 64) == lt.OK
     assert c.step(0) == lt.OK and last_decode(lib)["keys_per_block"] == keys and last_decode(lib)["n_splits"] == -(-(n + 2) // keys)
+    assert last_decode(lib)["tail_begin"] == NO_TAIL                  # a forced split leaves no shared tail
     assert c.step(1) == lt.OK and last_decode(lib)["keys_per_block"] == 64
     assert lib.lt_set_split(c.h, 64, 0) == lt.ERR_CAPACITY
     assert lib.lt_set_split(c.h, 100, 0) == lt.ERR_INVALID_ARG
@@ -308,3 +320,30 @@ def test_scoring_plans_cover_the_prompt():
             (t["n_chunks"] - t["n_chunks_a"]) * t["keys_per_block"] >= n - t["range_b_begin"]
         assert covered
     assert counts(lib)["score"] == 15
+
+
+def test_shared_tail_only_for_long_ranges_and_can_be_switched_off():
+    lib = stub_lib()
+    lib.lt_set_shared_tail.argtypes = [ctypes.c_void_p, ctypes.c_int32]
+    lib.lt_set_shared_tail.restype = ctypes.c_int
+    cfg = lt.make_config(2, 8, 32, 8, 128, 4, 2044, 40000)
+    c = Ctx(lib, cfg, [0, 1])
+    assert c.append(0, 32768) == lt.OK and c.append(1, 32768) == lt.OK
+    assert c.step(0) == lt.OK
+    d = last_decode(lib)
+    assert d["tail_begin"] == (32769 - 32769 // 8) // 64 * 64 and d["n_splits"] == 4
+    assert c.step(1) == lt.OK and last_decode(lib)["tail_begin"] == NO_TAIL       # a window of 2048 entries: ranges too short
+    assert lib.lt_set_shared_tail(c.h, 0) == lt.OK
+    assert c.step(0) == lt.OK
+    d = last_decode(lib)
+    assert d["tail_begin"] == NO_TAIL and d["n_splits"] * d["keys_per_block"] >= 32770
+    assert lib.lt_set_shared_tail(c.h, 1) == lt.OK
+    assert c.step(0) == lt.OK and last_decode(lib)["tail_begin"] != NO_TAIL
+    assert lib.lt_set_shared_tail(None, 1) == lt.ERR_INVALID_ARG
+    c.close()
+    # one workgroup per (sequence, KV head): nothing to share a tail between
+    cfg = lt.make_config(1, 32, 32, 8, 128, 4, 2044, 17000)
+    c = Ctx(lib, cfg, [0])
+    assert c.append(0, 16384) == lt.OK and c.step(0) == lt.OK
+    assert last_decode(lib)["n_splits"] == 1 and last_decode(lib)["tail_begin"] == NO_TAIL
+    c.close()
