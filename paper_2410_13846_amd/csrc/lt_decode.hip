@@ -641,52 +641,70 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     __syncthreads();
     if (!sh_is_last) return;
     __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");          // compiler ordering: no merge load moves above the ticket
-    // Every (head, split) pair's running max and sum go to LDS; the first eight partial
-    // accumulators of each output element are requested in the same round trip.
-    float first[(G * kHeadDim + kThreads - 1) / kThreads][8];
+    // Every (head, split) pair's running max and sum go to LDS.  In the same memory round trip every thread
+    // requests the partial accumulators of its output elements for the first kEager splits, eight at a time
+    // and only as far as there are splits; launches with more splits than that fetch the rest in further batches.
+    constexpr int kRounds = (G * kHeadDim + kThreads - 1) / kThreads;     // output elements per thread
+    constexpr int kEager = kRounds <= 1 ? 64 : kRounds == 2 ? 32 : 16;
+    float part[kRounds][kEager];
 #pragma unroll
-    for (int r = 0; r < (G * kHeadDim + kThreads - 1) / kThreads; ++r) {
+    for (int r = 0; r < kRounds; ++r) {
         const int idx = threadIdx.x + r * kThreads;
         const int h = (idx < G * kHeadDim ? idx : 0) / kHeadDim, dim = idx % kHeadDim;
         const float *acc = a.part_acc + ((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits * kHeadDim + dim;
 #pragma unroll
-        for (int u = 0; u < 8; ++u) first[r][u] = observe(acc + (int64_t)min(u, a.n_splits - 1) * kHeadDim);
+        for (int u0 = 0; u0 < kEager; u0 += 8)
+            if (u0 < a.n_splits) {                                  // uniform
+#pragma unroll
+                for (int u = u0; u < u0 + 8; ++u) part[r][u] = observe(acc + (int64_t)min(u, a.n_splits - 1) * kHeadDim);
+            }
     }
-    for (int idx = threadIdx.x; idx < G * a.n_splits; idx += kThreads) {
-        const int h = idx / a.n_splits, c = idx % a.n_splits;
-        const float *ml = a.part_ml + (((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + c) * 2;
-        sh_merge_m[h][c] = observe(ml);
-        sh_merge_l[h][c] = observe(ml + 1);
+    // The rows of maxima and sums are padded to a multiple of eight splits with empty entries (-inf, 0), so that
+    // what follows reads them eight at a time without looking at the split count.
+    const int padded_splits = (a.n_splits + 7) & ~7;
+    for (int idx = threadIdx.x; idx < G * padded_splits; idx += kThreads) {
+        const int h = idx / padded_splits, c = idx % padded_splits;
+        const float *ml = a.part_ml + (((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + min(c, a.n_splits - 1)) * 2;
+        const float m_c = observe(ml), l_c = observe(ml + 1);
+        sh_merge_m[h][c] = c < a.n_splits ? m_c : -INFINITY;
+        sh_merge_l[h][c] = c < a.n_splits ? l_c : 0.f;
     }
     __syncthreads();
-    // One thread per (head, dim); further partial accumulators are fetched 24 splits at a time, so that up to
-    // 32 splits cost two memory round trips in all instead of one per split.
+    // One thread per output element.  Everything it reads from LDS comes in groups of eight splits with constant
+    // offsets inside the group, so the reads of a group are issued together; a single wavefront per SIMD is left
+    // at this point, and reads waited for one by one would cost their full latency each.
 #pragma unroll
-    for (int r = 0; r < (G * kHeadDim + kThreads - 1) / kThreads; ++r) {
+    for (int r = 0; r < kRounds; ++r) {
         const int idx = threadIdx.x + r * kThreads;
         if (idx >= G * kHeadDim) break;
         const int h = idx / kHeadDim, dim = idx % kHeadDim;
         const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
         const float *acc = a.part_acc + head * a.n_splits * kHeadDim + dim;
         float mx = -INFINITY;
-        for (int c = 0; c < a.n_splits; ++c) mx = fmaxf(mx, sh_merge_m[h][c]);
+        for (int c0 = 0; c0 < a.n_splits; c0 += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) mx = fmaxf(mx, sh_merge_m[h][c0 + u]);
+        }
+        const float m_safe = mx == -INFINITY ? 0.f : mx;            // no split saw a key: every weight is 0
         float l = 0.f, o = 0.f;
-        auto weigh = [&](int c, float v) {
-            if (c < a.n_splits) {
-                const float wgt = sh_merge_m[h][c] == -INFINITY ? 0.f : fast_exp2(sh_merge_m[h][c] - mx);
-                l += wgt * sh_merge_l[h][c];
-                o += wgt * v;
+        auto weigh8 = [&](int c0, const float *v) __attribute__((always_inline)) {   // splits c0 .. c0 + 7; empty ones weigh 0
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float wgt = fast_exp2(sh_merge_m[h][c0 + u] - m_safe);
+                l = fmaf(wgt, sh_merge_l[h][c0 + u], l);
+                o = fmaf(wgt, v[u], o);
             }
         };
 #pragma unroll
-        for (int u = 0; u < 8; ++u) weigh(u, first[r][u]);
-        constexpr int kBatch = 24;                                  // splits 8.. : this many loads per round trip
-        for (int c0 = 8; c0 < a.n_splits; c0 += kBatch) {
-            float v[kBatch];
+        for (int u0 = 0; u0 < kEager; u0 += 8)
+            if (u0 < a.n_splits) weigh8(u0, &part[r][u0]);
+        for (int c0 = kEager; c0 < a.n_splits; c0 += 32) {         // launches with more than kEager splits: 32 per round trip
+            float v[32];
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) v[u] = observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
+            for (int u = 0; u < 32; ++u) v[u] = observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
 #pragma unroll
-            for (int u = 0; u < kBatch; ++u) weigh(c0 + u, v[u]);
+            for (int u0 = 0; u0 < 32; u0 += 8)
+                if (c0 + u0 < a.n_splits) weigh8(c0 + u0, &v[u0]);
         }
         store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);
         if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
