@@ -617,8 +617,16 @@ static WindowPlan window_plan(const lt_config *cfg, int64_t n, int32_t w_last, l
     first_recent = std::min<int64_t>(std::max<int64_t>(first_recent, 0), n);
     p.b_begin = std::max<int64_t>(p.a_end, first_recent / tile * tile);
     p.keys_per_block = score_keys_per_block(cfg, p.a_end + (n - p.b_begin));
-    p.chunks_a = (int32_t)ceil_div(p.a_end, p.keys_per_block);
-    p.chunks_b = (int32_t)ceil_div(n - p.b_begin, p.keys_per_block);
+    // Each of the two parts is cut on its own, so their ranges can add up to more than one workgroup per compute
+    // unit; the surplus would run as a second round after the first, on a call that is all fixed cost.  Longer
+    // ranges until the workgroups fit in one round (or each part is a single range).
+    const int64_t streams = (int64_t)cfg->batch * cfg->n_kv_heads;
+    for (;;) {
+        p.chunks_a = (int32_t)ceil_div(p.a_end, p.keys_per_block);
+        p.chunks_b = (int32_t)ceil_div(n - p.b_begin, p.keys_per_block);
+        if ((p.chunks_a + p.chunks_b) * streams <= 256 || (p.chunks_a <= 1 && p.chunks_b <= 1)) break;
+        p.keys_per_block += (int32_t)tile;
+    }
     return p;
 }
 

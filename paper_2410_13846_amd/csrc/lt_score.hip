@@ -458,16 +458,22 @@ __global__ __launch_bounds__(kScoreThreads, 1) void lt_lazy_ratio_kernel(ScoreAr
             if (qt >= QT || t >= a.w_last) continue;
             const int h = g * G + qt / QH;
             const float *src = a.part + ((int64_t)b * a.n_q_heads + h) * a.n_chunks * 3 * a.w_last + t;
-            constexpr int kBatch = 16;                              // key ranges per round trip (48 loads), merged in range order
+            // up to 16 key ranges per round trip, requested four at a time and only as far as there are ranges (these
+            // loads go past the caches: every one costs a memory access), merged in range order
+            constexpr int kBatch = 16;
             for (int c0 = 0; c0 < a.n_chunks; c0 += kBatch) {
                 float m[kBatch], f[kBatch], k[kBatch];
 #pragma unroll
-                for (int u = 0; u < kBatch; ++u) {
-                    const float *pc = src + (int64_t)min(c0 + u, a.n_chunks - 1) * 3 * a.w_last;
-                    m[u] = observe(pc);
-                    f[u] = observe(pc + a.w_last);
-                    k[u] = observe(pc + 2 * a.w_last);
-                }
+                for (int u0 = 0; u0 < kBatch; u0 += 4)
+                    if (c0 + u0 < a.n_chunks) {                     // uniform
+#pragma unroll
+                        for (int u = u0; u < u0 + 4; ++u) {
+                            const float *pc = src + (int64_t)min(c0 + u, a.n_chunks - 1) * 3 * a.w_last;
+                            m[u] = observe(pc);
+                            f[u] = observe(pc + a.w_last);
+                            k[u] = observe(pc + 2 * a.w_last);
+                        }
+                    }
 #pragma unroll
                 for (int u = 0; u < kBatch; ++u)
                     if (c0 + u < a.n_chunks) merge_state(fin_m[r], fin_c[r], fin_k[r], m[u], f[u], k[u]);
@@ -519,44 +525,42 @@ __global__ __launch_bounds__(kScoreThreads, 1) void lt_lazy_ratio_kernel(ScoreAr
     }
     __syncthreads();
     if (!*sh_flag) return;
-    // The heads' sums of several sequences at a time come into LDS with one load per thread and round trip; one
-    // thread per sequence then adds its heads in order.
-    constexpr int kHeadSlots = 4096;                            // floats of LDS for the heads' sums (16 KB)
-    float *sh_heads = sh_state;
-    float *sh_sum = sh_state + kHeadSlots;                      // [256]
-    const int seqs_per_pass = max(1, min(kScoreThreads, kHeadSlots / a.n_q_heads));
-    float mine = 0.f;
-    for (int b0 = 0; b0 < a.batch; b0 += seqs_per_pass) {
-        const int n_seq = min(seqs_per_pass, a.batch - b0);
-        float rseq = 0.f;
-        if (a.n_q_heads <= kHeadSlots) {
-            __syncthreads();                                    // the previous pass has been read
-            for (int i = threadIdx.x; i < n_seq * a.n_q_heads; i += kScoreThreads)
-                sh_heads[i] = observe(a.head_scratch + (int64_t)b0 * a.n_q_heads + i);
-            __syncthreads();
-            if ((int)threadIdx.x < n_seq) {
-                float sum = 0.f;
-                for (int h = 0; h < a.n_q_heads; ++h) sum += sh_heads[threadIdx.x * a.n_q_heads + h];
-                rseq = sum / (float)(a.n_q_heads * a.w_last);
+    // A sequence's mean: one wavefront per sequence, lane h takes head h (h + 64, ... when there are more), then a
+    // butterfly over the lanes; eight sequences per wavefront share a memory round trip.  Every addition has a
+    // fixed place, so the result does not depend on the launch.
+    float *sh_sum = sh_state;                                   // [kScoreWaves]
+    float wave_sum = 0.f;
+    for (int b0 = wave; b0 < a.batch; b0 += 8 * kScoreWaves) {
+        float v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int bb = b0 + u * kScoreWaves;
+            v[u] = 0.f;
+            if (bb < a.batch)                                       // uniform over the wavefront
+                for (int h = lane; h < a.n_q_heads; h += 64) v[u] += observe(a.head_scratch + (int64_t)bb * a.n_q_heads + h);
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int bb = b0 + u * kScoreWaves;
+            float x = v[u];
+#pragma unroll
+            for (int mask = 32; mask > 0; mask >>= 1) x += __shfl_xor(x, mask, 64);
+            if (bb < a.batch) {
+                const float rseq = x / (float)(a.n_q_heads * a.w_last);
+                if (lane == 0 && a.ratio_seq != nullptr) a.ratio_seq[bb] = rseq;
+                wave_sum += rseq;
             }
-        } else if (threadIdx.x == 0) {                          // more heads than the buffer holds: one sequence per pass, read directly
-            float sum = 0.f;
-            for (int h = 0; h < a.n_q_heads; ++h) sum += observe(a.head_scratch + (int64_t)b0 * a.n_q_heads + h);
-            rseq = sum / (float)(a.n_q_heads * a.w_last);
-        }
-        if ((int)threadIdx.x < n_seq) {
-            if (a.ratio_seq != nullptr) a.ratio_seq[b0 + threadIdx.x] = rseq;
-            mine += rseq;
         }
     }
+    __syncthreads();                                            // sh_state is no longer read as rho
+    if (lane == 0) sh_sum[wave] = wave_sum;
     __syncthreads();
-    sh_sum[threadIdx.x] = mine;
-    __syncthreads();
-    for (int stride = kScoreThreads / 2; stride > 0; stride >>= 1) {
-        if ((int)threadIdx.x < stride) sh_sum[threadIdx.x] += sh_sum[threadIdx.x + stride];
-        __syncthreads();
+    if (threadIdx.x == 0) {
+        float total = 0.f;
+#pragma unroll
+        for (int w = 0; w < kScoreWaves; ++w) total += sh_sum[w];
+        a.ratio_mean[0] = total / (float)a.batch;
     }
-    if (threadIdx.x == 0) a.ratio_mean[0] = sh_sum[0] / (float)a.batch;
 }
 
 __global__ void lt_score_zero_tickets_kernel(unsigned int *tickets, int n)
