@@ -239,7 +239,7 @@ __device__ __forceinline__ float sum_rows4(float x0, float x1, float x2, float x
 template <int LANE>
 __device__ __forceinline__ float row_broadcast(float x)      // value of lane LANE of the row, in every lane of the row
 {
-    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + LANE, 0xf, 0xf, false));
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), 0x150 + LANE, 0xf, 0xf, true));
 }
 
 template <int G>
