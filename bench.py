@@ -42,6 +42,8 @@ def parse_args():
     ap.add_argument("--n-lazy", type=int, default=None, help="override the number of lazy layers")
     ap.add_argument("--keys-full", type=int, default=0, help="keys per workgroup in full layers (0 = built-in)")
     ap.add_argument("--keys-lazy", type=int, default=0)
+    ap.add_argument("--no-shared-tail", action="store_true",
+                    help="every key in a fixed place (lt_set_shared_tail off): bit-reproducible outputs, for comparison")
     ap.add_argument("--no-speedup", action="store_true", help="skip the all-full comparison run")
     ap.add_argument("--headline-only", action="store_true",
                     help="with the default workload: skip the extra batch-1 and 32K x batch 8 runs")
@@ -80,6 +82,8 @@ def log(*a):
 
 class Stack:
     """A hybrid stack with its decode inputs pre-generated on the device."""
+
+    shared_tail = True                  # --no-shared-tail clears it for every stack of the run
 
     def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0, online=False, page_tokens=0,
                  shuffled=True):
@@ -131,6 +135,8 @@ class Stack:
                 del k, v
         if keys_full or keys_lazy:
             self.ctx.set_split(keys_full, keys_lazy)
+        if not Stack.shared_tail:
+            self.ctx.set_shared_tail(False)
         self.q, self.k, self.v = [], [], []
         for layer in range(wl.n_layers):
             q, k, v = W.decode_qkv_block(wl, layer, 0, total_steps, dev)
@@ -732,6 +738,8 @@ def main():
 
     import lt_workloads as W
     from paper_2410_13846_amd import lt
+
+    Stack.shared_tail = not args.no_shared_tail
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)

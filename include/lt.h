@@ -337,8 +337,8 @@ lt_status lt_set_output_dtype(lt_ctx *ctx, lt_out_dtype dtype);
  *            sum_j softmax_j(softmax_scale * q.k_j) v_j over the stored entries
  *   lse_out  device, fp32 [B][Hq]: natural-log of the softmax denominator; may be NULL
  * One launch: workgroups each take a range of the stored entries and the last one to finish
- * merges the ranges by their log-sum-exp.  On long histories (8192 keys or more per workgroup) the
- * last eighth of the entries is shared out at run time, so the fp32 sums can be taken in a
+ * merges the ranges by their log-sum-exp.  On long histories (thousands of keys per workgroup) the
+ * last part of the entries is shared out at run time, so the fp32 sums can be taken in a
  * different order from launch to launch and outputs may differ in their last bits (a few 1e-7)
  * between two calls on the same inputs; lt_set_shared_tail in lt_measure.h switches that off.
  * LT_ERR_STATE if the layer is empty. */

@@ -20,6 +20,7 @@ constexpr int64_t kMaxTokens = (int64_t)1 << 30;        // per-sequence position
 constexpr int kMinKeysFull = 256;                       // smallest split the decode workspace is sized for (full layers)
 constexpr int kMinKeysLazy = 64;                        // same, lazy layers
 constexpr int kMinKeysSharedTail = 8192;                // key ranges at least this long leave a shared tail
+constexpr int kMinSplitsWideTail = 16;                  // ranges half as long do when a (sequence, KV head) has this many
 constexpr int kMaxEventPairs = 65536;
 constexpr float kLog2e = 1.4426950408889634f;
 
@@ -963,12 +964,17 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     }
     a.n_splits = (int32_t)ceil_div(stored, a.keys_per_block);
     a.tail_begin = INT32_MAX;
-    // Long ranges leave their last eighth to the shared tail (see DecodeArgs::tail_begin): it evens out the
-    // workgroups' different speeds.  Below kMinKeysSharedTail keys per workgroup a wavefront's two pieces in
-    // flight are too large a share of its work for that to pay (measured), and a forced split stays as given.
-    if (ctx->shared_tail && forced <= 0 && !paged && a.n_splits > 1 && a.keys_per_block >= kMinKeysSharedTail) {
+    // Long ranges leave their last part to the shared tail (see DecodeArgs::tail_begin), which evens out the
+    // workgroups' different speeds: an eighth of the keys when a workgroup's range has kMinKeysSharedTail keys or
+    // more; a quarter when it has half of that and a (sequence, KV head) is spread over at least kMinSplitsWideTail
+    // workgroups (128K x batch 1: the many wavefronts of a pair hold two claimed pieces each at the end, so the tail
+    // has to be longer to leave something to hand out; with fewer workgroups per pair such ranges lost time,
+    // measured).  Shorter ranges, paged layers and forced splits keep every key in a fixed place.
+    const bool long_ranges = a.keys_per_block >= kMinKeysSharedTail;
+    const bool many_ranges = a.keys_per_block >= kMinKeysSharedTail / 2 && a.n_splits >= kMinSplitsWideTail;
+    if (ctx->shared_tail && forced <= 0 && !paged && a.n_splits > 1 && (long_ranges || many_ranges)) {
         const int64_t streams = (int64_t)c.batch * c.n_kv_heads;
-        const int64_t begin = (stored - stored / 8) / ltk::kKeyGranule * ltk::kKeyGranule;
+        const int64_t begin = (stored - stored / (long_ranges ? 8 : 4)) / ltk::kKeyGranule * ltk::kKeyGranule;
         const int32_t keys = choose_keys_per_block(begin, streams, l.lazy, ctx->splits_cap);
         if (ceil_div(begin, keys) > 1) {
             a.tail_begin = (int32_t)begin;
