@@ -30,6 +30,15 @@ lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_pe
  * for identical inputs, at 1.5-3.5 % more time on long contexts. */
 lt_status lt_set_shared_tail(lt_ctx *ctx, int32_t on);
 
+/* Which kernel lt_decode_attn / lt_decode_step launch.  Two kernels compute the same attention: one forms q.k and
+ * p.v with vector instructions (dot products and FMAs, probabilities in fp32), the other on the matrix cores
+ * (probabilities as two bf16 terms, fp32 accumulation).  LT_DECODE_AUTO (the default) takes the matrix-core one for
+ * key ranges of 129..2048 keys per workgroup and, with six or more query heads per KV head, for every longer
+ * range; paged layers always run the vector kernel.  The other two values force a kernel (where it exists),
+ * for tests and comparisons. */
+enum { LT_DECODE_AUTO = 0, LT_DECODE_VECTOR = 1, LT_DECODE_MATRIX = 2 };
+lt_status lt_set_decode_path(lt_ctx *ctx, int32_t path);
+
 /* Measurement aid: one launch that reads `bytes` of `buf_dev` (rounded down to a multiple of
  * 16 KiB, and at least that) once, with the same kind of loads the decode kernel uses, and discards
  * them; timed by the caller, it gives the read rate this device sustains, the practical ceiling of

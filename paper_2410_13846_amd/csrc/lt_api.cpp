@@ -102,6 +102,7 @@ struct lt_ctx {
     int32_t keys_full = 0, keys_lazy = 0;      // 0 = heuristic
     bool out_bf16 = false;                     // decode outputs are bf16 instead of fp32
     bool shared_tail = true;                   // long key ranges end in a part the wavefronts share (lt_set_shared_tail)
+    int32_t decode_path = LT_DECODE_AUTO;      // which decode kernel (lt_set_decode_path)
     bool profiling = false;
     std::vector<EventPair> events;             // pool, created on first enable
     size_t events_used = 0;
@@ -964,6 +965,17 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     }
     a.n_splits = (int32_t)ceil_div(stored, a.keys_per_block);
     a.tail_begin = INT32_MAX;
+    // Which kernel.  The vector kernel's instruction count per key grows with the heads of a group: from six heads
+    // on it, not the memory, bounds a long range (eight heads: 4.3 TB/s against 6.4 for the matrix-core kernel,
+    // whose cost does not depend on the group), and over short ranges it bounds the end of every launch.  The
+    // matrix-core kernel works on pairs of tiles, so it needs more than one tile per wavefront to pay, and it
+    // has no paged form.
+    {
+        const int group = c.n_q_heads / c.n_kv_heads;
+        const bool pays = a.keys_per_block > 16 * 8 && (a.keys_per_block <= ltk::kWideBlockKeys || group >= 6);
+        a.matrix_cores = ctx->decode_path == LT_DECODE_MATRIX || (ctx->decode_path == LT_DECODE_AUTO && pays) ? 1 : 0;
+        if (paged) a.matrix_cores = 0;
+    }
     // Long ranges leave their last part to the shared tail (see DecodeArgs::tail_begin), which evens out the
     // workgroups' different speeds: an eighth of the keys when a workgroup's range has kMinKeysSharedTail keys or
     // more; a quarter when it has half of that and a (sequence, KV head) is spread over at least kMinSplitsWideTail
@@ -1137,6 +1149,13 @@ lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_pe
         return LT_ERR_CAPACITY;
     ctx->keys_full = keys_per_block_full;
     ctx->keys_lazy = keys_per_block_lazy;
+    return LT_OK;
+}
+
+lt_status lt_set_decode_path(lt_ctx *ctx, int32_t path)
+{
+    if (ctx == nullptr || (path != LT_DECODE_AUTO && path != LT_DECODE_VECTOR && path != LT_DECODE_MATRIX)) return LT_ERR_INVALID_ARG;
+    ctx->decode_path = path;
     return LT_OK;
 }
 

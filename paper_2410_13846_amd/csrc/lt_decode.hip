@@ -337,6 +337,155 @@ template <> struct ModeArgs<kPagedMode> { typedef PagedArgs type; };
 __device__ __forceinline__ const RaggedArgs &lengths_of(const RaggedArgs &r) { return r; }
 __device__ __forceinline__ const RaggedArgs &lengths_of(const PagedArgs &r) { return r.lengths; }
 
+// What every workgroup does after its wavefronts have put their partial results (running max in log2 units, sum,
+// un-normalised accumulator) into LDS and passed a barrier: merge the wavefronts, publish the split's partial result,
+// and -- in the workgroup that takes the last ticket of its (sequence, KV head) -- merge the splits.  n_pieces > 0:
+// the launch used the shared tail, whose counter goes back to zero here.
+template <int G, int kWaves>
+__device__ __forceinline__ void finish_workgroup(const DecodeArgs &a, int b, int g, int split, int n_pieces, unsigned int *counter,
+                                                 const float (&sh_m)[kWaves][G], const float (&sh_l)[kWaves][G],
+                                                 const float *sh_acc, int acc_stride)
+{
+    // sh_acc: wavefront w's accumulator of head h, dim d at sh_acc[w * acc_stride + h * kHeadDim + d]
+    constexpr int kThreads = 64 * kWaves;
+    __shared__ int sh_is_last;
+    __shared__ float sh_merge_m[G][kMaxSplits];
+    __shared__ float sh_merge_l[G][kMaxSplits];
+    // Merge the wavefronts.  With a single split this is the final result; otherwise store the
+    // split's partial result (un-normalised accumulator, running max in log2 units, sum).
+    const bool single = a.n_splits == 1;
+    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kThreads) {
+        const int h = idx / kHeadDim, dim = idx % kHeadDim;
+        float mx = sh_m[0][h];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sh_m[w][h]);
+        float l = 0.f, o = 0.f;
+#pragma unroll
+        for (int w = 0; w < kWaves; ++w) {
+            const float wgt = (sh_m[w][h] == -INFINITY) ? 0.f : fast_exp2(sh_m[w][h] - mx);
+            l += wgt * sh_l[w][h];
+            o += wgt * sh_acc[w * acc_stride + h * kHeadDim + dim];
+        }
+        const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
+        if (single) {
+            store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);                  // a sequence without tokens gives 0
+            if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
+        } else {
+            const int64_t row = head * a.n_splits + split;
+            publish(&a.part_acc[row * kHeadDim + dim], o);
+            if (dim == 0) { publish(&a.part_ml[row * 2], mx); publish(&a.part_ml[row * 2 + 1], l); }
+        }
+    }
+    if (single) {
+        // all wavefronts have left the shared tail (the barrier above): its counter is ready for the next launch
+        if (n_pieces > 0 && threadIdx.x == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return;
+    }
+
+    // The workgroup that takes the last ticket of its (sequence, KV head) merges all splits:
+    // softmax over a union of disjoint key sets is the sum of the per-set results weighted by
+    // exp(max_c - max) * l_c.
+    //
+    // Ordering between workgroups, made explicit step by step:
+    //  1. Partial results are written with device-scope atomic stores: they bypass the non-coherent
+    //     levels and complete at the point every compute unit of the device reads from.
+    //  2. Every thread waits until ALL of its own vector-memory operations have been acknowledged
+    //     (vmcnt(0); on this architecture stores count in vmcnt), i.e. its partial results are
+    //     visible device-wide.  A fence at workgroup scope would not promise that.
+    //  3. The barrier makes step 2 of every thread precede the ticket, which one thread takes
+    //     with a device-scope atomic add.
+    //  4. The merge loads (device-scope atomic loads, never served from a non-coherent cache
+    //     line) are issued only by a workgroup that has seen the last ticket value come back:
+    //     they depend on it through LDS and a barrier, and the hardware does not issue loads
+    //     past an unresolved branch.  Every other workgroup of the (sequence, KV head) took its
+    //     ticket after its own step 2, so all partial results are complete by then.
+    // No cache write-back or invalidate is involved (a device-scope release fence here costs a
+    // whole-L2 write-back per workgroup and doubled the kernel time).
+    __builtin_amdgcn_s_waitcnt(0x0F70);                             // vmcnt(0): this thread's publish() stores are acknowledged
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // compiler ordering; the hardware wait is the line above
+    __syncthreads();
+    unsigned int *ticket = a.tickets + ((int64_t)b * a.n_kv_heads + g) * kTicketStride;
+    if (threadIdx.x == 0) {
+        const unsigned int t_mine = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        sh_is_last = (t_mine == (unsigned int)(a.n_splits - 1)) ? 1 : 0;
+    }
+    __syncthreads();
+    if (!sh_is_last) return;
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");          // compiler ordering: no merge load moves above the ticket
+    // Every (head, split) pair's running max and sum go to LDS.  In the same memory round trip every thread
+    // requests the partial accumulators of its output elements for the first kEager splits, eight at a time
+    // and only as far as there are splits; launches with more splits than that fetch the rest in further batches.
+    constexpr int kRounds = (G * kHeadDim + kThreads - 1) / kThreads;     // output elements per thread
+    constexpr int kEager = kRounds <= 1 ? 64 : kRounds == 2 ? 32 : 16;
+    float part[kRounds][kEager];
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int idx = threadIdx.x + r * kThreads;
+        const int h = (idx < G * kHeadDim ? idx : 0) / kHeadDim, dim = idx % kHeadDim;
+        const float *acc = a.part_acc + ((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits * kHeadDim + dim;
+#pragma unroll
+        for (int u0 = 0; u0 < kEager; u0 += 8)
+            if (u0 < a.n_splits) {                                  // uniform
+#pragma unroll
+                for (int u = u0; u < u0 + 8; ++u) part[r][u] = observe(acc + (int64_t)min(u, a.n_splits - 1) * kHeadDim);
+            }
+    }
+    // The rows of maxima and sums are padded to a multiple of eight splits with empty entries (-inf, 0), so that
+    // what follows reads them eight at a time without looking at the split count.
+    const int padded_splits = (a.n_splits + 7) & ~7;
+    for (int idx = threadIdx.x; idx < G * padded_splits; idx += kThreads) {
+        const int h = idx / padded_splits, c = idx % padded_splits;
+        const float *ml = a.part_ml + (((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + min(c, a.n_splits - 1)) * 2;
+        const float m_c = observe(ml), l_c = observe(ml + 1);
+        sh_merge_m[h][c] = c < a.n_splits ? m_c : -INFINITY;
+        sh_merge_l[h][c] = c < a.n_splits ? l_c : 0.f;
+    }
+    __syncthreads();
+    // One thread per output element.  Everything it reads from LDS comes in groups of eight splits with constant
+    // offsets inside the group, so the reads of a group are issued together; a single wavefront per SIMD is left
+    // at this point, and reads waited for one by one would cost their full latency each.
+#pragma unroll
+    for (int r = 0; r < kRounds; ++r) {
+        const int idx = threadIdx.x + r * kThreads;
+        if (idx >= G * kHeadDim) break;
+        const int h = idx / kHeadDim, dim = idx % kHeadDim;
+        const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
+        const float *acc = a.part_acc + head * a.n_splits * kHeadDim + dim;
+        float mx = -INFINITY;
+        for (int c0 = 0; c0 < a.n_splits; c0 += 8) {
+#pragma unroll
+            for (int u = 0; u < 8; ++u) mx = fmaxf(mx, sh_merge_m[h][c0 + u]);
+        }
+        const float m_safe = mx == -INFINITY ? 0.f : mx;            // no split saw a key: every weight is 0
+        float l = 0.f, o = 0.f;
+        auto weigh8 = [&](int c0, const float *v) __attribute__((always_inline)) {   // splits c0 .. c0 + 7; empty ones weigh 0
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const float wgt = fast_exp2(sh_merge_m[h][c0 + u] - m_safe);
+                l = fmaf(wgt, sh_merge_l[h][c0 + u], l);
+                o = fmaf(wgt, v[u], o);
+            }
+        };
+#pragma unroll
+        for (int u0 = 0; u0 < kEager; u0 += 8)
+            if (u0 < a.n_splits) weigh8(u0, &part[r][u0]);
+        for (int c0 = kEager; c0 < a.n_splits; c0 += 32) {         // launches with more than kEager splits: 32 per round trip
+            float v[32];
+#pragma unroll
+            for (int u = 0; u < 32; ++u) v[u] = observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
+#pragma unroll
+            for (int u0 = 0; u0 < 32; u0 += 8)
+                if (c0 + u0 < a.n_splits) weigh8(c0 + u0, &v[u0]);
+        }
+        store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);
+        if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
+    }
+    if (threadIdx.x == 0) {                                         // ready for the next launch
+        __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(ticket + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
 template <int G, int LAZY_TAG, int kWaves, int kMode>
 __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
 {
@@ -345,9 +494,6 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
     __shared__ float sh_acc[kWaves][G][kHeadDim];
-    __shared__ int sh_is_last;
-    __shared__ float sh_merge_m[G][kMaxSplits];
-    __shared__ float sh_merge_l[G][kMaxSplits];
 
     const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
     const int lane = threadIdx.x & 63;
@@ -580,139 +726,273 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     }
     __syncthreads();
 
-    // Merge the wavefronts.  With a single split this is the final result; otherwise store the
-    // split's partial result (un-normalised accumulator, running max in log2 units, sum).
-    const bool single = a.n_splits == 1;
-    for (int idx = threadIdx.x; idx < G * kHeadDim; idx += kThreads) {
-        const int h = idx / kHeadDim, dim = idx % kHeadDim;
-        float mx = sh_m[0][h];
+    finish_workgroup<G, kWaves>(a, b, g, split, n_pieces, counter, sh_m, sh_l, &sh_acc[0][0][0], G * kHeadDim);
+}
+
+// ---------------------------------------------------------------------------------------------
+// The same split decode attention with both products on the matrix cores, for short key ranges.
+//
+// Over a short range a launch is bound by the vector instructions of process_tile (about 400 per 16-key tile
+// for four heads: the time of eight tiles per SIMD, not the bytes, ends a launch over 2048 entries).  Here a
+// wavefront still loads its tiles the same way (one coalesced kilobyte per load, two tiles in flight), but hands
+// each pair of tiles to v_mfma_f32_16x16x32_bf16 through a stretch of LDS of its own:
+//   S^T = K Q^T   rows = 16 keys, columns = 16 head slots (G of them in use), contraction over 32 dims per
+//                 instruction: K rows are written to LDS as loaded and read back one row per lane;
+//   O^T = V^T P^T rows = 16 dims, columns = head slots, contraction over the 32 keys of the pair: V is
+//                 transposed 8 x 4 in registers (four keys of a lane's eight dims) on its way into LDS.
+// A lane's logits of a tile are those of keys 4 i + j (i = 0..3, j = lane / 16), the keys whose V entries the
+// transposing lane j wrote side by side, so the probabilities a lane computes are, packed to bf16, its own piece of
+// the B operand.  They go in as two bf16 terms (p = hi + lo): a single bf16 would put 2^-9 of relative error on
+// every probability, which the 2e-3 bound on the output does not leave room for; K, Q and V are bf16 already, so
+// their products are exact and everything is accumulated in fp32.
+// ---------------------------------------------------------------------------------------------
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
+typedef __attribute__((__vector_size__(4 * sizeof(float)))) float floatx4_t;
+typedef float float2_t __attribute__((ext_vector_type(2)));
+typedef __bf16 bf16x2v_t __attribute__((ext_vector_type(2)));
+
+constexpr int kMfmaKRow = 2 * kHeadDim + 16;              // bytes of a K row in LDS: 16 bytes of padding spread the row reads over the banks
+constexpr int kMfmaVRow = 64 + 16;                        // bytes of a V^T row: 32 key slots of the pair, padded
+constexpr int kMfmaWaveBytes = 16 * kMfmaKRow + kHeadDim * kMfmaVRow;   // one K tile + the pair's V^T: 14592 bytes per wavefront
+
+__device__ __forceinline__ uint32_t pack_bf16_pair(float lo, float hi)
+{
+    const float2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2v_t));
+}
+
+__device__ __forceinline__ float sum_rows(float x)                 // sum of x over the four 16-lane rows, in every row
+{
+    float a = x, b = x;
+    swap_rows16(a, b);
+    const float s = a + b;
+    a = s;
+    b = s;
+    swap_rows32(a, b);
+    return a + b;
+}
+
+template <int G, int LAZY_TAG, int kMode>
+__global__ __launch_bounds__(512) void lt_decode_mfma_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
+{
+    static_assert(kMode != kPagedMode, "paged layers use the other kernel");
+    constexpr bool kRagged = kMode != kUniform;
+    constexpr int kWaves = 8;
+    __shared__ float sh_m[kWaves][G];
+    __shared__ float sh_l[kWaves][G];
+    __shared__ __attribute__((aligned(16))) char sh_stage[kWaves][kMfmaWaveBytes];   // later: each wavefront's accumulators
+
+    const int split = blockIdx.x, g = blockIdx.y, b = blockIdx.z;
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int sub = lane >> 4, chunk = lane & 15;               // as a loader: keys 4 i + sub, dims 8 chunk .. 8 chunk + 7
+    const int slot = lane & 15, j = lane >> 4;                  // as a matrix operand: row / column `slot`, k-slice j
+
+    int stored = a.stored;
+    if constexpr (kRagged) stored = lengths_of(r).stored_b[b];
+    const int begin_key = split * a.keys_per_block;
+    // the workgroup's own range ends where the shared tail begins (see lt_decode_kernel); a tile lies inside the range
+    // or inside the tail, so `stored` is the only bound a key has to be checked against
+    const int end_key = min(min(stored, a.tail_begin), begin_key + a.keys_per_block);
+    const int n_tiles = max((end_key - begin_key + 15) >> 4, 0);
+    const int wrap = max(n_tiles, 1);
+    uint16_t *kb = a.k_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
+    uint16_t *vb = a.v_cache + (int64_t)b * a.stride_b + (int64_t)g * a.stride_h;
+    int new_slot = a.k_new != nullptr ? a.new_slot : -1;
+    if constexpr (kRagged) new_slot = a.k_new != nullptr ? lengths_of(r).new_slot_b[b] : -1;
+    const int64_t new_off = new_slot >= 0 ? ((int64_t)b * a.n_kv_heads + g) * kHeadDim : 0;
+    const uint16_t *k_new = a.k_new + new_off;
+    const uint16_t *v_new = a.v_new + new_off;
+    const uint16_t *hot = a.q + ((int64_t)b * a.n_q_heads + g * G) * kHeadDim;
+
+    // Q^T as the B operand: column `slot` is head g G + slot (zeros beyond the group), k-slice j of k-block kb is
+    // dims 32 kb + 8 j .. + 7
+    bf16x8_t qb[4];
 #pragma unroll
-        for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, sh_m[w][h]);
-        float l = 0.f, o = 0.f;
-#pragma unroll
-        for (int w = 0; w < kWaves; ++w) {
-            const float wgt = (sh_m[w][h] == -INFINITY) ? 0.f : fast_exp2(sh_m[w][h] - mx);
-            l += wgt * sh_l[w][h];
-            o += wgt * sh_acc[w][h][dim];
-        }
-        const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
-        if (single) {
-            store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);                  // a sequence without tokens gives 0
-            if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
-        } else {
-            const int64_t row = head * a.n_splits + split;
-            publish(&a.part_acc[row * kHeadDim + dim], o);
-            if (dim == 0) { publish(&a.part_ml[row * 2], mx); publish(&a.part_ml[row * 2 + 1], l); }
-        }
-    }
-    if (single) {
-        // all wavefronts have left the shared tail (the barrier above): its counter is ready for the next launch
-        if (n_pieces > 0 && threadIdx.x == 0) __hip_atomic_store(counter, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        return;
+    for (int kq = 0; kq < 4; ++kq) {
+        u32x4_t u = {0u, 0u, 0u, 0u};
+        if (slot < G) u = load16(a.q + ((int64_t)b * a.n_q_heads + g * G + slot) * kHeadDim + 32 * kq + 8 * j);
+        qb[kq] = __builtin_bit_cast(bf16x8_t, u);
     }
 
-    // The workgroup that takes the last ticket of its (sequence, KV head) merges all splits:
-    // softmax over a union of disjoint key sets is the sum of the per-set results weighted by
-    // exp(max_c - max) * l_c.
-    //
-    // Ordering between workgroups, made explicit step by step:
-    //  1. Partial results are written with device-scope atomic stores: they bypass the non-coherent
-    //     levels and complete at the point every compute unit of the device reads from.
-    //  2. Every thread waits until ALL of its own vector-memory operations have been acknowledged
-    //     (vmcnt(0); on this architecture stores count in vmcnt), i.e. its partial results are
-    //     visible device-wide.  A fence at workgroup scope would not promise that.
-    //  3. The barrier makes step 2 of every thread precede the ticket, which one thread takes
-    //     with a device-scope atomic add.
-    //  4. The merge loads (device-scope atomic loads, never served from a non-coherent cache
-    //     line) are issued only by a workgroup that has seen the last ticket value come back:
-    //     they depend on it through LDS and a barrier, and the hardware does not issue loads
-    //     past an unresolved branch.  Every other workgroup of the (sequence, KV head) took its
-    //     ticket after its own step 2, so all partial results are complete by then.
-    // No cache write-back or invalidate is involved (a device-scope release fence here costs a
-    // whole-L2 write-back per workgroup and doubled the kernel time).
-    __builtin_amdgcn_s_waitcnt(0x0F70);                             // vmcnt(0): this thread's publish() stores are acknowledged
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");          // compiler ordering; the hardware wait is the line above
-    __syncthreads();
-    unsigned int *ticket = a.tickets + ((int64_t)b * a.n_kv_heads + g) * kTicketStride;
-    if (threadIdx.x == 0) {
-        const unsigned int t_mine = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        sh_is_last = (t_mine == (unsigned int)(a.n_splits - 1)) ? 1 : 0;
-    }
-    __syncthreads();
-    if (!sh_is_last) return;
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");          // compiler ordering: no merge load moves above the ticket
-    // Every (head, split) pair's running max and sum go to LDS.  In the same memory round trip every thread
-    // requests the partial accumulators of its output elements for the first kEager splits, eight at a time
-    // and only as far as there are splits; launches with more splits than that fetch the rest in further batches.
-    constexpr int kRounds = (G * kHeadDim + kThreads - 1) / kThreads;     // output elements per thread
-    constexpr int kEager = kRounds <= 1 ? 64 : kRounds == 2 ? 32 : 16;
-    float part[kRounds][kEager];
+    // start tiles as in lt_decode_kernel: spread over the memory channels, wrapping inside the range
+    const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
+    const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)begin_key * kHeadDim)) >> 12);
+    const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
+    const int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
+                                     : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+    const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
+    int next_tile = wave + phase, fetched = 0;
+    while (next_tile >= wrap) next_tile -= wrap;
+    auto advance = [&]() {                                          // first key of the next tile to fetch, -1 past the last
+        const int cur = next_tile;
+        next_tile += kWaves;
+        while (next_tile >= wrap) next_tile -= wrap;
+        return fetched++ < my_tiles ? begin_key + 16 * cur : -1;
+    };
+
+    char *stage = sh_stage[wave];
+    char *k_rows = stage, *v_rows = stage + 16 * kMfmaKRow;
+    // this lane's places: where its loaded pieces go, and where its operand rows are read
+    const int k_write = sub * kMfmaKRow + chunk * 16;                       // + 4 i rows for load i
+    const int k_read = (4 * (slot & 3) + (slot >> 2)) * kMfmaKRow + 16 * j; // operand row `slot` is key 4 (slot % 4) + slot / 4; + 64 per k-block
+    const int v_write = 8 * chunk * kMfmaVRow + 16 * sub;                   // + one row per dim of the chunk; 8 bytes further for the pair's second tile
+    const int v_read = slot * kMfmaVRow + 16 * j;                           // + 16 rows per dim tile
+
+    float m_run = -INFINITY, l_run = 0.f;       // of this lane's head slot; m_run is the same in the four lanes of a slot
+    floatx4_t acc[8];                           // O^T: acc[dt][i] = dim 16 dt + 4 j + i of head slot `slot`
 #pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int idx = threadIdx.x + r * kThreads;
-        const int h = (idx < G * kHeadDim ? idx : 0) / kHeadDim, dim = idx % kHeadDim;
-        const float *acc = a.part_acc + ((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits * kHeadDim + dim;
+    for (int dt = 0; dt < 8; ++dt) acc[dt] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+    // S^T of one tile (in LDS rows 0..15) for this lane: logits of keys key0 + 4 i + j, scaled, -inf where there is no key
+    auto logits = [&](const Tile &t, int key0, float (&s4)[4]) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u0 = 0; u0 < kEager; u0 += 8)
-            if (u0 < a.n_splits) {                                  // uniform
+        for (int i = 0; i < 4; ++i) *reinterpret_cast<u32x4_t *>(k_rows + k_write + 4 * i * kMfmaKRow) = t.k[i];
+        floatx4_t c = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                for (int u = u0; u < u0 + 8; ++u) part[r][u] = observe(acc + (int64_t)min(u, a.n_splits - 1) * kHeadDim);
-            }
-    }
-    // The rows of maxima and sums are padded to a multiple of eight splits with empty entries (-inf, 0), so that
-    // what follows reads them eight at a time without looking at the split count.
-    const int padded_splits = (a.n_splits + 7) & ~7;
-    for (int idx = threadIdx.x; idx < G * padded_splits; idx += kThreads) {
-        const int h = idx / padded_splits, c = idx % padded_splits;
-        const float *ml = a.part_ml + (((int64_t)b * a.n_q_heads + g * G + h) * a.n_splits + min(c, a.n_splits - 1)) * 2;
-        const float m_c = observe(ml), l_c = observe(ml + 1);
-        sh_merge_m[h][c] = c < a.n_splits ? m_c : -INFINITY;
-        sh_merge_l[h][c] = c < a.n_splits ? l_c : 0.f;
-    }
-    __syncthreads();
-    // One thread per output element.  Everything it reads from LDS comes in groups of eight splits with constant
-    // offsets inside the group, so the reads of a group are issued together; a single wavefront per SIMD is left
-    // at this point, and reads waited for one by one would cost their full latency each.
-#pragma unroll
-    for (int r = 0; r < kRounds; ++r) {
-        const int idx = threadIdx.x + r * kThreads;
-        if (idx >= G * kHeadDim) break;
-        const int h = idx / kHeadDim, dim = idx % kHeadDim;
-        const int64_t head = (int64_t)b * a.n_q_heads + g * G + h;
-        const float *acc = a.part_acc + head * a.n_splits * kHeadDim + dim;
-        float mx = -INFINITY;
-        for (int c0 = 0; c0 < a.n_splits; c0 += 8) {
-#pragma unroll
-            for (int u = 0; u < 8; ++u) mx = fmaxf(mx, sh_merge_m[h][c0 + u]);
+        for (int kq = 0; kq < 4; ++kq) {
+            const bf16x8_t kf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(k_rows + k_read + 64 * kq));
+            c = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qb[kq], c, 0, 0, 0);
         }
-        const float m_safe = mx == -INFINITY ? 0.f : mx;            // no split saw a key: every weight is 0
-        float l = 0.f, o = 0.f;
-        auto weigh8 = [&](int c0, const float *v) __attribute__((always_inline)) {   // splits c0 .. c0 + 7; empty ones weigh 0
 #pragma unroll
-            for (int u = 0; u < 8; ++u) {
-                const float wgt = fast_exp2(sh_merge_m[h][c0 + u] - m_safe);
-                l = fmaf(wgt, sh_merge_l[h][c0 + u], l);
-                o = fmaf(wgt, v[u], o);
-            }
-        };
+        for (int i = 0; i < 4; ++i) s4[i] = (key0 >= 0 && key0 + 4 * i + j < stored) ? c[i] * a.scale_log2e : -INFINITY;
+    };
+    // the V entries of one tile, transposed, into the pair's V^T rows (second: the tile is the pair's second)
+    auto park_values = [&](const Tile &t, int second) __attribute__((always_inline)) {
 #pragma unroll
-        for (int u0 = 0; u0 < kEager; u0 += 8)
-            if (u0 < a.n_splits) weigh8(u0, &part[r][u0]);
-        for (int c0 = kEager; c0 < a.n_splits; c0 += 32) {         // launches with more than kEager splits: 32 per round trip
-            float v[32];
-#pragma unroll
-            for (int u = 0; u < 32; ++u) v[u] = observe(acc + (int64_t)min(c0 + u, a.n_splits - 1) * kHeadDim);
-#pragma unroll
-            for (int u0 = 0; u0 < 32; u0 += 8)
-                if (c0 + u0 < a.n_splits) weigh8(c0 + u0, &v[u0]);
+        for (int w = 0; w < 4; ++w) {
+            // dims 2 w (low halves) and 2 w + 1 (high halves) of the lane's four keys
+            const uint32_t e0 = __builtin_amdgcn_perm(t.v[1][w], t.v[0][w], 0x05040100u), e1 = __builtin_amdgcn_perm(t.v[3][w], t.v[2][w], 0x05040100u);
+            const uint32_t o0 = __builtin_amdgcn_perm(t.v[1][w], t.v[0][w], 0x07060302u), o1 = __builtin_amdgcn_perm(t.v[3][w], t.v[2][w], 0x07060302u);
+            typedef __attribute__((__vector_size__(2 * sizeof(uint32_t)))) uint32_t u32x2_t;
+            *reinterpret_cast<u32x2_t *>(v_rows + v_write + (2 * w) * kMfmaVRow + 8 * second) = u32x2_t{e0, e1};
+            *reinterpret_cast<u32x2_t *>(v_rows + v_write + (2 * w + 1) * kMfmaVRow + 8 * second) = u32x2_t{o0, o1};
         }
-        store_out(a, head * kHeadDim + dim, l > 0.f ? o / l : 0.f);
-        if (a.lse != nullptr && dim == 0) a.lse[head] = (mx + log2f(l)) * kLn2;
+    };
+
+    // The shared tail (see lt_decode_kernel): pieces of two tiles handed out by a counter of the (sequence, KV head).
+    // The first two claims are made right away -- every wavefront is in for two pieces -- and each later one when a
+    // piece is taken up, so a claim has come back long before its piece is needed.
+    const int n_pieces = stored > a.tail_begin ? (stored - a.tail_begin + kTailKeys - 1) / kTailKeys : 0;
+    unsigned int *counter = a.tickets + ((int64_t)b * a.n_kv_heads + g) * kTicketStride + 1;
+    auto claim = [&]() __attribute__((always_inline)) {
+        unsigned int c = 0;
+        if (lane == 0) c = __hip_atomic_fetch_add(counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        return c;
+    };
+    unsigned int claim_a = 0, claim_b = 0;
+    int turn = 0;
+    if (n_pieces > 0) {
+        claim_a = claim();
+        claim_b = claim();
+        unsigned int window = 1;
+        while (2 * window <= (unsigned int)n_pieces && window < 512) window *= 2;
+        const unsigned int n_pairs = gridDim.y * gridDim.z, pair = blockIdx.z * gridDim.y + blockIdx.y;
+        const unsigned int tail_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)a.tail_begin * kHeadDim)) / (kTailKeys * kHeadDim * 2));
+        turn = (int)(((pair * window / n_pairs - tail_addr) & (window - 1)) % (unsigned int)n_pieces);
     }
-    if (threadIdx.x == 0) {                                         // ready for the next launch
-        __hip_atomic_store(ticket, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        __hip_atomic_store(ticket + 1, 0u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    // first keys of the two tiles of a piece of the tail (-1: no such piece, or no second tile)
+    auto piece_keys = [&](unsigned int claimed, int &key_a, int &key_b) __attribute__((always_inline)) {
+        const int piece = (int)__builtin_amdgcn_readfirstlane(claimed);
+        int at = piece + turn;
+        at = at >= n_pieces ? at - n_pieces : at;
+        key_a = piece < n_pieces ? a.tail_begin + at * kTailKeys : -1;
+        key_b = key_a >= 0 && key_a + 16 < stored ? key_a + 16 : -1;
+    };
+
+    // One pair of tiles: new token into the cache, both tiles to LDS, the registers refilled with the next pair,
+    // then the two products.
+    auto work = [&](Tile &ta, Tile &tb, int &key_a, int &key_b, int after_a, int after_b) __attribute__((always_inline)) {
+        store_new_token(ta, kb, vb, key_a, sub, chunk, stored - 1, new_slot);
+        if (key_b >= 0) store_new_token(tb, kb, vb, key_b, sub, chunk, stored - 1, new_slot);
+        float s[8];
+        logits(ta, key_a, reinterpret_cast<float (&)[4]>(s[0]));
+        logits(tb, key_b, reinterpret_cast<float (&)[4]>(s[4]));
+        park_values(ta, 0);
+        park_values(tb, 1);
+        // the registers are free: the next pair travels while this one is worked on (refilling each tile as soon as
+        // it was in LDS, half a pair earlier, was slower)
+        key_a = after_a;
+        key_b = after_b;
+        load_tile(ta, kb, vb, key_a, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+        load_tile(tb, kb, vb, key_b, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+
+        // online softmax of the head slot over the pair's 32 keys (8 per lane, the four lanes of a slot together)
+        float tmax = s[0];
+#pragma unroll
+        for (int i = 1; i < 8; ++i) tmax = fmaxf(tmax, s[i]);
+        tmax = max_rows(tmax);
+        if (__any(tmax > m_run)) {
+            const float m_new = fmaxf(m_run, tmax);
+            const float alpha = (m_new == -INFINITY) ? 1.f : fast_exp2(m_run - m_new);   // 0 while m_run = -inf
+            m_run = m_new;
+            l_run *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[dt][i] *= alpha;
+        }
+        const float m_safe = (m_run == -INFINITY) ? 0.f : m_run;
+        float p[8], p_hi[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            p[i] = fast_exp2(s[i] - m_safe);
+            l_run += p[i];
+        }
+        uint32_t hi[4], lo[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            hi[i] = pack_bf16_pair(p[2 * i], p[2 * i + 1]);
+            p_hi[2 * i] = bf16_lo(hi[i]);
+            p_hi[2 * i + 1] = bf16_hi(hi[i]);
+            lo[i] = pack_bf16_pair(p[2 * i] - p_hi[2 * i], p[2 * i + 1] - p_hi[2 * i + 1]);
+        }
+        const bf16x8_t b_hi = __builtin_bit_cast(bf16x8_t, u32x4_t{hi[0], hi[1], hi[2], hi[3]});
+        const bf16x8_t b_lo = __builtin_bit_cast(bf16x8_t, u32x4_t{lo[0], lo[1], lo[2], lo[3]});
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) {
+            const bf16x8_t vf = __builtin_bit_cast(bf16x8_t, *reinterpret_cast<const u32x4_t *>(v_rows + v_read + 16 * dt * kMfmaVRow));
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, b_hi, acc[dt], 0, 0, 0);
+            acc[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, b_lo, acc[dt], 0, 0, 0);
+        }
+    };
+
+    // The wavefront's own tiles, pair by pair; the last pair is followed by the wavefront's first piece of the tail
+    // (claimed at the start), so that the loads do not pause between the two parts.  No claim is made inside this loop:
+    // the wait counts of its loads stay exact.
+    Tile t0, t1;
+    int key0 = advance(), key1 = advance();
+    if (key0 < 0 && n_pieces > 0) piece_keys(claim_a, key0, key1);         // a wavefront without tiles of its own
+    load_tile(t0, kb, vb, key0, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+    load_tile(t1, kb, vb, key1, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+    for (int k = 0; k < my_tiles; k += 2) {
+        int after_a = advance(), after_b = advance();
+        if (after_a < 0 && n_pieces > 0) piece_keys(claim_a, after_a, after_b);     // the last round
+        work(t0, t1, key0, key1, after_a, after_b);
     }
+    // the tail: the piece after the one in hand was claimed a round ago (or at the start)
+    while (n_pieces > 0 && key0 >= 0) {
+        int after_a, after_b;
+        piece_keys(claim_b, after_a, after_b);
+        claim_b = claim();
+        work(t0, t1, key0, key1, after_a, after_b);
+    }
+
+    // this wavefront's partial result into LDS: its accumulators go where its tiles were (nobody else reads there)
+    const float l_slot = sum_rows(l_run);
+    float *acc_out = reinterpret_cast<float *>(stage);
+    if (slot < G) {
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) *reinterpret_cast<floatx4_t *>(acc_out + slot * kHeadDim + 16 * dt + 4 * j) = acc[dt];
+        if (j == 0) {
+            sh_m[wave][slot] = m_run;
+            sh_l[wave][slot] = l_slot;
+        }
+    }
+    __syncthreads();
+    finish_workgroup<G, kWaves>(a, b, g, split, n_pieces, counter, sh_m, sh_l,
+                                reinterpret_cast<const float *>(&sh_stage[0][0]), kMfmaWaveBytes / 4);
 }
 
 __global__ void lt_zero_tickets_kernel(unsigned int *tickets, int n)
@@ -727,6 +1007,12 @@ hipError_t launch_decode_as(const DecodeArgs &a, const typename ModeArgs<kMode>:
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
     // short ranges: eight wavefronts per workgroup; not for groups of eight heads, whose state needs more than
     // the 256 registers a wavefront has when two share a SIMD
+    if constexpr (kMode != kPagedMode) {
+        if (a.matrix_cores) {
+            hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, kMode>), grid, dim3(512), 0, stream, a, r);
+            return hipGetLastError();
+        }
+    }
     if constexpr (G < 8) {
         if (a.keys_per_block <= kWideBlockKeys) {
             hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);

@@ -17,11 +17,12 @@ RECENT_PER_QUERY, RECENT_FIXED = 0, 1
 KERNEL_DECODE_FULL, KERNEL_DECODE_LAZY, KERNEL_APPEND = range(3)
 MASK_CAUSAL, MASK_STREAMING = 0, 1
 OUT_BF16, OUT_F32 = 0, 1
+DECODE_AUTO, DECODE_VECTOR, DECODE_MATRIX = 0, 1, 2
 
 EXPORTS = [
     "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
     "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
-    "lt_set_split", "lt_set_shared_tail", "lt_profile_enable", "lt_profile_read", "lt_status_str",
+    "lt_set_split", "lt_set_shared_tail", "lt_set_decode_path", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
     "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
@@ -110,6 +111,8 @@ def load() -> ctypes.CDLL:
     lib.lt_set_split.restype = ctypes.c_int
     lib.lt_set_shared_tail.argtypes = [vp, i32]
     lib.lt_set_shared_tail.restype = ctypes.c_int
+    lib.lt_set_decode_path.argtypes = [vp, i32]
+    lib.lt_set_decode_path.restype = ctypes.c_int
     lib.lt_profile_enable.argtypes = [vp, i32]
     lib.lt_profile_enable.restype = ctypes.c_int
     lib.lt_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
@@ -432,6 +435,11 @@ class Context:
             _check(st, "lt_create")
         self._h = handle
         self.out_dtype = torch.float32
+        # LT_DECODE_PATH=vector|matrix forces one of the two decode kernels for every context of the process (the test
+        # suite runs its decode tests once more on each); unset or "auto": the library chooses per launch
+        forced = os.environ.get("LT_DECODE_PATH", "auto")
+        if forced != "auto":
+            self.set_decode_path({"vector": DECODE_VECTOR, "matrix": DECODE_MATRIX}[forced])
 
     def check_guards(self) -> bool:
         """True when the guard bands around the slab and the workspace still hold their pattern."""
@@ -579,6 +587,10 @@ class Context:
 
     def set_split(self, keys_full: int = 0, keys_lazy: int = 0):
         _check(load().lt_set_split(self._h, int(keys_full), int(keys_lazy)), "lt_set_split")
+
+    def set_decode_path(self, path: int = 0):
+        """DECODE_AUTO, DECODE_VECTOR or DECODE_MATRIX."""
+        _check(load().lt_set_decode_path(self._h, int(path)), "lt_set_decode_path")
 
     def set_shared_tail(self, on: bool = True):
         _check(load().lt_set_shared_tail(self._h, 1 if on else 0), "lt_set_shared_tail")
