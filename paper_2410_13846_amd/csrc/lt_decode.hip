@@ -772,12 +772,11 @@ __device__ __forceinline__ float sum_rows(float x)                 // sum of x o
     return a + b;
 }
 
-template <int G, int LAZY_TAG, int kMode>
-__global__ __launch_bounds__(512) void lt_decode_mfma_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
+template <int G, int LAZY_TAG, int kWaves, int kMode>
+__global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
 {
     static_assert(kMode != kPagedMode, "paged layers use the other kernel");
     constexpr bool kRagged = kMode != kUniform;
-    constexpr int kWaves = 8;
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
     __shared__ __attribute__((aligned(16))) char sh_stage[kWaves][kMfmaWaveBytes];   // later: each wavefront's accumulators
@@ -1009,7 +1008,9 @@ hipError_t launch_decode_as(const DecodeArgs &a, const typename ModeArgs<kMode>:
     // the 256 registers a wavefront has when two share a SIMD
     if constexpr (kMode != kPagedMode) {
         if (a.matrix_cores) {
-            hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, kMode>), grid, dim3(512), 0, stream, a, r);
+            // as in the vector kernel: eight wavefronts for short ranges, four for long ones
+            if (a.keys_per_block <= kWideBlockKeys) hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);
+            else hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 4, kMode>), grid, dim3(256), 0, stream, a, r);
             return hipGetLastError();
         }
     }
