@@ -34,8 +34,7 @@ lt_status lt_set_shared_tail(lt_ctx *ctx, int32_t on);
  * p.v with vector instructions (dot products and FMAs, probabilities in fp32), the other on the matrix cores
  * (probabilities as two bf16 terms, fp32 accumulation).  LT_DECODE_AUTO (the default) takes the matrix-core one for
  * key ranges of 129..2048 keys per workgroup and, with six or more query heads per KV head, for every longer
- * range; paged layers always run the vector kernel.  The other two values force a kernel (where it exists),
- * for tests and comparisons. */
+ * range.  The other two values force a kernel, for tests and comparisons. */
 enum { LT_DECODE_AUTO = 0, LT_DECODE_VECTOR = 1, LT_DECODE_MATRIX = 2 };
 lt_status lt_set_decode_path(lt_ctx *ctx, int32_t path);
 

@@ -968,13 +968,11 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     // Which kernel.  The vector kernel's instruction count per key grows with the heads of a group: from six heads
     // on it, not the memory, bounds a long range (eight heads: 4.3 TB/s against 6.4 for the matrix-core kernel,
     // whose cost does not depend on the group), and over short ranges it bounds the end of every launch.  The
-    // matrix-core kernel works on pairs of tiles, so it needs more than one tile per wavefront to pay, and it
-    // has no paged form.
+    // matrix-core kernel works on pairs of tiles, so it needs more than one tile per wavefront to pay.
     {
         const int group = c.n_q_heads / c.n_kv_heads;
         const bool pays = a.keys_per_block > 16 * 8 && (a.keys_per_block <= ltk::kWideBlockKeys || group >= 6);
         a.matrix_cores = ctx->decode_path == LT_DECODE_MATRIX || (ctx->decode_path == LT_DECODE_AUTO && pays) ? 1 : 0;
-        if (paged) a.matrix_cores = 0;
     }
     // Long ranges leave their last part to the shared tail (see DecodeArgs::tail_begin), which evens out the
     // workgroups' different speeds: an eighth of the keys when a workgroup's range has kMinKeysSharedTail keys or

@@ -775,8 +775,7 @@ __device__ __forceinline__ float sum_rows(float x)                 // sum of x o
 template <int G, int LAZY_TAG, int kWaves, int kMode>
 __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
 {
-    static_assert(kMode != kPagedMode, "paged layers use the other kernel");
-    constexpr bool kRagged = kMode != kUniform;
+    constexpr bool kRagged = kMode != kUniform, kPaged = kMode == kPagedMode;
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
     __shared__ __attribute__((aligned(16))) char sh_stage[kWaves][kMfmaWaveBytes];   // later: each wavefront's accumulators
@@ -803,6 +802,44 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
     const uint16_t *hot = a.q + ((int64_t)b * a.n_q_heads + g * G) * kHeadDim;
+    // paged cache: the pages of the range in registers, a tile's page by a cross-lane read (see lt_decode_kernel)
+    constexpr int kPageRegs = kPaged ? kMaxRangePages / 64 : 1;
+    int32_t range_pages[kPageRegs] = {};
+    int first_page = 0;
+    if constexpr (kPaged) {
+        first_page = begin_key >> r.page_shift;
+        const int last_page = max(end_key - 1, begin_key) >> r.page_shift;
+#pragma unroll
+        for (int i = 0; i < kPageRegs; ++i)
+            if (n_tiles > 0 && first_page + 64 * i <= last_page)          // uniform
+                range_pages[i] = r.block_table[(int64_t)b * r.max_pages + min(first_page + 64 * i + lane, last_page)];
+        kb = a.k_cache;
+        vb = a.v_cache;
+    }
+    auto tile_shift = [&](int key0) -> int64_t {
+        int64_t shift = 0;
+        if constexpr (kPaged) {
+            const int key = max(key0, begin_key);                   // key0 < 0: a fetch whose tile is never consumed
+            const int idx = (key >> r.page_shift) - first_page;     // uniform, below kMaxRangePages
+            int32_t page = __builtin_amdgcn_readlane(range_pages[0], idx & 63);
+#pragma unroll
+            for (int i = 1; i < kPageRegs; ++i)
+                if ((idx >> 6) == i) page = __builtin_amdgcn_readlane(range_pages[i], idx & 63);
+            const int64_t in_pool = (((int64_t)page * a.n_kv_heads + g) << r.page_shift) * kHeadDim;
+            shift = in_pool - (int64_t)((key >> r.page_shift) << r.page_shift) * kHeadDim;
+        }
+        return shift;
+    };
+    auto fetch = [&](Tile &t, int key0) __attribute__((always_inline)) {
+        const int64_t shift = tile_shift(key0);
+        load_tile(t, kb + shift, vb + shift, key0, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+    };
+    auto put_new_token = [&](const Tile &t, int key0) __attribute__((always_inline)) {
+        if (new_slot >= key0 && new_slot < key0 + 16) {             // wave-uniform, true for one tile of one workgroup
+            const int64_t shift = tile_shift(key0);
+            store_new_token(t, kb + shift, vb + shift, key0, sub, chunk, stored - 1, new_slot);
+        }
+    };
 
     // Q^T as the B operand: column `slot` is head g G + slot (zeros beyond the group), k-slice j of k-block kb is
     // dims 32 kb + 8 j .. + 7
@@ -819,8 +856,16 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
     const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
     const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)begin_key * kHeadDim)) >> 12);
     const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
-    const int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
-                                     : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+    int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
+                               : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+    if constexpr (kPaged) {                                         // as in lt_decode_kernel: spread inside a page, a pseudo-random page
+        const unsigned int page_tiles = 1u << (r.page_shift - 4);
+        const unsigned int among = gridDim.x * gridDim.z, mine = blockIdx.z * gridDim.x + blockIdx.x;
+        const unsigned int want = (unsigned int)(((uint64_t)mine * page_tiles) / among) & (page_tiles - 1);
+        const unsigned int in_page = (want - ((unsigned int)begin_key >> 4)) & (page_tiles - 1);
+        const unsigned int pages_here = ((unsigned int)wrap + page_tiles - 1) / page_tiles;
+        phase = (int)((in_page + (((linear_block * 2654435761u) >> 12) % pages_here) * page_tiles) % (unsigned int)wrap);
+    }
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     int next_tile = wave + phase, fetched = 0;
     while (next_tile >= wrap) next_tile -= wrap;
@@ -903,8 +948,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
     // One pair of tiles: new token into the cache, both tiles to LDS, the registers refilled with the next pair,
     // then the two products.
     auto work = [&](Tile &ta, Tile &tb, int &key_a, int &key_b, int after_a, int after_b) __attribute__((always_inline)) {
-        store_new_token(ta, kb, vb, key_a, sub, chunk, stored - 1, new_slot);
-        if (key_b >= 0) store_new_token(tb, kb, vb, key_b, sub, chunk, stored - 1, new_slot);
+        put_new_token(ta, key_a);
+        if (key_b >= 0) put_new_token(tb, key_b);
         float s[8];
         logits(ta, key_a, reinterpret_cast<float (&)[4]>(s[0]));
         logits(tb, key_b, reinterpret_cast<float (&)[4]>(s[4]));
@@ -914,8 +959,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
         // it was in LDS, half a pair earlier, was slower)
         key_a = after_a;
         key_b = after_b;
-        load_tile(ta, kb, vb, key_a, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
-        load_tile(tb, kb, vb, key_b, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+        fetch(ta, key_a);
+        fetch(tb, key_b);
 
         // online softmax of the head slot over the pair's 32 keys (8 per lane, the four lanes of a slot together)
         float tmax = s[0];
@@ -963,8 +1008,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
     Tile t0, t1;
     int key0 = advance(), key1 = advance();
     if (key0 < 0 && n_pieces > 0) piece_keys(claim_a, key0, key1);         // a wavefront without tiles of its own
-    load_tile(t0, kb, vb, key0, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
-    load_tile(t1, kb, vb, key1, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
+    fetch(t0, key0);
+    fetch(t1, key1);
     for (int k = 0; k < my_tiles; k += 2) {
         int after_a = advance(), after_b = advance();
         if (after_a < 0 && n_pieces > 0) piece_keys(claim_a, after_a, after_b);     // the last round
@@ -1006,7 +1051,7 @@ hipError_t launch_decode_as(const DecodeArgs &a, const typename ModeArgs<kMode>:
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
     // short ranges: eight wavefronts per workgroup; not for groups of eight heads, whose state needs more than
     // the 256 registers a wavefront has when two share a SIMD
-    if constexpr (kMode != kPagedMode) {
+    {
         if (a.matrix_cores) {
             // as in the vector kernel: eight wavefronts for short ranges, four for long ones
             if (a.keys_per_block <= kWideBlockKeys) hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);

@@ -11,7 +11,7 @@ import pytest
 pytestmark = pytest.mark.gpu
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 FILES = ["tests/test_gpu_decode.py", "tests/test_gpu_ragged.py", "tests/test_gpu_online.py", "tests/test_gpu_graph.py",
-         "tests/test_gpu_random.py", "tests/test_gpu_guards.py"]
+         "tests/test_gpu_random.py", "tests/test_gpu_guards.py", "tests/test_gpu_paged.py"]
 
 
 @pytest.mark.parametrize("path", ["matrix", "vector"])
