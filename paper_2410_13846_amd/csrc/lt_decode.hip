@@ -337,6 +337,75 @@ template <> struct ModeArgs<kPagedMode> { typedef PagedArgs type; };
 __device__ __forceinline__ const RaggedArgs &lengths_of(const RaggedArgs &r) { return r; }
 __device__ __forceinline__ const RaggedArgs &lengths_of(const PagedArgs &r) { return r.lengths; }
 
+// Paged cache: lane i of every wavefront holds the pages of the range's pages i, 64 + i, 128 + i, 192 + i; a 16-key
+// tile never straddles pages (their size is a multiple of 16), so a tile costs one cross-lane read of one of those
+// registers to find its page and no memory access.  shift() is the element offset that, added to the layer's pool,
+// makes "base + key * 128" land on the key inside its page.  For the other modes the struct is empty and shift() is 0.
+template <bool kPaged>
+struct RangePages {
+    static constexpr int kRegs = kPaged ? kMaxRangePages / 64 : 1;
+    int32_t pages[kRegs] = {};
+    int first_page = 0;
+
+    __device__ __forceinline__ void load(const PagedArgs &r, int b, int lane, int begin_key, int end_key, int n_tiles)
+    {
+        first_page = begin_key >> r.page_shift;
+        const int last_page = max(end_key - 1, begin_key) >> r.page_shift;
+#pragma unroll
+        for (int i = 0; i < kRegs; ++i)
+            if (n_tiles > 0 && first_page + 64 * i <= last_page)          // uniform
+                pages[i] = r.block_table[(int64_t)b * r.max_pages + min(first_page + 64 * i + lane, last_page)];
+    }
+    template <typename Other>
+    __device__ __forceinline__ void load(const Other &, int, int, int, int, int) {}
+
+    __device__ __forceinline__ int64_t shift(const PagedArgs &r, int key0, int begin_key, int n_kv_heads, int g) const
+    {
+        const int key = max(key0, begin_key);                       // key0 < 0: a fetch whose tile is never consumed
+        const int idx = (key >> r.page_shift) - first_page;         // uniform, below kMaxRangePages
+        int32_t page = __builtin_amdgcn_readlane(pages[0], idx & 63);
+#pragma unroll
+        for (int i = 1; i < kRegs; ++i)
+            if ((idx >> 6) == i) page = __builtin_amdgcn_readlane(pages[i], idx & 63);
+        const int64_t in_pool = (((int64_t)page * n_kv_heads + g) << r.page_shift) * kHeadDim;
+        return in_pool - (int64_t)((key >> r.page_shift) << r.page_shift) * kHeadDim;
+    }
+    template <typename Other>
+    __device__ __forceinline__ int64_t shift(const Other &, int, int, int, int) const { return 0; }
+};
+
+// The tile (0 .. wrap - 1) a workgroup starts at inside its range.  Workgroups run in lockstep, and their ranges
+// start at multiples of the same strides, so without care they all hit the same few memory channels at the same
+// moment (measured: 185 vs 162 us per launch depending on the cache capacity alone).  The order of keys does not
+// matter to the result, so each workgroup starts at a tile of its own and wraps around.  The start tiles are chosen
+// by absolute address (the memory channels are picked from the address bits): workgroup i of n starts where its
+// address is i * window / n modulo a window of spread_tiles 4 KB tiles, so the n address streams, which advance at
+// the same pace, stay evenly spread over that window (measured 5 % faster than pseudo-random starts, which remain
+// for ranges shorter than any useful window).  Paged layers: pages scatter the high address bits by themselves;
+// what the start tile still decides is the position inside a page -- the workgroups of one KV head (whose pages all
+// sit at the same offset inside a pool page) start evenly spread over the tiles of a page, at a pseudo-random page
+// of their range.
+__device__ __forceinline__ int start_tile(const DecodeArgs &a, const uint16_t *range_begin, int begin_key, int wrap, int page_shift)
+{
+    const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
+    if (page_shift > 0) {
+        const unsigned int page_tiles = 1u << (page_shift - 4);
+        const unsigned int among = gridDim.x * gridDim.z, mine = blockIdx.z * gridDim.x + blockIdx.x;
+        const unsigned int want = (unsigned int)(((uint64_t)mine * page_tiles) / among) & (page_tiles - 1);
+        const unsigned int in_page = (want - ((unsigned int)begin_key >> 4)) & (page_tiles - 1);
+        const unsigned int pages_here = ((unsigned int)wrap + page_tiles - 1) / page_tiles;
+        return (int)((in_page + (((linear_block * 2654435761u) >> 12) % pages_here) * page_tiles) % (unsigned int)wrap);
+    }
+    const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
+    const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)range_begin) >> 12);
+    const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
+    return a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
+                          : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
+}
+__device__ __forceinline__ int page_shift_of(const PagedArgs &r) { return r.page_shift; }
+template <typename Other>
+__device__ __forceinline__ int page_shift_of(const Other &) { return 0; }
+
 // What every workgroup does after its wavefronts have put their partial results (running max in log2 units, sum,
 // un-normalised accumulator) into LDS and passed a barrier: merge the wavefronts, publish the split's partial result,
 // and -- in the workgroup that takes the last ticket of its (sequence, KV head) -- merge the splits.  n_pieces > 0:
@@ -517,35 +586,9 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
     const uint16_t *hot = a.q + ((int64_t)b * a.n_q_heads + g * G) * kHeadDim;
-    // Paged cache: lane i of every wavefront holds the pages of the range's pages i, 64 + i, 128 + i, 192 + i;
-    // a 16-key tile never straddles pages (their size is a multiple of 16), so a tile costs one cross-lane
-    // read of one of those registers to find its page and no memory access.  tile_shift is the element offset
-    // that, added to the layer's pool, makes "base + key * 128" land on the key inside its page.
-    constexpr int kPageRegs = kPaged ? kMaxRangePages / 64 : 1;
-    int32_t range_pages[kPageRegs] = {};
-    int first_page = 0;
-    if constexpr (kPaged) {
-        first_page = begin_key >> r.page_shift;
-        const int last_page = max(end_key - 1, begin_key) >> r.page_shift;
-#pragma unroll
-        for (int i = 0; i < kPageRegs; ++i)
-            if (n_tiles > 0 && first_page + 64 * i <= last_page)          // uniform
-                range_pages[i] = r.block_table[(int64_t)b * r.max_pages + min(first_page + 64 * i + lane, last_page)];
-    }
-    auto tile_shift = [&](int key0) -> int64_t {
-        int64_t shift = 0;
-        if constexpr (kPaged) {
-            const int key = max(key0, begin_key);                   // key0 < 0: a fetch whose tile is never consumed
-            const int idx = (key >> r.page_shift) - first_page;     // uniform, below kMaxRangePages
-            int32_t page = __builtin_amdgcn_readlane(range_pages[0], idx & 63);
-#pragma unroll
-            for (int i = 1; i < kPageRegs; ++i)
-                if ((idx >> 6) == i) page = __builtin_amdgcn_readlane(range_pages[i], idx & 63);
-            const int64_t in_pool = (((int64_t)page * a.n_kv_heads + g) << r.page_shift) * kHeadDim;
-            shift = in_pool - (int64_t)((key >> r.page_shift) << r.page_shift) * kHeadDim;
-        }
-        return shift;
-    };
+    RangePages<kPaged> range_pages;
+    range_pages.load(r, b, lane, begin_key, end_key, n_tiles);
+    auto tile_shift = [&](int key0) -> int64_t { return range_pages.shift(r, key0, begin_key, a.n_kv_heads, g); };
     if constexpr (kPaged) { kb = a.k_cache; vb = a.v_cache; }
     // `limit` is the end of the keys a tile may hold: the end of the workgroup's range, or `stored` in the shared tail
     auto fetch = [&](Tile &t, int key0, int limit) __attribute__((always_inline)) {
@@ -589,32 +632,8 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
     // its last tile a wavefront re-fetches tiles it never consumes): with a fixed number of loads
     // between a fetch and its use the wait counts are exact, and a tile is consumed while the
     // following one is still arriving.
-    // Workgroups run in lockstep, and their ranges start at multiples of the same strides, so
-    // without care they all hit the same few memory channels at the same moment (measured: 185
-    // vs 162 us per launch depending on the cache capacity alone).  The order of keys does not
-    // matter to the result, so each workgroup starts at a tile of its own inside its range and
-    // wraps around.  The start tiles are chosen by absolute address (the memory channels are
-    // picked from the address bits): workgroup i of n starts where its address is i * window / n
-    // modulo a window of spread_tiles 4 KB tiles, so the n address streams, which advance at the
-    // same pace, stay evenly spread over that window (measured 5 % faster than pseudo-random
-    // starts, which remain for ranges shorter than any useful window).
-    const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
-    const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)begin_key * kHeadDim)) >> 12);
-    const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
-    int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
-                               : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
-    if constexpr (kPaged) {
-        // Pages scatter the high address bits by themselves; what the start tile still decides is the position
-        // inside a page.  The workgroups of one KV head (whose pages all sit at the same offset inside a pool
-        // page) start evenly spread over the tiles of a page, at a pseudo-random page of their range.
-        const unsigned int page_tiles = 1u << (r.page_shift - 4);
-        const unsigned int among = gridDim.x * gridDim.z, mine = blockIdx.z * gridDim.x + blockIdx.x;
-        const unsigned int want = (unsigned int)(((uint64_t)mine * page_tiles) / among) & (page_tiles - 1);
-        const unsigned int in_page = (want - ((unsigned int)begin_key >> 4)) & (page_tiles - 1);
-        const unsigned int pages_here = ((unsigned int)wrap + page_tiles - 1) / page_tiles;
-        phase = (int)((in_page + (((linear_block * 2654435761u) >> 12) % pages_here) * page_tiles) % (unsigned int)wrap);
-    }
+    // each workgroup starts at a tile of its own inside its range and wraps around (start_tile)
+    const int phase = start_tile(a, kb + (int64_t)begin_key * kHeadDim, begin_key, wrap, page_shift_of(r));
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     int next_tile = wave + phase, fetched = 0;
     while (next_tile >= wrap) next_tile -= wrap;
@@ -802,34 +821,13 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
     const uint16_t *k_new = a.k_new + new_off;
     const uint16_t *v_new = a.v_new + new_off;
     const uint16_t *hot = a.q + ((int64_t)b * a.n_q_heads + g * G) * kHeadDim;
-    // paged cache: the pages of the range in registers, a tile's page by a cross-lane read (see lt_decode_kernel)
-    constexpr int kPageRegs = kPaged ? kMaxRangePages / 64 : 1;
-    int32_t range_pages[kPageRegs] = {};
-    int first_page = 0;
+    RangePages<kPaged> range_pages;                              // paged cache: see RangePages
+    range_pages.load(r, b, lane, begin_key, end_key, n_tiles);
     if constexpr (kPaged) {
-        first_page = begin_key >> r.page_shift;
-        const int last_page = max(end_key - 1, begin_key) >> r.page_shift;
-#pragma unroll
-        for (int i = 0; i < kPageRegs; ++i)
-            if (n_tiles > 0 && first_page + 64 * i <= last_page)          // uniform
-                range_pages[i] = r.block_table[(int64_t)b * r.max_pages + min(first_page + 64 * i + lane, last_page)];
         kb = a.k_cache;
         vb = a.v_cache;
     }
-    auto tile_shift = [&](int key0) -> int64_t {
-        int64_t shift = 0;
-        if constexpr (kPaged) {
-            const int key = max(key0, begin_key);                   // key0 < 0: a fetch whose tile is never consumed
-            const int idx = (key >> r.page_shift) - first_page;     // uniform, below kMaxRangePages
-            int32_t page = __builtin_amdgcn_readlane(range_pages[0], idx & 63);
-#pragma unroll
-            for (int i = 1; i < kPageRegs; ++i)
-                if ((idx >> 6) == i) page = __builtin_amdgcn_readlane(range_pages[i], idx & 63);
-            const int64_t in_pool = (((int64_t)page * a.n_kv_heads + g) << r.page_shift) * kHeadDim;
-            shift = in_pool - (int64_t)((key >> r.page_shift) << r.page_shift) * kHeadDim;
-        }
-        return shift;
-    };
+    auto tile_shift = [&](int key0) -> int64_t { return range_pages.shift(r, key0, begin_key, a.n_kv_heads, g); };
     auto fetch = [&](Tile &t, int key0) __attribute__((always_inline)) {
         const int64_t shift = tile_shift(key0);
         load_tile(t, kb + shift, vb + shift, key0, sub, chunk, stored - 1, new_slot, k_new, v_new, hot);
@@ -851,21 +849,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_mfma_kernel(DecodeArgs 
         qb[kq] = __builtin_bit_cast(bf16x8_t, u);
     }
 
-    // start tiles as in lt_decode_kernel: spread over the memory channels, wrapping inside the range
-    const unsigned int linear_block = (blockIdx.z * gridDim.y + blockIdx.y) * gridDim.x + blockIdx.x;
-    const unsigned int n_blocks = gridDim.x * gridDim.y * gridDim.z;
-    const unsigned int first_tile_addr = (unsigned int)(((uintptr_t)(kb + (int64_t)begin_key * kHeadDim)) >> 12);
-    const unsigned int target = (unsigned int)(((uint64_t)linear_block * a.spread_tiles) / n_blocks);
-    int phase = a.spread_tiles ? (int)(((target - first_tile_addr) & (a.spread_tiles - 1)) % (unsigned int)wrap)
-                               : (int)(((linear_block * 2654435761u) >> 12) % (unsigned int)wrap);
-    if constexpr (kPaged) {                                         // as in lt_decode_kernel: spread inside a page, a pseudo-random page
-        const unsigned int page_tiles = 1u << (r.page_shift - 4);
-        const unsigned int among = gridDim.x * gridDim.z, mine = blockIdx.z * gridDim.x + blockIdx.x;
-        const unsigned int want = (unsigned int)(((uint64_t)mine * page_tiles) / among) & (page_tiles - 1);
-        const unsigned int in_page = (want - ((unsigned int)begin_key >> 4)) & (page_tiles - 1);
-        const unsigned int pages_here = ((unsigned int)wrap + page_tiles - 1) / page_tiles;
-        phase = (int)((in_page + (((linear_block * 2654435761u) >> 12) % pages_here) * page_tiles) % (unsigned int)wrap);
-    }
+    const int phase = start_tile(a, kb + (int64_t)begin_key * kHeadDim, begin_key, wrap, page_shift_of(r));
     const int my_tiles = wave < n_tiles ? (n_tiles - wave + kWaves - 1) / kWaves : 0;
     int next_tile = wave + phase, fetched = 0;
     while (next_tile >= wrap) next_tile -= wrap;
