@@ -658,8 +658,9 @@ def decode_bench(args, lt, W, wl, dev, K, Wm, want_cpu, want_speedup, want_profi
         avg_ms = total_ms / max(launches, 1)
         achieved = launch_bytes / avg_ms / 1e6
         roofline = {
-            "bound": "hbm", "kernel": "lt_decode_kernel<%d, 0, *> (full layers)" % wl.group if kernel == lt.KERNEL_DECODE_FULL
-            else "lt_decode_kernel<%d, 1, *> (lazy layers)" % wl.group,
+            # long ranges of groups of six heads or more run on the matrix-core kernel (see lt_set_decode_path)
+            "bound": "hbm", "kernel": "%s<%d, 0, *> (full layers)" % ("lt_decode_mfma_kernel" if wl.group >= 6 else "lt_decode_kernel", wl.group)
+            if kernel == lt.KERNEL_DECODE_FULL else "lt_decode_kernel<%d, 1, *> (lazy layers)" % wl.group,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": read_traffic(wl.name), "launches": launches, "avg_launch_us": avg_ms * 1e3,
             "bytes_per_launch": launch_bytes, "ms_per_step_with_events": elapsed_p / K * 1e3, "kernels": per_kernel,
