@@ -42,6 +42,10 @@ def parse_args():
     ap.add_argument("--n-lazy", type=int, default=None, help="override the number of lazy layers")
     ap.add_argument("--keys-full", type=int, default=0, help="keys per workgroup in full layers (0 = built-in)")
     ap.add_argument("--keys-lazy", type=int, default=0)
+    ap.add_argument("--q-heads", type=int, default=None,
+                    help="override the number of query heads (heads per KV head = this / the workload's KV heads, up to 8)")
+    ap.add_argument("--decode-path", choices=("auto", "vector", "matrix"), default="auto",
+                    help="force one of the two decode kernels (lt_set_decode_path)")
     ap.add_argument("--no-shared-tail", action="store_true",
                     help="every key in a fixed place (lt_set_shared_tail off): bit-reproducible outputs, for comparison")
     ap.add_argument("--no-speedup", action="store_true", help="skip the all-full comparison run")
@@ -84,6 +88,7 @@ class Stack:
     """A hybrid stack with its decode inputs pre-generated on the device."""
 
     shared_tail = True                  # --no-shared-tail clears it for every stack of the run
+    decode_path = 0                     # --decode-path: lt.DECODE_VECTOR / lt.DECODE_MATRIX for every stack of the run
 
     def __init__(self, lt, W, wl, is_lazy, total_steps, dev, keys_full=0, keys_lazy=0, online=False, page_tokens=0,
                  shuffled=True):
@@ -137,6 +142,8 @@ class Stack:
             self.ctx.set_split(keys_full, keys_lazy)
         if not Stack.shared_tail:
             self.ctx.set_shared_tail(False)
+        if Stack.decode_path:
+            self.ctx.set_decode_path(Stack.decode_path)
         self.q, self.k, self.v = [], [], []
         for layer in range(wl.n_layers):
             q, k, v = W.decode_qkv_block(wl, layer, 0, total_steps, dev)
@@ -741,6 +748,7 @@ def main():
     from paper_2410_13846_amd import lt
 
     Stack.shared_tail = not args.no_shared_tail
+    Stack.decode_path = {"auto": lt.DECODE_AUTO, "vector": lt.DECODE_VECTOR, "matrix": lt.DECODE_MATRIX}[args.decode_path]
 
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
@@ -753,6 +761,8 @@ def main():
         wl = wl.scaled(n_lazy=args.n_lazy)
     if args.context is not None:
         wl = wl.scaled(context=args.context)
+    if args.q_heads is not None:
+        wl = wl.scaled(n_q_heads=args.q_heads)
     K, Wm = args.steps, args.warmup
 
     if args.calibrate_copy:
