@@ -6,6 +6,12 @@
 // lazy layer's ring is read as a plain array of `stored` entries and both layer kinds share
 // one kernel.  One workgroup streams a contiguous range of keys of one (sequence, KV head)
 // once from HBM and applies it to all G query heads of that KV head.
+//
+// Two kernels do this: lt_decode_kernel forms q.k and p.v with vector instructions (the fastest over
+// long ranges while a group has at most five heads), lt_decode_mfma_kernel with the matrix cores (short
+// ranges, where the vector instructions are what ends a launch, and larger groups, where they fall
+// behind the memory).  They load tiles the same way and share everything after the loop over the keys
+// (finish_workgroup); the C-ABI layer picks one per launch.
 #include "lt_kernels.h"
 
 #include <type_traits>
