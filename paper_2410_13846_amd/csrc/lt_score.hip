@@ -153,7 +153,7 @@ constexpr int kScoreWaves = kScoreThreads / 64;
 // loads count in vmcnt like any other).  No other instruction of these kernels uses M0.
 __device__ __forceinline__ void load_to_lds(const void *src, uint32_t lds_base)
 {
-    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off" : : "v"(src), "s"(lds_base) : "memory");
+    asm volatile("s_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, off nt" : : "v"(src), "s"(lds_base) : "memory");
 }
 __device__ __forceinline__ uint32_t lds_address(const void *p)
 {
