@@ -52,6 +52,7 @@ __device__ __forceinline__ u32x4_t load16(const uint16_t *p) { return *(global_q
 __device__ __forceinline__ u32x4_t load16_stream(const uint16_t *p) { return __builtin_nontemporal_load((global_quad_ptr)p); }
 
 __device__ __forceinline__ void store16(uint16_t *p, u32x4_t v) { *(global_quad_wptr)p = v; }
+__device__ __forceinline__ void store16_stream(uint16_t *p, u32x4_t v) { __builtin_nontemporal_store(v, (global_quad_wptr)p); }
 
 // Device-scope relaxed atomic store / load: coherent between workgroups anywhere on the chip
 // without flushing or invalidating a cache.
@@ -86,8 +87,9 @@ __global__ __launch_bounds__(256) void lt_append_kv_kernel(AppendArgs a)
         const int64_t page = a.block_table[(int64_t)b * a.max_pages + (slot >> a.page_shift)];
         dst = (((page * a.n_kv_heads + g) << a.page_shift) + (slot & ((1 << a.page_shift) - 1))) * kHeadDim + c * 8;
     }
-    store16(a.k_cache + dst, load16(a.k_new + src));
-    store16(a.v_cache + dst, load16(a.v_new + src));
+    // a prompt's K/V pass through once: streamed in and out
+    store16_stream(a.k_cache + dst, load16_stream(a.k_new + src));
+    store16_stream(a.v_cache + dst, load16_stream(a.v_new + src));
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -110,8 +112,8 @@ __global__ __launch_bounds__(256) void lt_truncate_kernel(TruncateArgs a)
     const int64_t slot = p < a.w_sink ? p : a.w_sink + (p - a.w_sink) % a.w_recent;
     const int64_t src = (int64_t)b * a.stride_b_full + (int64_t)g * a.stride_h_full + p * kHeadDim + c * 8;
     const int64_t dst = (int64_t)b * a.stride_b_ring + (int64_t)g * a.stride_h_ring + slot * kHeadDim + c * 8;
-    store16(a.k_ring + dst, load16(a.k_full + src));
-    store16(a.v_ring + dst, load16(a.v_full + src));
+    store16_stream(a.k_ring + dst, load16_stream(a.k_full + src));
+    store16_stream(a.v_ring + dst, load16_stream(a.v_full + src));
 }
 
 // ---------------------------------------------------------------------------------------------
