@@ -664,10 +664,13 @@ def decode_bench(args, lt, W, wl, dev, K, Wm, want_cpu, want_speedup, want_profi
         launch_bytes = wl.batch * per_seq
         avg_ms = total_ms / max(launches, 1)
         achieved = launch_bytes / avg_ms / 1e6
+        # which of the two decode kernels the timed layers ran on (lt_set_decode_path gives the rule), and how
+        timed_lazy = 0 if kernel == lt.KERNEL_DECODE_FULL else 1
+        plan = stack.ctx.decode_plan(list(stack.is_lazy).index(timed_lazy))
         roofline = {
-            # long ranges of groups of six heads or more run on the matrix-core kernel (see lt_set_decode_path)
-            "bound": "hbm", "kernel": "%s<%d, 0, *> (full layers)" % ("lt_decode_mfma_kernel" if wl.group >= 6 else "lt_decode_kernel", wl.group)
-            if kernel == lt.KERNEL_DECODE_FULL else "lt_decode_kernel<%d, 1, *> (lazy layers)" % wl.group,
+            "bound": "hbm", "kernel": "%s<%d, %d, *> (%s layers)" % ("lt_decode_mfma_kernel" if plan["matrix_cores"] else "lt_decode_kernel",
+                                                                     wl.group, timed_lazy, "lazy" if timed_lazy else "full"),
+            "plan": plan,
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
             "traffic": read_traffic(wl.name), "launches": launches, "avg_launch_us": avg_ms * 1e3,
             "bytes_per_launch": launch_bytes, "ms_per_step_with_events": elapsed_p / K * 1e3, "kernels": per_kernel,

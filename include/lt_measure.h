@@ -38,6 +38,14 @@ lt_status lt_set_shared_tail(lt_ctx *ctx, int32_t on);
 enum { LT_DECODE_AUTO = 0, LT_DECODE_VECTOR = 1, LT_DECODE_MATRIX = 2 };
 lt_status lt_set_decode_path(lt_ctx *ctx, int32_t path);
 
+/* How the layer's most recent decode launch (lt_decode_attn, lt_decode_step, lt_decode_step_active) was laid out:
+ *   plan_host   host, 4 x int32, written: [0] keys per workgroup range, [1] ranges per (sequence, KV head),
+ *               [2] first key of the shared tail or -1 without one (lt_set_shared_tail), [3] 1 if the matrix-core
+ *               kernel ran, 0 for the vector kernel (lt_set_decode_path)
+ * For benchmarks and tests that have to name the kernel they timed.  LT_ERR_INVALID_ARG for a bad handle, layer or
+ * pointer, and for a layer that no decode call has run on yet; nothing is written then. */
+lt_status lt_decode_plan_read(lt_ctx *ctx, int32_t layer, int32_t *plan_host);
+
 /* Measurement aid: one launch that reads `bytes` of `buf_dev` (rounded down to a multiple of
  * 16 KiB, and at least that) once, with the same kind of loads the decode kernel uses, and discards
  * them; timed by the caller, it gives the read rate this device sustains, the practical ceiling of

@@ -70,6 +70,9 @@ WORKLOADS = {
     # 128K context, Llama-3.1-8B-shaped
     "llama31_8b_128k_b1": Workload("llama31_8b_128k_b1", 4, 32, 1, 32, 8, 128, 131072, 4, 4092, 16, 32, bias="planted"),
     "llama31_8b_128k_b16": Workload("llama31_8b_128k_b16", 4, 32, 16, 32, 8, 128, 131072, 4, 4092, 16, 32, bias="planted"),
+    # a group of eight query heads per KV head (Llama-3-70B-shaped attention): not one of the benchmark's
+    # configurations, but the shape where the decode kernels differ most
+    "llama3_70b_32k": Workload("llama3_70b_32k", 5, 80, 4, 64, 8, 128, 32768, 4, 2044, 40, 64, bias="planted"),
 }
 
 

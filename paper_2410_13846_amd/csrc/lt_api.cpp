@@ -83,6 +83,7 @@ struct Layer {
     std::vector<int64_t> total_b;               // ragged batches: tokens of every sequence; empty while all are equal
     bool lazy = false;
     int32_t slot = -1;                          // online mode: index of the full / ring slot in use, -1 = none yet
+    int32_t plan[4] = {0, 0, -1, 0};            // most recent decode launch (lt_decode_plan_read); plan[1] = 0: none yet
 };
 
 struct EventPair {
@@ -976,15 +977,20 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     }
     // Long ranges leave their last part to the shared tail (see DecodeArgs::tail_begin), which evens out the
     // workgroups' different speeds: an eighth of the keys when a workgroup's range has kMinKeysSharedTail keys or
-    // more; a quarter when it has half of that and a (sequence, KV head) is spread over at least kMinSplitsWideTail
+    // more; with half of that, a quarter when a (sequence, KV head) is spread over at least kMinSplitsWideTail
     // workgroups (128K x batch 1: the many wavefronts of a pair hold two claimed pieces each at the end, so the tail
-    // has to be longer to leave something to hand out; with fewer workgroups per pair such ranges lost time,
-    // measured).  Shorter ranges, paged layers and forced splits keep every key in a fixed place.
+    // has to be longer to leave something to hand out), and an eighth when it is spread over half as many and a
+    // piece is cheap to work through (the matrix-core kernel, or the vector kernel with at most four heads per
+    // group: 32K x batch 4 gains 2-3 % either way, where five heads per group lost 1.6 %, measured).  Shorter
+    // ranges, paged layers and forced splits keep every key in a fixed place.
     const bool long_ranges = a.keys_per_block >= kMinKeysSharedTail;
-    const bool many_ranges = a.keys_per_block >= kMinKeysSharedTail / 2 && a.n_splits >= kMinSplitsWideTail;
-    if (ctx->shared_tail && forced <= 0 && !paged && a.n_splits > 1 && (long_ranges || many_ranges)) {
+    const bool half_ranges = a.keys_per_block >= kMinKeysSharedTail / 2;
+    const bool many_ranges = half_ranges && a.n_splits >= kMinSplitsWideTail;
+    const bool cheap_pieces = a.matrix_cores || c.n_q_heads / c.n_kv_heads <= 4;
+    const bool some_ranges = half_ranges && a.n_splits >= kMinSplitsWideTail / 2 && cheap_pieces;
+    if (ctx->shared_tail && forced <= 0 && !paged && a.n_splits > 1 && (long_ranges || many_ranges || some_ranges)) {
         const int64_t streams = (int64_t)c.batch * c.n_kv_heads;
-        const int64_t begin = (stored - stored / (long_ranges ? 8 : 4)) / ltk::kKeyGranule * ltk::kKeyGranule;
+        const int64_t begin = (stored - stored / (many_ranges && !long_ranges ? 4 : 8)) / ltk::kKeyGranule * ltk::kKeyGranule;
         const int32_t keys = choose_keys_per_block(begin, streams, l.lazy, ctx->splits_cap);
         if (ceil_div(begin, keys) > 1) {
             a.tail_begin = (int32_t)begin;
@@ -1025,6 +1031,10 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
         }
         if (ltk::decode(a, ragged && !paged ? &per_seq : nullptr, paged ? &paged_args : nullptr, s) != hipSuccess) return LT_ERR_HIP;
     }
+    l.plan[0] = a.keys_per_block;
+    l.plan[1] = a.n_splits;
+    l.plan[2] = a.tail_begin == INT32_MAX ? -1 : a.tail_begin;
+    l.plan[3] = a.matrix_cores;
     if (ragged) {
         if (fused)
             for (int b = 0; b < c.batch; ++b) l.total_b[b] += takes_part(b) ? 1 : 0;
@@ -1154,6 +1164,15 @@ lt_status lt_set_decode_path(lt_ctx *ctx, int32_t path)
 {
     if (ctx == nullptr || (path != LT_DECODE_AUTO && path != LT_DECODE_VECTOR && path != LT_DECODE_MATRIX)) return LT_ERR_INVALID_ARG;
     ctx->decode_path = path;
+    return LT_OK;
+}
+
+lt_status lt_decode_plan_read(lt_ctx *ctx, int32_t layer, int32_t *plan_host)
+{
+    if (ctx == nullptr || plan_host == nullptr || layer < 0 || layer >= ctx->cfg.n_layers) return LT_ERR_INVALID_ARG;
+    const Layer &l = ctx->layers[layer];
+    if (l.plan[1] == 0) return LT_ERR_INVALID_ARG;
+    std::copy(l.plan, l.plan + 4, plan_host);
     return LT_OK;
 }
 

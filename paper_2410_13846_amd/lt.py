@@ -22,7 +22,7 @@ DECODE_AUTO, DECODE_VECTOR, DECODE_MATRIX = 0, 1, 2
 EXPORTS = [
     "lt_kv_bytes", "lt_workspace_bytes", "lt_create", "lt_destroy", "lt_reset", "lt_layer_len", "lt_layer_view",
     "lt_lazy_ratio_workspace_bytes", "lt_lazy_ratio", "lt_select_lazy", "lt_append_kv", "lt_decode_attn", "lt_decode_step",
-    "lt_set_split", "lt_set_shared_tail", "lt_set_decode_path", "lt_profile_enable", "lt_profile_read", "lt_status_str",
+    "lt_set_split", "lt_set_shared_tail", "lt_set_decode_path", "lt_decode_plan_read", "lt_profile_enable", "lt_profile_read", "lt_status_str",
     "lt_queue_create", "lt_queue_destroy", "lt_select_push", "lt_kv_bytes_online", "lt_create_online", "lt_truncate_layer",
     "lt_lazy_ratio_lse_workspace_bytes", "lt_lazy_ratio_lse", "lt_prefill_attn", "lt_preselect_lazy",
     "lt_append_kv_ragged", "lt_seq_len", "lt_set_output_dtype", "lt_probe_read",
@@ -113,6 +113,8 @@ def load() -> ctypes.CDLL:
     lib.lt_set_shared_tail.restype = ctypes.c_int
     lib.lt_set_decode_path.argtypes = [vp, i32]
     lib.lt_set_decode_path.restype = ctypes.c_int
+    lib.lt_decode_plan_read.argtypes = [vp, i32, ctypes.POINTER(ctypes.c_int32)]
+    lib.lt_decode_plan_read.restype = ctypes.c_int
     lib.lt_profile_enable.argtypes = [vp, i32]
     lib.lt_profile_enable.restype = ctypes.c_int
     lib.lt_profile_read.argtypes = [vp, i32, ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_double)]
@@ -591,6 +593,13 @@ class Context:
     def set_decode_path(self, path: int = 0):
         """DECODE_AUTO, DECODE_VECTOR or DECODE_MATRIX."""
         _check(load().lt_set_decode_path(self._h, int(path)), "lt_set_decode_path")
+
+    def decode_plan(self, layer: int) -> dict:
+        """Layout of the layer's most recent decode launch: keys_per_block, n_splits, tail_begin (-1 = no shared
+        tail), matrix_cores."""
+        plan = (ctypes.c_int32 * 4)()
+        _check(load().lt_decode_plan_read(self._h, int(layer), plan), "lt_decode_plan_read")
+        return {"keys_per_block": plan[0], "n_splits": plan[1], "tail_begin": plan[2], "matrix_cores": bool(plan[3])}
 
     def set_shared_tail(self, on: bool = True):
         _check(load().lt_set_shared_tail(self._h, 1 if on else 0), "lt_set_shared_tail")

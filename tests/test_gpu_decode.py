@@ -105,6 +105,41 @@ def test_shared_tail_switched_off_gives_the_same_bits_every_time():
     ctx.close()
 
 
+def test_decode_plan_names_the_kernel_and_the_ranges_of_the_last_launch():
+    import os
+    forced = os.environ.get("LT_DECODE_PATH", "auto")        # the forced-kernel runs of this file set it
+    # (batch, query heads, keys) -> matrix-core kernel by the library's own rule, shared tail
+    cases = [((4, 64, 32768), True, True),                    # eight heads per group: long ranges too, an eighth shared
+             ((4, 32, 32768), False, True),                   # four heads per group, ranges of 4096 keys: vector kernel
+             ((8, 32, 4000), True, False),                    # ranges of at most 2048 keys
+             ((1, 8, 100), True, False)]                      # the smallest range the library chooses has 256 keys
+    for (B, Hq, n), matrix, tail in cases:
+        Hkv = 8 if Hq >= 32 else 2
+        cfg = lt.make_config(1, B, Hq, Hkv, 128, 4, 1020, n + 8)
+        ctx = lt.Context(cfg, [0], DEV)
+        with pytest.raises(lt.LtError):
+            ctx.decode_plan(0)                                # nothing launched yet
+        ctx.append_kv(0, randn_bf16((B, Hkv, n, 128), 491), randn_bf16((B, Hkv, n, 128), 492))
+        say("decode plan", (B, Hq, n), forced)
+        ctx.decode_attn(0, randn_bf16((B, Hq, 128), 493))
+        plan = ctx.decode_plan(0)
+        assert plan["matrix_cores"] == {"auto": matrix, "matrix": True, "vector": False}[forced], plan
+        if Hq == 64 and forced == "vector":
+            tail = False                                      # ranges of 4096 keys share a tail only where a piece is cheap
+        assert (plan["tail_begin"] >= 0) == tail, plan
+        covered = plan["tail_begin"] if tail else n
+        assert (plan["n_splits"] - 1) * plan["keys_per_block"] < covered <= plan["n_splits"] * plan["keys_per_block"], plan
+        ctx.set_split(512, 512)
+        ctx.decode_attn(0, randn_bf16((B, Hq, 128), 494))
+        plan = ctx.decode_plan(0)
+        assert plan["keys_per_block"] == 512 and plan["n_splits"] == -(-n // 512) and plan["tail_begin"] == -1, plan
+        if n <= 128:                                          # a single tile per wavefront: the vector kernel
+            ctx.set_split(128, 128)
+            ctx.decode_attn(0, randn_bf16((B, Hq, 128), 495))
+            assert ctx.decode_plan(0)["matrix_cores"] == (forced == "matrix")
+        ctx.close()
+
+
 @pytest.mark.parametrize("split", [(256, 64), (512, 128), (2048, 2048)])
 def test_result_does_not_depend_on_the_split(split):
     run_case(B=1, Hq=8, Hkv=2, n_prefill=3000, steps=2, w_sink=4, w_recent=1020, seed=500, split=split)

@@ -147,6 +147,17 @@ def test_llama3_8b_32k_shapes_sampled():
                 score_samples=[(0, 2, 1), (1, 6, 7)])
 
 
+def test_llama3_70b_32k_shapes_sampled():
+    """Batch 4, 64/8 heads (eight query heads per KV head: the matrix-core decode kernel on the full layers too, the
+    scoring kernel's sixteen-tile form), context 32768, 4 + 2044 window."""
+    wl = W.WORKLOADS["llama3_70b_32k"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layers = [l for l in range(wl.n_layers) if l not in lazy_layers]
+    layers = [full_layers[0], lazy_layers[0], full_layers[-1], lazy_layers[-1]]
+    run_sampled(wl, layers, [0, 1, 0, 1], samples=[(0, 0), (1, 3), (2, 2), (3, 1)], steps=3,
+                score_samples=[(0, 2, 1), (1, 3, 7)])
+
+
 def test_llama3_8b_32k_paged_shapes_sampled():
     """The same shape with the full layers in pages of 256 tokens handed out in a random order (bench.py --paged 256)."""
     wl = W.WORKLOADS["llama3_8b_32k"]

@@ -343,6 +343,28 @@ def test_shared_tail_only_for_long_ranges_and_can_be_switched_off():
     assert c.step(0) == lt.OK and last_decode(lib)["tail_begin"] != NO_TAIL
     assert lib.lt_set_shared_tail(None, 1) == lt.ERR_INVALID_ARG
     c.close()
+    # eight ranges of 4096 keys per (sequence, KV head): an eighth is shared when a piece is cheap to work through
+    # (four heads per group, or the matrix-core kernel that takes eight heads per group), not with five heads per group
+    for q_heads, shares in ((32, True), (64, True), (40, False)):
+        cfg = lt.make_config(1, 4, q_heads, 8, 128, 4, 2044, 40000)
+        c = Ctx(lib, cfg, [0])
+        assert c.append(0, 32768) == lt.OK and c.step(0) == lt.OK
+        d = last_decode(lib)
+        assert d["tail_begin"] == ((32769 - 32769 // 8) // 64 * 64 if shares else NO_TAIL), (q_heads, d)
+        assert d["n_splits"] == 8 and d["n_splits"] * d["keys_per_block"] >= (d["tail_begin"] if shares else 32769)
+        assert (d["n_splits"] - 1) * d["keys_per_block"] < (d["tail_begin"] if shares else 32769)
+        plan = (ctypes.c_int32 * 4)()
+        assert lib.lt_decode_plan_read(c.h, 0, plan) == lt.OK
+        assert list(plan) == [d["keys_per_block"], 8, d["tail_begin"] if shares else -1, 1 if q_heads == 64 else 0]
+        assert lib.lt_decode_plan_read(c.h, 1, plan) == lt.ERR_INVALID_ARG and lib.lt_decode_plan_read(c.h, 0, None) == lt.ERR_INVALID_ARG
+        c.close()
+    cfg = lt.make_config(2, 1, 8, 2, 128, 4, 60, 500)
+    c = Ctx(lib, cfg, [0, 1])
+    assert c.append(1, 100) == lt.OK and c.step(1) == lt.OK
+    plan = (ctypes.c_int32 * 4)(7, 7, 7, 7)
+    assert lib.lt_decode_plan_read(c.h, 0, plan) == lt.ERR_INVALID_ARG and list(plan) == [7, 7, 7, 7]     # layer 0 has not run
+    assert lib.lt_decode_plan_read(c.h, 1, plan) == lt.OK and plan[1] >= 1 and plan[2] == -1
+    c.close()
     # one workgroup per (sequence, KV head): nothing to share a tail between
     cfg = lt.make_config(1, 32, 32, 8, 128, 4, 2044, 17000)
     c = Ctx(lib, cfg, [0])
