@@ -19,9 +19,11 @@ extern "C" {
  * 0 keeps the built-in choice.  LT_ERR_CAPACITY if the workspace cannot hold the resulting splits. */
 lt_status lt_set_split(lt_ctx *ctx, int32_t keys_per_block_full, int32_t keys_per_block_lazy);
 
-/* Decode launches whose workgroups each stream 8192 keys or more (4096 or more when a (sequence,
- * KV head) is spread over at least 16 workgroups) leave the last eighth (quarter) of every
- * (sequence, KV head) to whichever wavefronts finish their own range first (on by default): the
+/* Decode launches whose workgroups each stream 8192 keys or more leave the last eighth of every
+ * (sequence, KV head) to whichever wavefronts finish their own range first (on by default); with
+ * 4096 keys or more it is the last quarter when a (sequence, KV head) is spread over at least 16
+ * workgroups, and the last eighth when it is spread over at least 8 and the launch runs on the
+ * matrix-core kernel or has at most four query heads per KV head.  The reason: the
  * compute units do not all read memory equally fast, and a launch ends with its slowest
  * workgroup.  Which wavefront gets which keys of that part is decided at run time, so the
  * floating-point sums are taken in an order that varies from launch to launch and outputs can

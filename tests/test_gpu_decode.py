@@ -105,6 +105,49 @@ def test_shared_tail_switched_off_gives_the_same_bits_every_time():
     ctx.close()
 
 
+@pytest.mark.parametrize("shape", [(16, 32, 16500), (4, 64, 32768), (4, 32, 32768), (1, 32, 131072)])
+def test_shared_tail_gives_the_fixed_order_result_on_every_one_of_many_launches(shape):
+    """Which wavefront takes which piece of the shared tail differs from launch to launch: a piece dropped or taken
+    twice now and then would show here as one launch in a hundred that is off by more than rounding."""
+    B, Hq, n = shape
+    Hkv = 8
+    cfg = lt.make_config(1, B, Hq, Hkv, 128, 4, 1020, n + 200)
+    ctx = lt.Context(cfg, [0], DEV)
+    ctx.append_kv(0, randn_bf16((B, Hkv, n, 128), 471), randn_bf16((B, Hkv, n, 128), 472))
+    q = randn_bf16((B, Hq, 128), 473, scale=1.5)
+    say("shared tail, 100 launches", shape)
+    ctx.set_shared_tail(False)
+    fixed, fixed_lse = ctx.decode_attn(0, q, want_lse=True)
+    fixed, fixed_lse = fixed.clone(), fixed_lse.clone()
+    assert ctx.decode_plan(0)["tail_begin"] == -1
+    ctx.set_shared_tail(True)
+    worst = torch.zeros((), device=DEV)
+    for _ in range(100):
+        out, lse = ctx.decode_attn(0, q, want_lse=True)
+        worst = torch.maximum(worst, torch.maximum((out - fixed).abs().max(), (lse - fixed_lse).abs().max() * 0.1))
+    import os
+    vector_forced_on_large_group = Hq == 64 and os.environ.get("LT_DECODE_PATH") == "vector"     # then: no tail for 4096-key ranges
+    assert ctx.decode_plan(0)["tail_begin"] > 0 or vector_forced_on_large_group
+    assert worst.item() <= 2e-6, worst.item()
+    # the fused step as well: the appended token is part of the tail's last piece
+    k_new, v_new = randn_bf16((B, Hkv, 128), 474), randn_bf16((B, Hkv, 128), 475)
+    ctx.set_shared_tail(False)
+    outs = []
+    for step in range(60):
+        if step == 30:
+            ctx.set_shared_tail(True)
+        outs.append(ctx.decode_step(0, q, k_new, v_new).clone())
+    # identical new tokens every step: step s with the tail on has s more copies than step 29 had; compare like with like
+    ctx2 = lt.Context(cfg, [0], DEV)
+    ctx2.set_shared_tail(False)
+    ctx2.append_kv(0, randn_bf16((B, Hkv, n, 128), 471), randn_bf16((B, Hkv, n, 128), 472))
+    for step in range(60):
+        ref = ctx2.decode_step(0, q, k_new, v_new)
+        assert (ref - outs[step]).abs().max().item() <= 2e-6, step
+    ctx.close()
+    ctx2.close()
+
+
 def test_decode_plan_names_the_kernel_and_the_ranges_of_the_last_launch():
     import os
     forced = os.environ.get("LT_DECODE_PATH", "auto")        # the forced-kernel runs of this file set it
