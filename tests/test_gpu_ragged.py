@@ -115,6 +115,13 @@ def test_ragged_batch_with_a_shared_tail():
     run_ragged(lengths, Hq=16, Hkv=8, ws=4, wr=1020, steps=3, seed=77)
 
 
+@pytest.mark.parametrize("Hq", [32, 64])
+def test_ragged_batch_with_a_shared_tail_over_eight_ranges(Hq):
+    # eight workgroups per (sequence, KV head) with ranges of about 4096 keys leave the last eighth (keys 28672..)
+    # to a shared tail, on the vector kernel (four heads per group) and on the matrix-core kernel (eight)
+    run_ragged([32780, 20000, 28673, 28672], Hq=Hq, Hkv=8, ws=4, wr=1020, steps=2, seed=78)
+
+
 def test_sequence_without_tokens_gives_zero():
     cfg = lt.make_config(1, 2, 4, 1, 128, 4, 28, 64)
     ctx = lt.Context(cfg, [0], DEV)
