@@ -127,6 +127,7 @@ struct PrefillArgs {
     int32_t streaming, w_sink, w_recent;
     int32_t out_f32;
     float scale_log2e;
+    int32_t kv_share;                  // set by prefill_attn: workgroups' head groups per KV head (see there), 1 normally
 };
 hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream);
 

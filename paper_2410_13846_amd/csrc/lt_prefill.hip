@@ -195,8 +195,9 @@ __global__ __launch_bounds__(64 * G * QB) void lt_prefill_attn_kernel(PrefillArg
     const int n_tiles = n_a + (t_last + 1 - t_b);
     auto tile_key = [&](int i) { return (i < n_a ? i : t_b + (i - n_a)) * kTileKeys; };
 
-    const uint16_t *kb = a.k + (int64_t)b * a.kv_stride_b + (int64_t)g * a.kv_stride_h;
-    const uint16_t *vb = a.v + (int64_t)b * a.kv_stride_b + (int64_t)g * a.kv_stride_h;
+    // g counts head groups of G query heads; kv_share of them read the same KV head
+    const uint16_t *kb = a.k + (int64_t)b * a.kv_stride_b + (int64_t)(g / a.kv_share) * a.kv_stride_h;
+    const uint16_t *vb = a.v + (int64_t)b * a.kv_stride_b + (int64_t)(g / a.kv_share) * a.kv_stride_h;
 
     // Q^T fragments (B operand of S^T = K Q^T): for its query column a lane holds dims 16 s + 8 half .. + 7
     bf16x8_t qf[NT][8];
@@ -451,8 +452,16 @@ hipError_t launch_prefill(const PrefillArgs &a, hipStream_t stream)
 
 // Up to twelve wavefronts per workgroup (three per SIMD, 168 registers each), so that one's matrix
 // instructions overlap the others' exponentials; each takes 32 queries.
-hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream)
+hipError_t prefill_attn(const PrefillArgs &args, hipStream_t stream)
 {
+    PrefillArgs a = args;
+    a.kv_share = 1;
+    // Eight heads per KV head would be eight wavefronts, two per SIMD; as two groups of four heads with three query
+    // sub-blocks each they are twelve, and the two groups' workgroups read the same K/V tiles (from the L2, mostly).
+    if (a.n_q_heads / a.n_kv_heads == 8) {
+        a.kv_share = 2;
+        a.n_kv_heads *= 2;
+    }
     switch (a.n_q_heads / a.n_kv_heads) {
     case 1: return launch_prefill<1, 12, 1>(a, stream);
     case 2: return launch_prefill<2, 6, 1>(a, stream);
@@ -461,7 +470,6 @@ hipError_t prefill_attn(const PrefillArgs &a, hipStream_t stream)
     case 5: return launch_prefill<5, 2, 1>(a, stream);
     case 6: return launch_prefill<6, 2, 1>(a, stream);
     case 7: return launch_prefill<7, 1, 1>(a, stream);
-    case 8: return launch_prefill<8, 1, 1>(a, stream);
     default: return hipErrorInvalidValue;
     }
 }
