@@ -968,11 +968,14 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     a.tail_begin = INT32_MAX;
     // Which kernel.  The vector kernel's instruction count per key grows with the heads of a group: from six heads
     // on it, not the memory, bounds a long range (eight heads: 4.3 TB/s against 6.4 for the matrix-core kernel,
-    // whose cost does not depend on the group), and over short ranges it bounds the end of every launch.  The
-    // matrix-core kernel works on pairs of tiles, so it needs more than one tile per wavefront to pay.
+    // whose cost does not depend on the group), and over short ranges it bounds the end of every launch from four
+    // heads on (2048 entries, batch 8: 17.0 / 17.6 / 18.2 / 20.6 us for one to four heads against 18.9-19.7 us for
+    // the matrix-core kernel with any group).  The matrix-core kernel works on pairs of tiles, so it needs more than
+    // one tile per wavefront to pay.
     {
         const int group = c.n_q_heads / c.n_kv_heads;
-        const bool pays = a.keys_per_block > 16 * 8 && (a.keys_per_block <= ltk::kWideBlockKeys || group >= 6);
+        const bool short_ranges = a.keys_per_block <= ltk::kWideBlockKeys && group >= 4;
+        const bool pays = a.keys_per_block > 16 * 8 && (short_ranges || group >= 6);
         a.matrix_cores = ctx->decode_path == LT_DECODE_MATRIX || (ctx->decode_path == LT_DECODE_AUTO && pays) ? 1 : 0;
     }
     // Long ranges leave their last part to the shared tail (see DecodeArgs::tail_begin), which evens out the

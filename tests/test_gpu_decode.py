@@ -154,7 +154,8 @@ def test_decode_plan_names_the_kernel_and_the_ranges_of_the_last_launch():
     # (batch, query heads, keys) -> matrix-core kernel by the library's own rule, shared tail
     cases = [((4, 64, 32768), True, True),                    # eight heads per group: long ranges too, an eighth shared
              ((4, 32, 32768), False, True),                   # four heads per group, ranges of 4096 keys: vector kernel
-             ((8, 32, 4000), True, False),                    # ranges of at most 2048 keys
+             ((8, 32, 4000), True, False),                    # ranges of at most 2048 keys, four heads per group
+             ((8, 4, 4000), False, False),                    # the same with two heads per group: vector kernel
              ((1, 8, 100), True, False)]                      # the smallest range the library chooses has 256 keys
     for (B, Hq, n), matrix, tail in cases:
         Hkv = 8 if Hq >= 32 else 2

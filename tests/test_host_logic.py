@@ -365,6 +365,15 @@ def test_shared_tail_only_for_long_ranges_and_can_be_switched_off():
     assert lib.lt_decode_plan_read(c.h, 0, plan) == lt.ERR_INVALID_ARG and list(plan) == [7, 7, 7, 7]     # layer 0 has not run
     assert lib.lt_decode_plan_read(c.h, 1, plan) == lt.OK and plan[1] >= 1 and plan[2] == -1
     c.close()
+    # short ranges (at most 2048 keys per workgroup) go to the matrix-core kernel from four heads per group on
+    for group in (1, 2, 3, 4, 5, 8):
+        cfg = lt.make_config(1, 8, 8 * group, 8, 128, 4, 2044, 5000)
+        c = Ctx(lib, cfg, [0])
+        assert c.append(0, 4000) == lt.OK and c.step(0) == lt.OK
+        plan = (ctypes.c_int32 * 4)()
+        assert lib.lt_decode_plan_read(c.h, 0, plan) == lt.OK
+        assert 128 < plan[0] <= 2048 and plan[3] == (1 if group >= 4 else 0), (group, list(plan))
+        c.close()
     # one workgroup per (sequence, KV head): nothing to share a tail between
     cfg = lt.make_config(1, 32, 32, 8, 128, 4, 2044, 17000)
     c = Ctx(lib, cfg, [0])
