@@ -72,6 +72,9 @@ WORKLOADS = {
     "llama31_8b_128k_b16": Workload("llama31_8b_128k_b16", 4, 32, 16, 32, 8, 128, 131072, 4, 4092, 16, 32, bias="planted"),
     # a group of eight query heads per KV head (Llama-3-70B-shaped attention): not one of the benchmark's
     # configurations, but the shape where the decode kernels differ most
+    # multi-head attention (one query head per KV head, LLaMA2-7B-shaped stack at its 4K context, the paper's default
+    # 4 + 1020 window): the other end of the group sizes the paper's models have (1, 4, 5, 8)
+    "llama2_7b_4k": Workload("llama2_7b_4k", 6, 32, 32, 32, 32, 128, 4096, 4, 1020, 16, 64, bias="planted"),
     "llama3_70b_32k": Workload("llama3_70b_32k", 5, 80, 4, 64, 8, 128, 32768, 4, 2044, 40, 64, bias="planted"),
 }
 

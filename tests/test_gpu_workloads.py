@@ -147,6 +147,17 @@ def test_llama3_8b_32k_shapes_sampled():
                 score_samples=[(0, 2, 1), (1, 6, 7)])
 
 
+def test_llama2_7b_4k_shapes_sampled():
+    """Batch 32, 32/32 heads (multi-head attention: 1024 (sequence, KV head) pairs, one workgroup each), context 4096,
+    4 + 1020 window."""
+    wl = W.WORKLOADS["llama2_7b_4k"]
+    lazy_layers = W.planted_lazy_layers(wl)
+    full_layers = [l for l in range(wl.n_layers) if l not in lazy_layers]
+    layers = [full_layers[0], lazy_layers[0], full_layers[-1], lazy_layers[-1]]
+    run_sampled(wl, layers, [0, 1, 0, 1], samples=[(0, 0), (1, 31), (2, 17), (3, 5)], steps=3,
+                score_samples=[(0, 2, 1), (1, 30, 31)])
+
+
 def test_llama3_70b_32k_shapes_sampled():
     """Batch 4, 64/8 heads (eight query heads per KV head: the matrix-core decode kernel on the full layers too, the
     scoring kernel's sixteen-tile form), context 32768, 4 + 2044 window."""
