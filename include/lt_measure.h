@@ -35,8 +35,8 @@ lt_status lt_set_shared_tail(lt_ctx *ctx, int32_t on);
 /* Which kernel lt_decode_attn / lt_decode_step launch.  Two kernels compute the same attention: one forms q.k and
  * p.v with vector instructions (dot products and FMAs, probabilities in fp32), the other on the matrix cores
  * (probabilities as two bf16 terms, fp32 accumulation).  LT_DECODE_AUTO (the default) takes the matrix-core one for
- * key ranges of 129..2048 keys per workgroup with four or more query heads per KV head and, with six or more, for
- * every longer range.  The other two values force a kernel, for tests and comparisons. */
+ * key ranges of 129..2048 keys per workgroup with four or five query heads per KV head and, with six or more, for
+ * every range.  The other two values force a kernel, for tests and comparisons. */
 enum { LT_DECODE_AUTO = 0, LT_DECODE_VECTOR = 1, LT_DECODE_MATRIX = 2 };
 lt_status lt_set_decode_path(lt_ctx *ctx, int32_t path);
 

@@ -159,10 +159,13 @@ lt_status assign_full_slot(lt_ctx *ctx, Layer &l)
 // range: 256 workgroups reach 6.6 TB/s where 512 or 768 reach 6.1-6.2 TB/s.  So each of the
 // `streams` = B * Hkv key streams is cut into 256 / streams ranges; more streams than compute
 // units means one range per stream.  Short ranges are not cut below `lo` keys.
-int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t splits_cap)
+int choose_keys_per_block(int64_t stored, int64_t streams, bool lazy, int64_t splits_cap, int group)
 {
     constexpr int64_t workgroups = 256;                        // one per compute unit
-    const int64_t lo = lazy ? 128 : 256;
+    // a window of 2048 entries at batch 1 (eight streams): 32 ranges of 64 keys are 3-7 % faster than 16 of 128 with
+    // up to five heads per group (8.7 / 9.4 / 9.8 / 11.6 against 9.0 / 9.9 / 10.5 / 12.1 us for 1 / 2 / 4 / 5 heads),
+    // and slower with eight
+    const int64_t lo = lazy ? (group <= 5 ? kMinKeysLazy : 2 * kMinKeysLazy) : kMinKeysFull;
     const int64_t splits = std::max<int64_t>(workgroups / streams, 1);
     int64_t keys = ceil_div(ceil_div(stored, splits), ltk::kKeyGranule) * ltk::kKeyGranule;
     keys = std::max(keys, lo);
@@ -959,7 +962,7 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     a.n_kv_heads = c.n_kv_heads;
     a.stored = (int32_t)stored;
     const int32_t forced = l.lazy ? ctx->keys_lazy : ctx->keys_full;
-    a.keys_per_block = forced > 0 ? forced : choose_keys_per_block(stored, (int64_t)c.batch * c.n_kv_heads, l.lazy, ctx->splits_cap);
+    a.keys_per_block = forced > 0 ? forced : choose_keys_per_block(stored, (int64_t)c.batch * c.n_kv_heads, l.lazy, ctx->splits_cap, c.n_q_heads / c.n_kv_heads);
     if (paged) {                                // a workgroup's range may touch at most kMaxRangePages pages
         const int64_t most = ((int64_t)(ltk::kMaxRangePages - 1) << ctx->page_shift) / ltk::kKeyGranule * ltk::kKeyGranule;
         a.keys_per_block = (int32_t)std::min<int64_t>(a.keys_per_block, most);
@@ -970,12 +973,13 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     // on it, not the memory, bounds a long range (eight heads: 4.3 TB/s against 6.4 for the matrix-core kernel,
     // whose cost does not depend on the group), and over short ranges it bounds the end of every launch from four
     // heads on (2048 entries, batch 8: 17.0 / 17.6 / 18.2 / 20.6 us for one to four heads against 18.9-19.7 us for
-    // the matrix-core kernel with any group).  The matrix-core kernel works on pairs of tiles, so it needs more than
-    // one tile per wavefront to pay.
+    // the matrix-core kernel with any group).  The matrix-core kernel works on pairs of tiles, so with four or five
+    // heads it needs more than one tile per wavefront to pay; with six or more it pays everywhere (a window of 2048
+    // entries at batch 1, ranges of 128 keys, eight heads: 13.1 against 15.2 us).
     {
         const int group = c.n_q_heads / c.n_kv_heads;
-        const bool short_ranges = a.keys_per_block <= ltk::kWideBlockKeys && group >= 4;
-        const bool pays = a.keys_per_block > 16 * 8 && (short_ranges || group >= 6);
+        const bool short_ranges = a.keys_per_block > 16 * 8 && a.keys_per_block <= ltk::kWideBlockKeys && group >= 4;
+        const bool pays = short_ranges || group >= 6;
         a.matrix_cores = ctx->decode_path == LT_DECODE_MATRIX || (ctx->decode_path == LT_DECODE_AUTO && pays) ? 1 : 0;
     }
     // Long ranges leave their last part to the shared tail (see DecodeArgs::tail_begin), which evens out the
@@ -994,7 +998,7 @@ static lt_status launch_decode(lt_ctx *ctx, int32_t layer, const void *q, const 
     if (ctx->shared_tail && forced <= 0 && !paged && a.n_splits > 1 && (long_ranges || many_ranges || some_ranges)) {
         const int64_t streams = (int64_t)c.batch * c.n_kv_heads;
         const int64_t begin = (stored - stored / (many_ranges && !long_ranges ? 4 : 8)) / ltk::kKeyGranule * ltk::kKeyGranule;
-        const int32_t keys = choose_keys_per_block(begin, streams, l.lazy, ctx->splits_cap);
+        const int32_t keys = choose_keys_per_block(begin, streams, l.lazy, ctx->splits_cap, c.n_q_heads / c.n_kv_heads);
         if (ceil_div(begin, keys) > 1) {
             a.tail_begin = (int32_t)begin;
             a.keys_per_block = keys;

@@ -374,6 +374,16 @@ def test_shared_tail_only_for_long_ranges_and_can_be_switched_off():
         assert lib.lt_decode_plan_read(c.h, 0, plan) == lt.OK
         assert 128 < plan[0] <= 2048 and plan[3] == (1 if group >= 4 else 0), (group, list(plan))
         c.close()
+    # a lazy layer at batch 1 (eight streams, a window of 2048 entries): 32 ranges of 64 keys on the vector kernel with up
+    # to five heads per group, 16 ranges of 128 keys on the matrix-core kernel with six or more
+    for group, keys, matrix in ((1, 64, 0), (4, 64, 0), (5, 64, 0), (6, 128, 1), (8, 128, 1)):
+        cfg = lt.make_config(1, 1, 8 * group, 8, 128, 4, 2044, 5000)
+        c = Ctx(lib, cfg, [1])
+        assert c.append(0, 4000) == lt.OK and c.step(0) == lt.OK
+        plan = (ctypes.c_int32 * 4)()
+        assert lib.lt_decode_plan_read(c.h, 0, plan) == lt.OK
+        assert list(plan) == [keys, 2048 // keys, -1, matrix], (group, list(plan))
+        c.close()
     # one workgroup per (sequence, KV head): nothing to share a tail between
     cfg = lt.make_config(1, 32, 32, 8, 128, 4, 2044, 17000)
     c = Ctx(lib, cfg, [0])
