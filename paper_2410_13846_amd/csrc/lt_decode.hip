@@ -1041,16 +1041,14 @@ template <int G, int LAZY_TAG, int kMode>
 hipError_t launch_decode_as(const DecodeArgs &a, const typename ModeArgs<kMode>::type &r, hipStream_t stream)
 {
     const dim3 grid(a.n_splits, a.n_kv_heads, a.batch);
-    // short ranges: eight wavefronts per workgroup; not for groups of eight heads, whose state needs more than
-    // the 256 registers a wavefront has when two share a SIMD
-    {
-        if (a.matrix_cores) {
-            // as in the vector kernel: eight wavefronts for short ranges, four for long ones
-            if (a.keys_per_block <= kWideBlockKeys) hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);
-            else hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 4, kMode>), grid, dim3(256), 0, stream, a, r);
-            return hipGetLastError();
-        }
+    // either kernel: eight wavefronts per workgroup for short ranges, four for long ones
+    if (a.matrix_cores) {
+        if (a.keys_per_block <= kWideBlockKeys) hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);
+        else hipLaunchKernelGGL((lt_decode_mfma_kernel<G, LAZY_TAG, 4, kMode>), grid, dim3(256), 0, stream, a, r);
+        return hipGetLastError();
     }
+    // the vector kernel with groups of eight heads always has four: its state needs more than the 256 registers a
+    // wavefront has when two share a SIMD
     if constexpr (G < 8) {
         if (a.keys_per_block <= kWideBlockKeys) {
             hipLaunchKernelGGL((lt_decode_kernel<G, LAZY_TAG, 8, kMode>), grid, dim3(512), 0, stream, a, r);

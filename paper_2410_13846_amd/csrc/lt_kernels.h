@@ -67,7 +67,7 @@ struct DecodeArgs {
     // (sequence, KV head) take them in pieces of kTailKeys, first come first served, once their own tiles are done.
     // The n_splits ranges of keys_per_block keys then cover [0, tail_begin).  INT32_MAX: no shared tail.
     int32_t tail_begin;
-    int32_t matrix_cores;              // the kernel that forms both products on the matrix cores (not for paged layers)
+    int32_t matrix_cores;              // 1: the kernel that forms both products on the matrix cores; 0: the vector kernel
 };
 // ragged batches: per-sequence stored entries (<= stored, which sizes the grid) and new-token slots (-1: dropped);
 // a separate argument block, so that launches for equal-length batches do not carry it
