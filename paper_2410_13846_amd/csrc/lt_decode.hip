@@ -635,7 +635,7 @@ __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, ty
         for (int e = 0; e < 8; ++e) st.acc[h][e] = 0.f;
     }
 
-    // Wavefront w takes every fourth tile; two tile buffers alternate so the loads of the next
+    // Wavefront w takes every kWaves-th tile; two tile buffers alternate so the loads of the next
     // tile are in flight while the current one is consumed.  Every fetch is unconditional (past
     // its last tile a wavefront re-fetches tiles it never consumes): with a fixed number of loads
     // between a fetch and its use the wait counts are exact, and a tile is consumed while the
