@@ -567,7 +567,6 @@ template <int G, int LAZY_TAG, int kWaves, int kMode>
 __global__ __launch_bounds__(64 * kWaves) void lt_decode_kernel(DecodeArgs a, typename ModeArgs<kMode>::type r)
 {
     constexpr bool kRagged = kMode != kUniform, kPaged = kMode == kPagedMode;
-    constexpr int kThreads = 64 * kWaves;
     __shared__ float sh_m[kWaves][G];
     __shared__ float sh_l[kWaves][G];
     __shared__ float sh_acc[kWaves][G][kHeadDim];

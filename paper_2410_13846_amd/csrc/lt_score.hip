@@ -35,9 +35,6 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float floatx16_t;
 typedef __attribute__((__vector_size__(4 * sizeof(uint32_t)))) uint32_t u32x4_t;   // 16 bytes moved as one register quad
 
-constexpr int kRowPad = 8;                                  // bf16 elements of padding per key row in LDS
-constexpr int kRowElems = kHeadDim + kRowPad;               // 272-byte rows: 16-byte reads of 8 rows hit 8 bank groups
-
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
 struct LaneState {
@@ -45,9 +42,6 @@ struct LaneState {
 };
 
 // Uniform description of a 32-key sub-tile relative to the masks.
-// s_waitcnt immediate for gfx9: vmcnt = 0 (bits 3:0 and 15:14), expcnt and lgkmcnt left at their maxima
-constexpr int kWaitVmcnt0 = 0x0F70;
-
 struct TileClass {
     bool fast;      // every (key, query) pair is causal and the kept/dropped decision is the same for all pairs
     bool kept;      // on the fast path: all pairs are kept
