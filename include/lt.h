@@ -22,7 +22,7 @@
  *   are given; fp32 outputs are dense.  head_dim must be 128.  A layer keeps one token count per
  *   batch while every call adds the same number of tokens to every sequence; lt_append_kv_ragged,
  *   lt_reset_sequence, lt_decode_step_active and paged contexts switch a layer to one count per
- *   sequence (batch <= 64 then).
+ *   sequence (batch <= 128 then).
  *   Errors: every call validates its arguments and the state it needs on the host, before it
  *   enqueues the work it was asked for, and returns a status; on any status other than LT_OK no
  *   token was appended, no token count changed and no cache byte was written.  Two things may
@@ -278,7 +278,7 @@ lt_status lt_append_kv(lt_ctx *ctx, int32_t layer, const void *k_new, const void
  *   k_new, v_new     device, bf16 [B][Hkv][n_max][128]; rows past a sequence's count are not read
  *   n_per_seq_host   host, int64 [B]
  * The per-sequence counts travel to the kernels as launch arguments: nothing is allocated or copied.
- * LT_ERR_SHAPE if batch > 64; LT_ERR_STATE on a context made by lt_create_online; LT_ERR_CAPACITY
+ * LT_ERR_SHAPE if batch > 128; LT_ERR_STATE on a context made by lt_create_online; LT_ERR_CAPACITY
  * if the longest sequence would exceed max_tokens. */
 lt_status lt_append_kv_ragged(lt_ctx *ctx, int32_t layer, const void *k_new, const void *v_new, int64_t n_max,
                               const int64_t *n_per_seq_host, void *stream);
@@ -289,7 +289,7 @@ lt_status lt_seq_len(const lt_ctx *ctx, int32_t layer, int32_t sequence, int64_t
 
 /* Forget the tokens of one sequence in every layer (host counters only): the slot is free for a new
  * prompt, brought by lt_append_kv_ragged with a count of 0 for the other sequences.  Turns the
- * context into the per-sequence mode of lt_append_kv_ragged.  LT_ERR_SHAPE if batch > 64;
+ * context into the per-sequence mode of lt_append_kv_ragged.  LT_ERR_SHAPE if batch > 128;
  * LT_ERR_STATE on a context made by lt_create_online. */
 lt_status lt_reset_sequence(lt_ctx *ctx, int32_t sequence);
 
@@ -308,9 +308,9 @@ lt_status lt_reset_sequence(lt_ctx *ctx, int32_t sequence);
  * as on a context from lt_create, except lt_truncate_layer (LT_ERR_STATE), and lt_layer_view, whose
  * strides for a full layer are those inside one page (stride_b = the stride between pages).
  *
- * page_tokens: a power of two, 64 <= page_tokens <= 2^20.  batch <= 64.
+ * page_tokens: a power of two, 64 <= page_tokens <= 2^20.  batch <= 128.
  * lt_kv_bytes_paged: bytes of the slab (table + pools + rings); 0 on invalid arguments.
- * lt_create_paged: LT_ERR_SHAPE if page_tokens is no such power of two, batch > 64, or max_tokens
+ * lt_create_paged: LT_ERR_SHAPE if page_tokens is no such power of two, batch > 128, or max_tokens
  * exceeds what the split decode kernel covers with pages this small (255 pages per workgroup). */
 size_t lt_kv_bytes_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages);
 lt_status lt_create_paged(const lt_config *cfg, const uint8_t *is_lazy, int32_t page_tokens, int32_t n_pages,
@@ -355,7 +355,7 @@ lt_status lt_decode_step(lt_ctx *ctx, int32_t layer, const void *q, const void *
 /* lt_decode_step for the sequences that are still generating (serving: others have finished or their
  * slot is empty).  active_host: host, uint8 [B], non-zero = takes part.  A sequence that sits the step out
  * gets no token, keeps its length, is not read at all, and its rows of out / lse_out are 0 / -inf.  Turns
- * the context into the per-sequence mode of lt_append_kv_ragged.  LT_ERR_SHAPE if batch > 64; LT_ERR_STATE on
+ * the context into the per-sequence mode of lt_append_kv_ragged.  LT_ERR_SHAPE if batch > 128; LT_ERR_STATE on
  * a context made by lt_create_online, and when no active sequence has anything to attend over;
  * LT_ERR_CAPACITY / (paged) LT_ERR_STATE look at the active sequences only. */
 lt_status lt_decode_step_active(lt_ctx *ctx, int32_t layer, const void *q, const void *k_new, const void *v_new,

@@ -16,7 +16,7 @@ constexpr int kMaxSplits = 512;        // most key ranges one (sequence, KV head
 constexpr int kTicketStride = 64;      // uint32 slots between tickets: one per 256 bytes, so they spread over memory channels;
                                        // slot 1 after a ticket counts the pieces handed out of the shared tail
 constexpr int kTailKeys = 32;          // keys per piece of the shared tail (two tiles)
-constexpr int kMaxRaggedBatch = 64;    // sequences a launch can give their own lengths (the lengths travel as kernel arguments)
+constexpr int kMaxRaggedBatch = 128;   // sequences a launch can give their own lengths (the lengths travel as kernel arguments: 2 KB of the 4 KB there are)
 constexpr int kScoreTileKeys = 128;    // key ranges of the scoring kernel are multiples of this
 
 struct AppendArgs {

@@ -108,6 +108,12 @@ def test_ragged_batch_of_sixteen_groups_of_five():
     run_ragged(lengths, Hq=5, Hkv=1, ws=4, wr=124, steps=2, seed=8400)
 
 
+def test_ragged_batch_of_128_sequences():
+    """The most sequences a ragged launch can carry lengths for."""
+    lengths = [(53 * i * i + 7 * i) % 700 for i in range(128)]      # includes empty sequences
+    run_ragged(lengths, Hq=4, Hkv=1, ws=4, wr=124, steps=2, seed=8450)
+
+
 def test_ragged_batch_with_a_shared_tail():
     # two workgroups per (sequence, KV head) with ranges above 8192 keys: the launch leaves keys 14336.. to a shared
     # tail; sequences that end before it, inside it and at its first keys all take part in the same launch

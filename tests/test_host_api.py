@@ -264,9 +264,9 @@ def test_ragged_and_output_dtype_argument_validation():
     assert lib.lt_set_output_dtype(h, lt.OUT_BF16) == lt.OK
     assert lib.lt_set_output_dtype(None, lt.OUT_BF16) == lt.ERR_INVALID_ARG
     lib.lt_destroy(h)
-    wide = lt.make_config(1, 65, 4, 2, 128, 4, 60, 100)              # ragged lengths travel as launch arguments: at most 64 sequences
+    wide = lt.make_config(1, 129, 4, 2, 128, 4, 60, 100)             # ragged lengths travel as launch arguments: at most 128 sequences
     hw = make_ctx(wide, [0])
-    many = (ctypes.c_int64 * 65)(*([1] * 65))
+    many = (ctypes.c_int64 * 129)(*([1] * 129))
     assert lib.lt_append_kv_ragged(hw, 0, FAKE_DEV, FAKE_DEV, 1, many, None) == lt.ERR_SHAPE
     lib.lt_destroy(hw)
     del counts
@@ -399,7 +399,7 @@ def test_paged_context_sizes_and_argument_validation():
     for bad_page in (0, 32, 96, 1 << 21):
         assert lt.kv_bytes_paged(c, mask, bad_page, n_pages) == 0
     assert lt.kv_bytes_paged(c, mask, page, 0) == 0
-    assert lt.kv_bytes_paged(cfg(batch=65), mask, page, n_pages) == 0
+    assert lt.kv_bytes_paged(cfg(batch=129), mask, page, n_pages) == 0
 
     def create(conf, pg, npg, kvb=None):
         handle = ctypes.c_void_p()
@@ -492,8 +492,8 @@ def test_decode_step_active_argument_validation():
                                 lt.workspace_bytes(c), ctypes.byref(online)) == lt.OK
     assert lib.lt_decode_step_active(online, 0, FAKE_DEV, FAKE_DEV, FAKE_DEV, flags, FAKE_DEV, None, None) == lt.ERR_STATE
     lib.lt_destroy(online)
-    wide = lt.make_config(1, 65, 4, 2, 128, 4, 60, 100)
+    wide = lt.make_config(1, 129, 4, 2, 128, 4, 60, 100)
     hw = make_ctx(wide, [0])
-    many = (ctypes.c_uint8 * 65)(*([1] * 65))
+    many = (ctypes.c_uint8 * 129)(*([1] * 129))
     assert lib.lt_decode_step_active(hw, 0, FAKE_DEV, FAKE_DEV, FAKE_DEV, many, FAKE_DEV, None, None) == lt.ERR_SHAPE
     lib.lt_destroy(hw)

@@ -221,9 +221,15 @@ def test_per_sequence_lengths_reach_the_kernel_and_inactive_sequences_look_empty
     assert c.append_ragged(0, 60, [60, 0, 0, 0]) == lt.ERR_CAPACITY
     assert c.seq_len(0, 0) == (5, 5)
     c.close()
-    big = lt.make_config(1, 65, 4, 2, 128, 2, 6, 50)                  # the lengths travel as launch arguments: 64 at most
+    big = lt.make_config(1, 129, 4, 2, 128, 2, 6, 50)                 # the lengths travel as launch arguments: 128 at most
     c = Ctx(lib, big, [0])
-    assert c.append_ragged(0, 3, [3] * 65) == lt.ERR_SHAPE and lib.lt_reset_sequence(c.h, 0) == lt.ERR_SHAPE
+    assert c.append_ragged(0, 3, [3] * 129) == lt.ERR_SHAPE and lib.lt_reset_sequence(c.h, 0) == lt.ERR_SHAPE
+    c.close()
+    most = lt.make_config(1, 128, 4, 2, 128, 2, 6, 50)
+    c = Ctx(lib, most, [0])
+    assert c.append_ragged(0, 3, [3] * 127 + [1]) == lt.OK and c.step(0) == lt.OK
+    stored_b, slot_b = last_lengths(lib, 128)
+    assert stored_b == [4] * 127 + [2] and slot_b == [3] * 127 + [1]
     c.close()
 
 
