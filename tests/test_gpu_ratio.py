@@ -41,6 +41,14 @@ def test_every_query_group_size(group):
     check(B=1, Hq=group, Hkv=1, n=700, w=64, ws=4, wr=252, seed=1200 + group)
 
 
+@pytest.mark.parametrize("group", [5, 6])
+@pytest.mark.parametrize("n", [65, 1500, 4133])
+@pytest.mark.parametrize("mode", [lt.RECENT_PER_QUERY, lt.RECENT_FIXED])
+def test_ten_and_twelve_query_tiles_per_kv_head(group, n, mode):
+    """Five and six heads of 64 scored queries: three query tiles per wavefront, two wavefronts sharing the keys."""
+    check(B=2, Hq=2 * group, Hkv=2, n=n, w=64, ws=4, wr=252, seed=1250 + 10 * group + n, mode=mode)
+
+
 @pytest.mark.parametrize("ws,wr", [(0, 252), (2, 508), (4, 1020), (6, 2044), (4, 0), (0, 1), (40, 70)])
 @pytest.mark.parametrize("mode", [lt.RECENT_PER_QUERY, lt.RECENT_FIXED])
 def test_window_shapes_and_both_readings_of_recent(ws, wr, mode):
